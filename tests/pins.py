@@ -1,0 +1,319 @@
+"""Pins for the CPU oracle: checks whose expected values come from hand-written
+fixtures, library routines or mathematics, never from the oracle itself.
+
+Every function takes the oracle as an argument (a module-like object with
+``check_one``, ``check_batch``, ``fitness`` and the flag constants), so that the same
+pins can be pointed at deliberately broken copies of it (test_oracle_mutants.py).
+Each raises AssertionError on a violated pin.
+"""
+import json
+import math
+import os
+
+import numpy as np
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+_F = np.float32
+SPECIAL = {
+    "+0": _F(0.0), "-0": _F(-0.0), "1": _F(1.0), "1+ulp": np.nextafter(_F(1), _F(2)),
+    "-1": _F(-1.0), "FLT_MIN": _F(1.17549435e-38), "DENORM_MIN": _F(1e-45),
+    "FLT_MAX": _F(3.4028234663852886e38), "+Inf": _F(np.inf), "-Inf": _F(-np.inf),
+    "NaN": _F(np.nan),
+}
+
+
+def _num(x):
+    return float(x) if not isinstance(x, str) else float(x)
+
+
+def _arr(xs):
+    return np.array([_num(x) for x in xs], dtype=np.float32)
+
+
+def _same_f32(a, b):
+    a, b = np.float32(a), np.float32(b)
+    return a.tobytes() == b.tobytes()
+
+
+def pin_truth_table(orc):
+    """121 special-value pairs against the hand-written match matrix."""
+    rows = []
+    with open(os.path.join(GOLDEN, "match_truth_table.txt")) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            rows.append(line.split())
+    assert rows[0][0] == "values:"
+    names = rows[0][1:]
+    assert len(names) == 11 and len(rows) == 12
+    for row in rows[1:]:
+        rname, cells = row[0], row[1:]
+        assert len(cells) == 11
+        for cname, cell in zip(names, cells):
+            r = np.array([SPECIAL[rname]], np.float32)
+            c = np.array([SPECIAL[cname]], np.float32)
+            got = orc.check_one(r, c, orc.F32, 0.25, 0.25)
+            want_mismatch = 0 if cell == "M" else 1
+            assert got["n_mismatch"] == want_mismatch, (rname, cname, got)
+            assert got["valid"] == 1 - want_mismatch, (rname, cname, got)
+
+
+def pin_flag_classes(orc):
+    """Flag bits and statistics membership for each pair of value classes."""
+    bit = {"CN": orc.F_CAND_NAN, "CI": orc.F_CAND_INF, "RN": orc.F_REF_NAN,
+           "RI": orc.F_REF_INF, "ND": orc.F_NAN_SITE_DIFF, "ID": orc.F_INF_DIFF}
+    val = {"fin": 2.0, "+inf": np.inf, "-inf": -np.inf, "nan": np.nan}
+    seen = 0
+    with open(os.path.join(GOLDEN, "flag_classes.txt")) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            rcls, ccls, flags, in_stats = line.split()
+            want = 0
+            if flags != "-":
+                for name in flags.split(","):
+                    want |= bit[name]
+            cv = 2.5 if ccls == "fin" else val[ccls]
+            got = orc.check_one(np.array([val[rcls]], np.float32), np.array([cv], np.float32),
+                                orc.F32, 1.0, 1.0)
+            assert got["flags"] == want, (rcls, ccls, got)
+            assert got["n_finite"] == int(in_stats), (rcls, ccls, got)
+            seen += 1
+    assert seen == 16
+
+
+def _load_examples():
+    with open(os.path.join(GOLDEN, "worked_examples.json")) as fh:
+        return json.load(fh)
+
+
+def pin_worked_check_examples(orc):
+    for ex in _load_examples()["check"]:
+        if ex["dtype"] == "bf16":
+            r = np.array(ex["ref_bits"], dtype=np.uint16)
+            c = np.array(ex["cand_bits"], dtype=np.uint16)
+            dt = orc.BF16
+        else:
+            r, c, dt = _arr(ex["ref"]), _arr(ex["cand"]), orc.F32
+        got = orc.check_one(r, c, dt, ex["atol"], ex["rtol"])
+        for key in ("n_mismatch", "n_finite", "valid", "flags"):
+            assert got[key] == ex[key], (ex["name"], key, got)
+        for key in ("max_abs_err", "max_rel_err"):
+            assert _same_f32(got[key], _num(ex[key])), (ex["name"], key, got)
+        for key in ("sum_abs_err", "sum_rel_err"):
+            assert got[key] == _num(ex[key]), (ex["name"], key, got)
+
+
+def pin_worked_fitness_examples(orc):
+    for ex in _load_examples()["fitness"]:
+        got = orc.fitness(np.array(ex["timings"], np.float32),
+                          np.array(ex["baseline"], np.float32),
+                          np.array(ex["valid"], np.uint32))
+        for key in ("median_ms", "mean_ms", "speedup", "fitness"):
+            want = np.array(ex[key], np.float32)
+            assert got[key].tobytes() == want.tobytes(), (ex["name"], key, got[key], want)
+        assert got["best_idx"] == ex["best_idx"], (ex["name"], got)
+        assert got["n_valid"] == ex["n_valid"], (ex["name"], got)
+        assert _same_f32(got["best_speedup"], ex["best_speedup"]), (ex["name"], got)
+        assert _same_f32(got["valid_rate"], ex["valid_rate"]), (ex["name"], got)
+
+
+def _mixed_pair(rng, n):
+    """Reference/candidate pair with close values, far values and special sites."""
+    r = rng.standard_normal(n).astype(np.float32) * np.float32(3)
+    c = (r * (1 + 0.02 * rng.standard_normal(n))).astype(np.float32)
+    far = rng.random(n) < 0.1
+    c[far] = rng.uniform(-10, 10, far.sum()).astype(np.float32)
+    for arr in (r, c):
+        k = max(1, n // 50)
+        arr[rng.integers(0, n, k)] = np.inf
+        arr[rng.integers(0, n, k)] = -np.inf
+        arr[rng.integers(0, n, k)] = np.nan
+        arr[rng.integers(0, n, k)] = 0.0
+        arr[rng.integers(0, n, k)] = np.float32(1e-41)
+    same = rng.random(n) < 0.2
+    c[same] = r[same]
+    return r, c
+
+
+def pin_numpy_isclose(orc):
+    """The mismatch count is the complement of numpy.isclose in binary32."""
+    rng = np.random.default_rng(1234)
+    for n, atol, rtol in ((1, 1e-2, 1e-2), (257, 1e-2, 1e-2), (4099, 0.0, 3e-2),
+                          (4099, 5e-2, 0.0), (1000, 0.0, 0.0)):
+        r, c = _mixed_pair(rng, n)
+        with np.errstate(all="ignore"):
+            close = np.isclose(c, r, rtol=np.float32(rtol), atol=np.float32(atol), equal_nan=False)
+        got = orc.check_one(r, c, orc.F32, atol, rtol)
+        assert got["n_mismatch"] == int((~close).sum()), (n, atol, rtol, got)
+        both = np.isfinite(r) & np.isfinite(c)
+        assert got["n_finite"] == int(both.sum())
+        assert got["n_elems"] == n
+
+
+def pin_sums_and_maxima(orc):
+    """Sums against exact summation (math.fsum), maxima against an element scan
+    written with Python scalars (no shared code path with the C loop)."""
+    rng = np.random.default_rng(99)
+    r, c = _mixed_pair(rng, 3001)
+    got = orc.check_one(r, c, orc.F32, 1e-2, 1e-2)
+    ds, qs = [], []
+    for ri, ci in zip(r, c):
+        if not (np.isfinite(ri) and np.isfinite(ci)):
+            continue
+        d = np.float32(abs(np.float32(ci - ri)))
+        ar = np.float32(abs(ri))
+        q = np.float32(d * np.float32(np.float32(1) / ar)) if ar >= np.float32(1.17549435e-38) else np.float32(0)
+        ds.append(float(d))
+        qs.append(float(q))
+    assert _same_f32(got["max_abs_err"], max(ds))
+    assert _same_f32(got["max_rel_err"], max(qs))
+    for key, terms in (("sum_abs_err", ds), ("sum_rel_err", qs)):
+        exact = math.fsum(terms)
+        assert abs(got[key] - exact) <= 1e-12 * exact, (key, got[key], exact)
+
+
+def pin_invariants(orc):
+    rng = np.random.default_rng(7)
+    r = rng.standard_normal(5000).astype(np.float32)
+    # identical candidate: nothing differs
+    got = orc.check_one(r, r.copy(), orc.F32, 0.0, 0.0)
+    assert got["n_mismatch"] == 0 and got["valid"] == 1 and got["flags"] == 0
+    assert got["max_abs_err"] == 0 and got["max_rel_err"] == 0
+    assert got["sum_abs_err"] == 0 and got["sum_rel_err"] == 0 and got["n_finite"] == 5000
+    # one NaN anywhere makes the candidate invalid, whatever the tolerance
+    c = r.copy()
+    c[1234] = np.nan
+    got = orc.check_one(r, c, orc.F32, 1e30, 1e30)
+    assert got["valid"] == 0 and got["n_mismatch"] == 1
+    assert got["flags"] == orc.F_CAND_NAN | orc.F_NAN_SITE_DIFF
+    # NaN in the reference at the same site does not excuse it
+    r2 = r.copy()
+    r2[1234] = np.nan
+    got = orc.check_one(r2, c, orc.F32, 1e30, 1e30)
+    assert got["valid"] == 0 and got["n_mismatch"] == 1
+    assert got["flags"] == orc.F_CAND_NAN | orc.F_REF_NAN
+    # monotone in each tolerance
+    c = (r + 0.05 * rng.standard_normal(5000)).astype(np.float32)
+    grid = [0.0, 1e-3, 1e-2, 3e-2, 1e-1, 1.0]
+    for fixed in (0.0, 1e-2):
+        prev_a = prev_r = None
+        for t in grid:
+            ma = orc.check_one(r, c, orc.F32, t, fixed)["n_mismatch"]
+            mr = orc.check_one(r, c, orc.F32, fixed, t)["n_mismatch"]
+            assert prev_a is None or ma <= prev_a
+            assert prev_r is None or mr <= prev_r
+            prev_a, prev_r = ma, mr
+    assert orc.check_one(r, c, orc.F32, 0.0, 0.0)["n_mismatch"] > 0
+    assert orc.check_one(r, c, orc.F32, 1.0, 0.0)["n_mismatch"] == 0
+    # candidate order only permutes rows
+    cands = [(r + s * rng.standard_normal(5000)).astype(np.float32) for s in (0, 1e-3, 1e-1)]
+    rows = orc.check_batch(r, cands, orc.F32, 1e-2, 1e-2)
+    rows_rev = orc.check_batch(r, cands[::-1], orc.F32, 1e-2, 1e-2)
+    assert rows == rows_rev[::-1]
+    # chunked feeding equals one pass (sums continue in index order: bit-identical)
+    rr, cc = _mixed_pair(rng, 4001)
+    whole = orc.check_one(rr, cc, orc.F32, 1e-2, 1e-2)
+    acc = orc.CheckAccumulator(orc.F32, 1e-2, 1e-2)
+    for lo, hi in ((0, 1), (1, 1000), (1000, 1000), (1000, 4001)):
+        acc.feed(rr[lo:hi], cc[lo:hi])
+    assert acc.result() == whole
+    # every element is either in the statistics set or has a non-finite side
+    nonfinite = int((~(np.isfinite(rr) & np.isfinite(cc))).sum())
+    assert whole["n_finite"] + nonfinite == 4001
+    # empty tensor
+    e = orc.check_one(np.zeros(0, np.float32), np.zeros(0, np.float32), orc.F32, 0.0, 0.0)
+    assert e["valid"] == 1 and e["n_mismatch"] == 0 and e["n_finite"] == 0
+
+
+def pin_bf16_widening(orc):
+    """bf16 inputs give exactly what the same values give as binary32."""
+    rng = np.random.default_rng(5)
+    bits_r = rng.integers(0, 1 << 16, 20000).astype(np.uint16)
+    bits_c = bits_r.copy()
+    move = rng.random(20000) < 0.5
+    bits_c[move] = (bits_c[move].astype(np.int32) + rng.integers(-3, 4, move.sum())).clip(0, 65535).astype(np.uint16)
+    r32 = (bits_r.astype(np.uint32) << 16).view(np.float32)
+    c32 = (bits_c.astype(np.uint32) << 16).view(np.float32)
+    a = orc.check_one(bits_r, bits_c, orc.BF16, 1e-2, 1e-2)
+    b = orc.check_one(r32, c32, orc.F32, 1e-2, 1e-2)
+    assert a == b and a["flags"] != 0  # random bits include Inf and NaN patterns
+
+
+def _rank_select(row, k):
+    """k-th smallest by counting, O(T^2): no sort involved."""
+    T = len(row)
+    for i in range(T):
+        rank = sum(1 for j in range(T) if row[j] < row[i] or (row[j] == row[i] and j < i))
+        if rank == k:
+            return row[i]
+    raise AssertionError("no element of rank %d" % k)
+
+
+def pin_median_and_speedup(orc):
+    rng = np.random.default_rng(11)
+    for T in (1, 2, 5, 100, 101, 1000):
+        P = 7
+        t = np.exp(0.1 * rng.standard_normal((P, T))).astype(np.float32)
+        t[3] = t[2]                      # duplicate row
+        t[4, : max(1, T // 3)] = t[4, 0]  # many equal samples
+        b = np.exp(0.1 * rng.standard_normal(T)).astype(np.float32)
+        valid = np.array([1, 0, 1, 1, 1, 1, 0], np.uint32)
+        got = orc.fitness(t, b, valid)
+        for p in range(P):
+            row = [np.float32(x) for x in t[p]]
+            if T % 2:
+                want = _rank_select(row, T // 2)
+            else:
+                want = np.float32(0.5) * np.float32(_rank_select(row, T // 2 - 1) + _rank_select(row, T // 2))
+            assert _same_f32(got["median_ms"][p], want), (T, p)
+            assert _same_f32(got["median_ms"][p], np.median(t[p])), (T, p)
+            exact_mean = math.fsum(float(x) for x in t[p]) / T
+            assert abs(float(got["mean_ms"][p]) - exact_mean) <= 2.0 ** -23 * exact_mean
+        bm = np.median(b)
+        assert _same_f32(got["base_median_ms"], bm)
+        for p in range(P):
+            assert _same_f32(got["speedup"][p], np.float32(bm) / got["median_ms"][p])
+            assert _same_f32(got["fitness"][p], got["speedup"][p] if valid[p] else 0.0)
+        assert got["n_valid"] == 5 and _same_f32(got["valid_rate"], np.float32(5) / np.float32(7))
+        fit = got["fitness"]
+        assert got["best_idx"] == int(np.argmax(fit))  # argmax returns the first maximum
+        assert _same_f32(got["best_speedup"], max(np.float32(1), fit.max()))
+    # closed forms: identical rows -> speedup exactly 1; doubling a row halves it
+    row = np.exp(0.1 * rng.standard_normal(100)).astype(np.float32)
+    got = orc.fitness(np.stack([row, row * 2, row[::-1].copy()]), row, np.ones(3, np.uint32))
+    assert got["speedup"].tolist() == [1.0, 0.5, 1.0]
+    assert got["best_idx"] == 0
+    # one huge outlier (the largest sample made 1000x larger) moves the mean, not the median
+    row2 = row.copy()
+    row2[int(np.argmax(row))] *= 1000
+    g1 = orc.fitness(row[None, :], row, np.ones(1, np.uint32))
+    g2 = orc.fitness(row2[None, :], row, np.ones(1, np.uint32))
+    assert _same_f32(g1["median_ms"][0], g2["median_ms"][0])
+    assert g2["mean_ms"][0] > 2 * g1["mean_ms"][0]
+
+
+def pin_unusable_timing_rows(orc):
+    """A row with a NaN, an Inf, a zero or a negative sample has no median."""
+    base = np.array([1, 2, 3, 4], np.float32)
+    rows = np.array([[1, 2, 3, 4], [1, np.nan, 3, 4], [1, 2, np.inf, 4], [0, 2, 3, 4],
+                     [1, 2, 3, -4]], np.float32)
+    got = orc.fitness(rows, base, np.ones(5, np.uint32))
+    qnan = np.array([0x7FC00000], np.uint32).view(np.float32)[0]
+    for p in range(1, 5):
+        assert _same_f32(got["median_ms"][p], qnan) and _same_f32(got["mean_ms"][p], qnan)
+        assert got["speedup"][p] == 0 and got["fitness"][p] == 0
+    assert got["speedup"][0] == 1.0 and got["best_idx"] == 0 and got["n_valid"] == 5
+    bad_base = orc.fitness(rows[:1], np.array([1, 2, 3, np.nan], np.float32), np.ones(1, np.uint32))
+    assert bad_base["speedup"][0] == 0 and bad_base["fitness"][0] == 0 and bad_base["best_idx"] == 1
+    assert bad_base["median_ms"][0] == 2.5
+
+
+ALL_PINS = [
+    pin_truth_table, pin_flag_classes, pin_worked_check_examples, pin_worked_fitness_examples,
+    pin_numpy_isclose, pin_sums_and_maxima, pin_invariants, pin_bf16_widening,
+    pin_median_and_speedup, pin_unusable_timing_rows,
+]
