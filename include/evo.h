@@ -1,0 +1,205 @@
+/*
+ * evo.h -- C ABI of the fitness-and-validity evaluation step of an LLM-driven
+ * kernel-evolution loop, for AMD Instinct MI355X (gfx950).
+ *
+ * Background (EvoEngineer, arXiv 2510.03760).  Sec. 3.1, Eq. 1 states kernel
+ * optimisation as  argmin f(p)  subject to  g(p) = 0 : g holds the validity
+ * constraints (the code compiles; its output matches the reference implementation
+ * across test cases) and f is the performance objective.  Sec. 4.3 describes the
+ * evaluator: functional testing compares candidate outputs with reference outputs,
+ * then execution time is collected over 100 runs.  Sec. 5.1 ("Evaluation Metric")
+ * defines the reported figures: speedup over the baseline kernel, 1.0 when nothing
+ * beats the baseline, and the ratio of valid kernels.  The appendix on threats to
+ * validity reduces repeated timings by their median.
+ *
+ * This library evaluates a whole population at once on one GPU: P candidate output
+ * tensors are checked against one reference output (evo_check_batch), ragged groups
+ * of (reference, candidates) are checked in one launch (evo_check_segmented), and
+ * per-candidate timing samples become a median, a speedup and a fitness
+ * (evo_fitness).  The compiler stage of g and the program generator are not here.
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory of the current device; "host"
+ *     pointers are ordinary process memory.  The library never frees, keeps or
+ *     writes caller memory beyond what each call documents.
+ *   - Tensors are contiguous and are read as flat arrays; their shape plays no
+ *     part in a tolerance check.  EVO_BF16 elements are the upper 16 bits of an
+ *     IEEE-754 binary32, little endian; they are widened exactly and every
+ *     operation is done in binary32.
+ *   - Every call that takes a stream only enqueues work on it and returns; results
+ *     are defined once the caller has synchronised that stream.  `stream` is a
+ *     hipStream_t passed as void* (NULL = the null stream).
+ *   - A context must not be used from two streams or two host threads at once:
+ *     it owns scratch memory that consecutive calls reuse in stream order.
+ *   - All functions return EVO_OK (0) or a negative evo_status.  Argument errors
+ *     are detected on the host before anything is enqueued.  Nothing is printed,
+ *     thrown or aborted.
+ */
+#ifndef EVO_H_
+#define EVO_H_
+
+#include <stdint.h>
+
+#if defined(EVO_BUILDING)
+#define EVO_API __attribute__((visibility("default")))
+#else
+#define EVO_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct evo_check evo_check_t; /* opaque, owned by the library */
+
+typedef enum { EVO_F32 = 0, EVO_BF16 = 1 } evo_dtype;
+
+typedef enum {
+    EVO_OK         = 0,
+    EVO_ERR_NULL   = -1, /* a required pointer is NULL                          */
+    EVO_ERR_DTYPE  = -2, /* unknown element type                                */
+    EVO_ERR_SIZE   = -3, /* zero or out-of-range count (n, P, S, T, rows)       */
+    EVO_ERR_TOL    = -4, /* tolerance negative, NaN or infinite                 */
+    EVO_ERR_ALIGN  = -5, /* a tensor pointer is not aligned to its element size */
+    EVO_ERR_DEVICE = -6, /* a HIP call failed (no device, launch error, ...)    */
+    EVO_ERR_NOMEM  = -7, /* host or device allocation failed                    */
+    EVO_ERR_HANDLE = -8  /* not a live context (never created, or destroyed)    */
+} evo_status;
+
+/* Bits of evo_stats.flags */
+enum {
+    EVO_F_CAND_NAN      = 1u << 0, /* a candidate element is NaN                 */
+    EVO_F_CAND_INF      = 1u << 1, /* a candidate element is +-Inf               */
+    EVO_F_REF_NAN       = 1u << 2, /* a reference element is NaN                 */
+    EVO_F_REF_INF       = 1u << 3, /* a reference element is +-Inf               */
+    EVO_F_NAN_SITE_DIFF = 1u << 4, /* NaN on exactly one side at some index      */
+    EVO_F_INF_DIFF      = 1u << 5  /* an Inf involved, no NaN, and c != r        */
+};
+
+/*
+ * One row per candidate, 72 bytes, 8-byte aligned, in device memory.
+ *
+ * Element rule (reading of "output must match the reference", Sec. 3.1, with the
+ * absolute/relative tolerance of the context; r = reference, c = candidate, all in
+ * binary32 with each operation rounded on its own):
+ *     match  <=>  c == r,  or  both finite and |c - r| <= atol + rtol*|r|
+ * so any NaN, Inf against finite and +Inf against -Inf are mismatches.
+ * Statistics run over elements where both sides are finite: d = |c - r| (kept when
+ * it overflows to +Inf), q = d * (1/|r|) with the reciprocal rounded first and
+ * q = 0 where |r| < FLT_MIN.
+ */
+typedef struct evo_stats {
+    uint64_t n_mismatch;  /* elements failing the rule (exact)                     */
+    uint64_t n_finite;    /* elements with both sides finite (exact)               */
+    double   sum_abs_err; /* sum of d; summation order is unspecified (1e-6 rel.)  */
+    double   sum_rel_err; /* sum of q; summation order is unspecified (1e-6 rel.)  */
+    float    max_abs_err; /* max d, 0 when the set is empty (exact)                */
+    float    max_rel_err; /* max q, 0 when the set is empty (exact)                */
+    uint32_t flags;       /* EVO_F_* bits (exact)                                  */
+    uint32_t valid;       /* 1 iff n_mismatch == 0: the constraint g(p) = 0        */
+    float    median_ms;   /* evo_fitness: median of the T samples                  */
+    float    mean_ms;     /* evo_fitness: mean of the T samples                    */
+    float    speedup;     /* evo_fitness: baseline median / candidate median       */
+    float    fitness;     /* evo_fitness: valid ? speedup : 0                      */
+    uint32_t n_elems_lo;  /* element count of the tensor this row was checked on   */
+    uint32_t n_elems_hi;
+} evo_stats;
+
+/* One ragged group: a reference and the candidates checked against it. */
+typedef struct evo_segment {
+    const void        *ref;        /* device, n_elems elements of `dtype`            */
+    const void *const *cand_ptrs;  /* HOST array of P_s device pointers              */
+    uint64_t           n_elems;    /* > 0                                            */
+    uint32_t           P_s;        /* > 0                                            */
+    uint32_t           dtype;      /* evo_dtype                                      */
+    uint32_t           stats_row0; /* first of the P_s rows this group writes        */
+    uint32_t           reserved;   /* set to 0                                       */
+} evo_segment;
+
+/* Population figures of Sec. 5.1, one per evo_fitness call, in device memory. */
+typedef struct evo_pop_summary {
+    uint32_t best_idx;     /* largest fitness, lowest index on ties; P if all are 0 */
+    uint32_t n_valid;      /* candidates with valid == 1                            */
+    float    best_speedup; /* max(1.0, fitness[best_idx]); 1.0 if none              */
+    float    valid_rate;   /* n_valid / P  (Pass@1 of the functional stage)         */
+} evo_pop_summary;
+
+/*
+ * Creates a context for tensors of `n_elems` elements of `dtype`, checked with the
+ * tolerance |c - r| <= atol + rtol*|r| (Sec. 3.1 constraint; tolerance form is this
+ * library's reading).  atol and rtol must be finite and >= 0; they are used as the
+ * binary32 values given.  Only host work is done here; device scratch memory is
+ * allocated by the first call that needs it, on the device current at that time.
+ * Errors: EVO_ERR_NULL (out), EVO_ERR_DTYPE, EVO_ERR_SIZE (n_elems == 0),
+ * EVO_ERR_TOL, EVO_ERR_NOMEM.  On error *out is set to NULL.
+ */
+EVO_API int evo_check_create(evo_check_t **out, evo_dtype dtype, uint64_t n_elems,
+                     float atol, float rtol);
+
+/*
+ * Functional testing of Sec. 4.3 for a population: checks P candidate tensors
+ * against `ref` (each of the context's n_elems elements and dtype) and overwrites
+ * stats[0..P) completely (timing fields are set to 0).
+ *   ref        device, read only
+ *   cand_ptrs  HOST array of P device pointers, read during the call only
+ *   stats      device, P rows, written by the enqueued work
+ * Each reference element is fetched from memory once and compared with all P
+ * candidates.  Tensor pointers must be aligned to the element size; 16-byte
+ * alignment gives the fast path.
+ * Errors: EVO_ERR_HANDLE, EVO_ERR_NULL (ref, cand_ptrs, any cand_ptrs[i], stats),
+ * EVO_ERR_SIZE (P == 0 or P > 65535), EVO_ERR_ALIGN, EVO_ERR_NOMEM, EVO_ERR_DEVICE.
+ */
+EVO_API int evo_check_batch(evo_check_t *c, const void *ref, const void *const *cand_ptrs,
+                    uint32_t P, void *stream, evo_stats *stats);
+
+/*
+ * The same check over S ragged groups in ONE launch (the test cases and output
+ * shapes of an operation set differ in size, Sec. 4.3 / operation taxonomy in the
+ * appendix).  Group s writes rows [stats_row0, stats_row0 + P_s); row ranges of
+ * different groups must not overlap and must lie inside [0, n_rows).  The
+ * context's tolerances apply; its n_elems and dtype are ignored.
+ *   segs   HOST array of S descriptors (and the host pointer arrays they name),
+ *          read during the call only
+ *   stats  device, n_rows rows; rows not named by any group are left untouched
+ * Errors: as evo_check_batch, plus EVO_ERR_SIZE for S == 0, an empty group, a row
+ * range outside n_rows or overlapping another, and EVO_ERR_DTYPE per group.
+ */
+EVO_API int evo_check_segmented(evo_check_t *c, const evo_segment *segs, uint32_t S,
+                        void *stream, evo_stats *stats, uint32_t n_rows);
+
+/*
+ * Performance objective of Sec. 3.1 with the metric of Sec. 5.1.  For each of the
+ * P candidates: median of its T timing samples (even T: 0.5f*(lo+hi) of the two
+ * middle order statistics), mean (binary64 sum in sample order, divided by T,
+ * rounded once), speedup = median(baseline) / median(candidate) in binary32, and
+ * fitness = stats[p].valid ? speedup : 0.  A row holding a sample that is not
+ * finite and > 0 gets median_ms = mean_ms = quiet NaN (0x7fc00000) and speedup =
+ * fitness = 0; an unusable baseline does that to every speedup.
+ *   timings   device, P*T binary32 milliseconds, row major
+ *   baseline  device, T samples of the baseline kernel
+ *   stats     device, P rows: `valid` is read (as left by an evo_check_* call that
+ *             precedes this one in stream order); median_ms, mean_ms, speedup and
+ *             fitness are written; other fields are untouched
+ *   summary   device, one record, or NULL
+ * Errors: EVO_ERR_HANDLE, EVO_ERR_NULL, EVO_ERR_SIZE (P == 0, T == 0,
+ * T > EVO_FITNESS_MAX_T, P > 1048576), EVO_ERR_ALIGN, EVO_ERR_DEVICE.
+ */
+#define EVO_FITNESS_MAX_T 4096u
+EVO_API int evo_fitness(evo_check_t *c, const float *timings, const float *baseline,
+                uint32_t P, uint32_t T, void *stream, evo_stats *stats,
+                evo_pop_summary *summary);
+
+/*
+ * Destroys a context: waits for the device to go idle, frees the library's scratch
+ * memory.  NULL, unknown and already destroyed handles are ignored
+ * (evo_check_destroy returns EVO_ERR_HANDLE for them and does nothing else).
+ */
+EVO_API int evo_check_destroy(evo_check_t *c);
+
+/* Static, never NULL description of a status code. */
+EVO_API const char *evo_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EVO_H_ */

@@ -1,0 +1,9 @@
+"""MI355X-native fitness-and-validity evaluation step for LLM-driven kernel evolution
+(EvoEngineer, arXiv 2510.03760): a C-ABI HIP library (include/evo.h) and a thin
+binding with the same names.  Importing this package loads the library; it raises if
+the library has not been built (python -m paper_2510_03760_amd.build)."""
+from .binding import (  # noqa: F401
+    EVO_BF16, EVO_F32, EvoError, EvoStats, EvoPopSummary, EvoSegment, STATS_DTYPE,
+    SUMMARY_DTYPE, Checker, evo_check_batch, evo_check_create, evo_check_destroy,
+    evo_check_segmented, evo_fitness, evo_strerror, lib, lib_path,
+)

@@ -1,0 +1,397 @@
+// Host side of the C ABI declared in evo.h: argument validation, job partitioning,
+// descriptor staging and launches.  Everything that is computed about tensors is
+// computed by the kernels; nothing here touches tensor data.
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <set>
+#include <utility>
+#include <vector>
+
+#include "evo_internal.h"
+
+namespace {
+
+using evo::Partial;
+using evo::SegDesc;
+
+// Workgroups the partitioner aims for: a few waves of work per CU slot of a
+// 256-CU part, so that the tail of the launch is short next to its body.
+constexpr uint32_t kTargetJobs = 4096;
+constexpr uint32_t kMinTilesPerWave = 4;
+constexpr uint32_t kMaxP = 65535;
+constexpr int kStageSlots = 8;
+
+struct StageSlot {
+    void *host = nullptr;      // pinned
+    size_t bytes = 0;
+    hipEvent_t done = nullptr; // recorded after the copy that reads `host`
+    bool in_flight = false;
+};
+
+}  // namespace
+
+struct evo_check {
+    evo_dtype dtype;
+    uint64_t n_elems;
+    float atol, rtol;
+    int device = -1;             // device the scratch lives on (-1: none yet)
+    // device scratch
+    void *d_table = nullptr;     // SegDesc[S] followed by the candidate pointer table
+    size_t table_bytes = 0;
+    Partial *d_partials = nullptr;
+    size_t partial_rows = 0;
+    uint32_t *d_tickets = nullptr;   // per segment, self re-arming, + fitness ticket
+    size_t n_tickets = 0;
+    float *d_base_median = nullptr;
+    uint32_t *d_fit_ticket = nullptr;
+    StageSlot slots[kStageSlots];
+    int next_slot = 0;
+};
+
+namespace {
+
+std::mutex g_mu;
+std::set<evo_check *> g_live;
+
+bool is_live(evo_check *c) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    return c != nullptr && g_live.count(c) != 0;
+}
+
+uint32_t elem_size(uint32_t dtype) { return dtype == EVO_BF16 ? 2u : 4u; }
+
+bool dtype_ok(uint32_t dtype) { return dtype == EVO_F32 || dtype == EVO_BF16; }
+
+int dev(hipError_t e) { return e == hipSuccess ? EVO_OK : (e == hipErrorOutOfMemory ? EVO_ERR_NOMEM : EVO_ERR_DEVICE); }
+
+#define EVO_TRY(expr)                       \
+    do {                                    \
+        const int rc_ = dev(expr);          \
+        if (rc_ != EVO_OK) return rc_;      \
+    } while (0)
+
+// Scratch is tied to the device that is current when it is first needed.
+int bind_device(evo_check *c) {
+    int cur = -1;
+    EVO_TRY(hipGetDevice(&cur));
+    if (c->device == -1) c->device = cur;
+    return c->device == cur ? EVO_OK : EVO_ERR_DEVICE;
+}
+
+int ensure_table(evo_check *c, size_t bytes) {
+    if (bytes <= c->table_bytes) return EVO_OK;
+    if (c->d_table) EVO_TRY(hipFree(c->d_table));   // hipFree waits for the device
+    c->d_table = nullptr;
+    c->table_bytes = 0;
+    const size_t cap = std::max<size_t>(bytes * 2, 4096);
+    EVO_TRY(hipMalloc(&c->d_table, cap));
+    c->table_bytes = cap;
+    return EVO_OK;
+}
+
+int ensure_partials(evo_check *c, size_t rows) {
+    if (rows <= c->partial_rows) return EVO_OK;
+    if (c->d_partials) EVO_TRY(hipFree(c->d_partials));
+    c->d_partials = nullptr;
+    c->partial_rows = 0;
+    EVO_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_partials), rows * sizeof(Partial)));
+    c->partial_rows = rows;
+    return EVO_OK;
+}
+
+int ensure_tickets(evo_check *c, size_t n, hipStream_t stream) {
+    if (n <= c->n_tickets) return EVO_OK;
+    if (c->d_tickets) EVO_TRY(hipFree(c->d_tickets));
+    c->d_tickets = nullptr;
+    c->n_tickets = 0;
+    const size_t cap = std::max<size_t>(n * 2, 64);
+    EVO_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_tickets), cap * sizeof(uint32_t)));
+    // counters start at zero and every launch leaves them at zero again
+    EVO_TRY(hipMemsetAsync(c->d_tickets, 0, cap * sizeof(uint32_t), stream));
+    c->n_tickets = cap;
+    return EVO_OK;
+}
+
+int ensure_fitness_scratch(evo_check *c, hipStream_t stream) {
+    if (c->d_base_median) return EVO_OK;
+    void *p = nullptr;
+    EVO_TRY(hipMalloc(&p, 256));
+    EVO_TRY(hipMemsetAsync(p, 0, 256, stream));
+    c->d_base_median = static_cast<float *>(p);
+    c->d_fit_ticket = reinterpret_cast<uint32_t *>(static_cast<char *>(p) + 128);
+    return EVO_OK;
+}
+
+// A pinned staging buffer whose previous upload has completed.
+int acquire_slot(evo_check *c, size_t bytes, StageSlot **out) {
+    StageSlot &s = c->slots[c->next_slot];
+    c->next_slot = (c->next_slot + 1) % kStageSlots;
+    if (s.in_flight) {
+        EVO_TRY(hipEventSynchronize(s.done));
+        s.in_flight = false;
+    }
+    if (!s.done) EVO_TRY(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
+    if (bytes > s.bytes) {
+        if (s.host) EVO_TRY(hipHostFree(s.host));
+        s.host = nullptr;
+        s.bytes = 0;
+        const size_t cap = std::max<size_t>(bytes * 2, 4096);
+        EVO_TRY(hipHostMalloc(&s.host, cap, hipHostMallocDefault));
+        s.bytes = cap;
+    }
+    *out = &s;
+    return EVO_OK;
+}
+
+struct HostSeg {
+    const void *ref;
+    const void *const *cand_ptrs;
+    uint64_t n;
+    uint32_t P, dtype, row0;
+};
+
+// Pure host validation of one group (no device call).
+int validate_seg(const HostSeg &h) {
+    if (!h.ref || !h.cand_ptrs) return EVO_ERR_NULL;
+    if (!dtype_ok(h.dtype)) return EVO_ERR_DTYPE;
+    if (h.n == 0 || h.P == 0 || h.P > kMaxP) return EVO_ERR_SIZE;
+    const uintptr_t am = elem_size(h.dtype) - 1;
+    if (reinterpret_cast<uintptr_t>(h.ref) & am) return EVO_ERR_ALIGN;
+    for (uint32_t p = 0; p < h.P; ++p) {
+        if (!h.cand_ptrs[p]) return EVO_ERR_NULL;
+        if (reinterpret_cast<uintptr_t>(h.cand_ptrs[p]) & am) return EVO_ERR_ALIGN;
+    }
+    return EVO_OK;
+}
+
+uint32_t pow2_ceil(uint32_t v) {
+    uint32_t p = 1;
+    while (p < v) p <<= 1;
+    return p;
+}
+
+// Splits every group into jobs (workgroups) of similar cost.  Cost unit: one
+// wavefront pass over one tile with one candidate group.
+void partition(const std::vector<HostSeg> &segs, std::vector<SegDesc> &descs,
+               uint32_t &total_jobs) {
+    descs.resize(segs.size());
+    uint64_t wave_tiles = 0;
+    for (size_t s = 0; s < segs.size(); ++s) {
+        const HostSeg &h = segs[s];
+        SegDesc &d = descs[s];
+        d.n = h.n;
+        d.P = h.P;
+        d.dtype = h.dtype;
+        d.stats_row0 = h.row0;
+        d.n_groups = (h.P + evo::kG - 1) / evo::kG;
+        d.cpg = (h.P + d.n_groups - 1) / d.n_groups;
+        d.gpw = std::min<uint32_t>(pow2_ceil(d.n_groups), evo::kWaves);
+        const uint64_t tiles = (h.n + evo::tile_elems(h.dtype) - 1) / evo::tile_elems(h.dtype);
+        wave_tiles += tiles * d.n_groups;
+    }
+    // tiles one wavefront should take per job
+    uint64_t per_wave = (wave_tiles + (uint64_t)kTargetJobs * evo::kWaves - 1) /
+                        ((uint64_t)kTargetJobs * evo::kWaves);
+    per_wave = std::max<uint64_t>(per_wave, kMinTilesPerWave);
+    uint32_t job0 = 0;
+    for (size_t s = 0; s < segs.size(); ++s) {
+        SegDesc &d = descs[s];
+        const uint64_t tiles = (d.n + evo::tile_elems(d.dtype) - 1) / evo::tile_elems(d.dtype);
+        const uint32_t tpw = evo::kWaves / d.gpw;
+        uint64_t per_chunk = per_wave * tpw;
+        uint64_t chunks = (tiles + per_chunk - 1) / per_chunk;
+        // keep chunk and job counts inside 32 bits for any n
+        while (chunks > (1u << 20)) {
+            per_chunk *= 2;
+            chunks = (tiles + per_chunk - 1) / per_chunk;
+        }
+        d.tiles_per_chunk = (uint32_t)per_chunk;
+        d.n_chunks = (uint32_t)chunks;
+        const uint32_t gblocks = (d.n_groups + d.gpw - 1) / d.gpw;
+        d.n_jobs = gblocks * d.n_chunks;
+        d.job0 = job0;
+        job0 += d.n_jobs;
+    }
+    total_jobs = job0;
+}
+
+int run_check(evo_check *c, const std::vector<HostSeg> &segs, hipStream_t stream,
+              evo_stats *stats) {
+    int rc = bind_device(c);
+    if (rc != EVO_OK) return rc;
+
+    std::vector<SegDesc> descs;
+    uint32_t total_jobs = 0;
+    size_t total_ptrs = 0;
+    try {
+        partition(segs, descs, total_jobs);
+    } catch (const std::bad_alloc &) {
+        return EVO_ERR_NOMEM;
+    }
+    for (const HostSeg &h : segs) total_ptrs += h.P;
+
+    const size_t S = segs.size();
+    const size_t desc_bytes = S * sizeof(SegDesc);
+    const size_t blob_bytes = desc_bytes + total_ptrs * sizeof(void *);
+
+    if ((rc = ensure_table(c, blob_bytes)) != EVO_OK) return rc;
+    if ((rc = ensure_partials(c, (size_t)total_jobs * evo::kRowsPerJob)) != EVO_OK) return rc;
+    if ((rc = ensure_tickets(c, S, stream)) != EVO_OK) return rc;
+
+    StageSlot *slot = nullptr;
+    if ((rc = acquire_slot(c, blob_bytes, &slot)) != EVO_OK) return rc;
+
+    // blob = descriptors, then all candidate pointers; descriptors point into the
+    // device copy of the pointer part
+    char *hb = static_cast<char *>(slot->host);
+    const void **hptrs = reinterpret_cast<const void **>(hb + desc_bytes);
+    const void *const *dptrs =
+        reinterpret_cast<const void *const *>(static_cast<char *>(c->d_table) + desc_bytes);
+    size_t off = 0;
+    for (size_t s = 0; s < S; ++s) {
+        descs[s].ref = segs[s].ref;
+        descs[s].cands = dptrs + off;
+        for (uint32_t p = 0; p < segs[s].P; ++p) hptrs[off + p] = segs[s].cand_ptrs[p];
+        off += segs[s].P;
+    }
+    std::memcpy(hb, descs.data(), desc_bytes);
+
+    EVO_TRY(hipMemcpyAsync(c->d_table, hb, blob_bytes, hipMemcpyHostToDevice, stream));
+    EVO_TRY(hipEventRecord(slot->done, stream));
+    slot->in_flight = true;
+
+    return dev(evo::launch_check(static_cast<const SegDesc *>(c->d_table), (uint32_t)S,
+                                 total_jobs, c->atol, c->rtol, c->d_partials, c->d_tickets,
+                                 stats, stream));
+}
+
+}  // namespace
+
+extern "C" {
+
+int evo_check_create(evo_check_t **out, evo_dtype dtype, uint64_t n_elems, float atol,
+                     float rtol) {
+    if (!out) return EVO_ERR_NULL;
+    *out = nullptr;
+    if (!dtype_ok((uint32_t)dtype)) return EVO_ERR_DTYPE;
+    if (n_elems == 0) return EVO_ERR_SIZE;
+    if (!(atol >= 0.0f) || !(rtol >= 0.0f) || std::isinf(atol) || std::isinf(rtol))
+        return EVO_ERR_TOL;
+    evo_check *c = new (std::nothrow) evo_check();
+    if (!c) return EVO_ERR_NOMEM;
+    c->dtype = dtype;
+    c->n_elems = n_elems;
+    c->atol = atol;
+    c->rtol = rtol;
+    try {
+        std::lock_guard<std::mutex> lk(g_mu);
+        g_live.insert(c);
+    } catch (const std::bad_alloc &) {
+        delete c;
+        return EVO_ERR_NOMEM;
+    }
+    *out = c;
+    return EVO_OK;
+}
+
+int evo_check_batch(evo_check_t *c, const void *ref, const void *const *cand_ptrs, uint32_t P,
+                    void *stream, evo_stats *stats) {
+    if (!is_live(c)) return EVO_ERR_HANDLE;
+    if (!stats) return EVO_ERR_NULL;
+    HostSeg h{ref, cand_ptrs, c->n_elems, P, (uint32_t)c->dtype, 0u};
+    const int rc = validate_seg(h);
+    if (rc != EVO_OK) return rc;
+    try {
+        std::vector<HostSeg> segs(1, h);
+        return run_check(c, segs, static_cast<hipStream_t>(stream), stats);
+    } catch (const std::bad_alloc &) {
+        return EVO_ERR_NOMEM;
+    }
+}
+
+int evo_check_segmented(evo_check_t *c, const evo_segment *segs, uint32_t S, void *stream,
+                        evo_stats *stats, uint32_t n_rows) {
+    if (!is_live(c)) return EVO_ERR_HANDLE;
+    if (!segs || !stats) return EVO_ERR_NULL;
+    if (S == 0 || n_rows == 0) return EVO_ERR_SIZE;
+    try {
+        std::vector<HostSeg> hs(S);
+        std::vector<std::pair<uint64_t, uint64_t>> ranges(S);
+        for (uint32_t s = 0; s < S; ++s) {
+            hs[s] = HostSeg{segs[s].ref, segs[s].cand_ptrs, segs[s].n_elems, segs[s].P_s,
+                            segs[s].dtype, segs[s].stats_row0};
+            const int rc = validate_seg(hs[s]);
+            if (rc != EVO_OK) return rc;
+            const uint64_t lo = segs[s].stats_row0, hi = lo + segs[s].P_s;
+            if (hi > n_rows) return EVO_ERR_SIZE;
+            ranges[s] = {lo, hi};
+        }
+        std::sort(ranges.begin(), ranges.end());
+        for (uint32_t s = 1; s < S; ++s)
+            if (ranges[s].first < ranges[s - 1].second) return EVO_ERR_SIZE;
+        return run_check(c, hs, static_cast<hipStream_t>(stream), stats);
+    } catch (const std::bad_alloc &) {
+        return EVO_ERR_NOMEM;
+    }
+}
+
+int evo_fitness(evo_check_t *c, const float *timings, const float *baseline, uint32_t P,
+                uint32_t T, void *stream, evo_stats *stats, evo_pop_summary *summary) {
+    if (!is_live(c)) return EVO_ERR_HANDLE;
+    if (!timings || !baseline || !stats) return EVO_ERR_NULL;
+    if (P == 0 || T == 0 || T > EVO_FITNESS_MAX_T || P > (1u << 20)) return EVO_ERR_SIZE;
+    if ((reinterpret_cast<uintptr_t>(timings) & 3u) || (reinterpret_cast<uintptr_t>(baseline) & 3u) ||
+        (reinterpret_cast<uintptr_t>(stats) & 7u) || (reinterpret_cast<uintptr_t>(summary) & 3u))
+        return EVO_ERR_ALIGN;
+    int rc = bind_device(c);
+    if (rc != EVO_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if ((rc = ensure_fitness_scratch(c, st)) != EVO_OK) return rc;
+    return dev(evo::launch_fitness(timings, baseline, P, T, stats, summary, c->d_base_median,
+                                   c->d_fit_ticket, st));
+}
+
+int evo_check_destroy(evo_check_t *c) {
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        if (!c || g_live.erase(c) == 0) return EVO_ERR_HANDLE;
+    }
+    int rc = EVO_OK;
+    if (c->device != -1) {
+        int cur = -1;
+        if (hipGetDevice(&cur) == hipSuccess && cur != c->device) (void)hipSetDevice(c->device);
+        if (hipDeviceSynchronize() != hipSuccess) rc = EVO_ERR_DEVICE;
+        if (c->d_table) (void)hipFree(c->d_table);
+        if (c->d_partials) (void)hipFree(c->d_partials);
+        if (c->d_tickets) (void)hipFree(c->d_tickets);
+        if (c->d_base_median) (void)hipFree(c->d_base_median);
+        for (StageSlot &s : c->slots) {
+            if (s.host) (void)hipHostFree(s.host);
+            if (s.done) (void)hipEventDestroy(s.done);
+        }
+        if (cur != -1 && cur != c->device) (void)hipSetDevice(cur);
+    }
+    delete c;
+    return rc;
+}
+
+const char *evo_strerror(int code) {
+    switch (code) {
+        case EVO_OK: return "ok";
+        case EVO_ERR_NULL: return "a required pointer is NULL";
+        case EVO_ERR_DTYPE: return "unknown element type";
+        case EVO_ERR_SIZE: return "zero or out-of-range count";
+        case EVO_ERR_TOL: return "tolerance is negative, NaN or infinite";
+        case EVO_ERR_ALIGN: return "pointer not aligned to its element size";
+        case EVO_ERR_DEVICE: return "HIP call failed";
+        case EVO_ERR_NOMEM: return "out of memory";
+        case EVO_ERR_HANDLE: return "not a live context";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,577 @@
+// Batched / segmented tolerance check for gfx950 (MI355X).
+//
+// Functional-correctness constraint g(p) = 0 of EvoEngineer (arXiv 2510.03760,
+// Sec. 3.1, Eq. 1) as evaluated by the functional-testing stage of Sec. 4.3, for a
+// whole population per launch.  The element rule and the statistics are stated in
+// evo.h (evo_stats).
+//
+// Shape of the kernel.  HBM-bound streaming reduction, no contraction, so no MFMA.
+// A wavefront takes one 2 KiB reference tile into registers with two 128-bit loads
+// per lane, derives the per-reference-element tolerance and reciprocal once, and
+// then streams the same tile of each candidate of its group past it.  Statistics of
+// a group live in registers for the whole job and are reduced across lanes once, at
+// the end of the job (wavefront shuffles, then LDS across the wavefronts of the
+// workgroup, then one partial row per candidate in global scratch).  The last
+// workgroup of a segment to finish folds the partial rows in a fixed order, so
+// results do not depend on scheduling.
+//
+// Two code paths per (tile, candidate):
+//   fast  -- full, 16-byte aligned tile whose reference elements are all finite;
+//            branch-free arithmetic; it is discarded if any |c - r| in the tile is
+//            not finite (NaN/Inf candidate, or overflow);
+//   exact -- element-at-a-time transcription of the rule with bounds checks; used
+//            for ragged tails, unaligned tensors and every tile the fast path
+//            rejects.
+// Both give identical integers and maxima on the tiles the fast path accepts; the
+// sums differ only in summation order (fp32 over 8 non-negative terms in a tree,
+// then fp64), which stays far inside the 1e-6 relative budget of evo_stats.
+
+#include "evo_internal.h"
+
+namespace evo {
+namespace {
+
+constexpr float kInf = __builtin_huge_valf();
+constexpr float kFltMin = 1.17549435e-38f;
+constexpr int kDepth = 4;   // candidates whose tile loads a wavefront keeps in flight
+
+template <uint32_t DT> struct Tile;
+template <> struct Tile<EVO_F32> {
+    static constexpr int kVec = 4;   // elements per 16-byte vector
+    static constexpr int kNV = 2;    // vectors per lane per tile
+    static constexpr int kE = kVec * kNV;
+    using elem_t = float;
+};
+template <> struct Tile<EVO_BF16> {
+    static constexpr int kVec = 8;
+    static constexpr int kNV = 2;
+    static constexpr int kE = kVec * kNV;
+    using elem_t = uint16_t;
+};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 128-bit load
+
+__device__ __forceinline__ float as_f32(uint32_t w) { return __builtin_bit_cast(float, w); }
+
+__device__ __forceinline__ uint32_t popc64(uint64_t m) { return (uint32_t)__builtin_popcountll(m); }
+
+__device__ __forceinline__ uint64_t ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
+
+// Widen one 16-byte vector to binary32 values (exact for both element types).
+template <uint32_t DT>
+__device__ __forceinline__ void widen(const u32x4 &raw, float *out) {
+    if constexpr (DT == EVO_F32) {
+        out[0] = as_f32(raw.x);
+        out[1] = as_f32(raw.y);
+        out[2] = as_f32(raw.z);
+        out[3] = as_f32(raw.w);
+    } else {
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            out[2 * k] = as_f32(w[k] << 16);
+            out[2 * k + 1] = as_f32(w[k] & 0xffff0000u);
+        }
+    }
+}
+
+template <uint32_t DT>
+__device__ __forceinline__ float load_elem(const void *base, uint64_t idx) {
+    if constexpr (DT == EVO_F32) {
+        return static_cast<const float *>(base)[idx];
+    } else {
+        return as_f32((uint32_t) static_cast<const uint16_t *>(base)[idx] << 16);
+    }
+}
+
+// Per-lane running statistics of one candidate, plus wave-uniform integers.
+struct Acc {
+    float max_abs;
+    float max_rel;
+    double sum_abs;
+    double sum_rel;
+};
+
+// What the exact path has gathered for one candidate of one wavefront.  It lives in
+// LDS (indexed by a run-time candidate number) so that the rarely taken exact path
+// never touches the register-resident accumulators of the fast path.
+struct ExactAcc {
+    double sum_abs, sum_rel;
+    float max_abs, max_rel;
+    uint32_t n_mismatch, n_excluded, flags, pad;
+};
+
+template <typename T>
+__device__ __forceinline__ T wave_shfl_xor(T v, int mask) { return __shfl_xor(v, mask, kLanes); }
+
+// Exact path: the rule of evo.h one element per lane at a time.  Handles elements
+// beyond n (ignored), any alignment and every special value.
+template <uint32_t DT>
+__device__ __noinline__ void exact_tile(const void *ref, const void *cand, uint64_t n,
+                                        uint64_t tile_base, int lane, float atol, float rtol,
+                                        ExactAcc *out) {
+    constexpr int kE = Tile<DT>::kE;
+    float max_abs = 0.0f, max_rel = 0.0f;
+    double sum_abs = 0.0, sum_rel = 0.0;
+    uint32_t n_mismatch = 0, n_excluded = 0, flags = 0;
+#pragma unroll 1
+    for (int k = 0; k < kE; ++k) {
+        const uint64_t idx = tile_base + (uint64_t)(k * kLanes + lane);
+        const bool inb = idx < n;
+        float r = 0.0f, c = 0.0f;
+        if (inb) {
+            r = load_elem<DT>(ref, idx);
+            c = load_elem<DT>(cand, idx);
+        }
+        const float ar = __builtin_fabsf(r);
+        const float ac = __builtin_fabsf(c);
+        const float scaled = rtol * ar;
+        const float tol = atol + scaled;
+        const bool r_nan = r != r, c_nan = c != c;
+        const bool r_inf = ar == kInf, c_inf = ac == kInf;
+        const bool both = !r_nan && !c_nan && !r_inf && !c_inf;
+        const float d = __builtin_fabsf(c - r);
+        const bool match = (c == r) || (both && d <= tol);
+        n_mismatch += popc64(ballot(inb && !match));
+        n_excluded += popc64(ballot(inb && !both));
+        if (ballot(c_nan)) flags |= EVO_F_CAND_NAN;
+        if (ballot(c_inf)) flags |= EVO_F_CAND_INF;
+        if (ballot(r_nan)) flags |= EVO_F_REF_NAN;
+        if (ballot(r_inf)) flags |= EVO_F_REF_INF;
+        if (ballot(c_nan != r_nan)) flags |= EVO_F_NAN_SITE_DIFF;
+        if (ballot((c_inf || r_inf) && !c_nan && !r_nan && c != r)) flags |= EVO_F_INF_DIFF;
+        if (inb && both) {
+            float inv = 0.0f;
+            if (ar >= kFltMin) inv = 1.0f / ar;
+            const float q = d * inv;
+            max_abs = d > max_abs ? d : max_abs;
+            max_rel = q > max_rel ? q : max_rel;
+            sum_abs += (double)d;
+            sum_rel += (double)q;
+        }
+    }
+    // lanes -> wavefront, then into this wavefront's LDS record for the candidate
+#pragma unroll
+    for (int m = kLanes / 2; m >= 1; m >>= 1) {
+        max_abs = __builtin_fmaxf(max_abs, wave_shfl_xor(max_abs, m));
+        max_rel = __builtin_fmaxf(max_rel, wave_shfl_xor(max_rel, m));
+        sum_abs += wave_shfl_xor(sum_abs, m);
+        sum_rel += wave_shfl_xor(sum_rel, m);
+    }
+    if (lane == 0) {
+        out->sum_abs += sum_abs;
+        out->sum_rel += sum_rel;
+        out->max_abs = __builtin_fmaxf(out->max_abs, max_abs);
+        out->max_rel = __builtin_fmaxf(out->max_rel, max_rel);
+        out->n_mismatch += n_mismatch;
+        out->n_excluded += n_excluded;
+        out->flags |= flags;
+    }
+}
+
+// 16 bytes from global memory at a wave-uniform base plus a per-lane byte offset.
+__device__ __forceinline__ u32x4 load16(const char *base, uint32_t lane_off) {
+    typedef __attribute__((address_space(1))) const u32x4 global_u32x4;
+    return *(global_u32x4 *)((__attribute__((address_space(1))) const char *)base + lane_off);
+}
+
+// max(m, |a|, |b|) and max(m, a, b) in one instruction each.  Operands are finite
+// whenever the result is used (tiles holding anything else are redone exactly).
+__device__ __forceinline__ float max3_abs(float m, float a, float b) {
+    float o;
+    asm("v_max3_f32 %0, |%1|, |%2|, %3" : "=v"(o) : "v"(a), "v"(b), "v"(m));
+    return o;
+}
+__device__ __forceinline__ float max3(float m, float a, float b) {
+    float o;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(o) : "v"(a), "v"(b), "v"(m));
+    return o;
+}
+
+__device__ __forceinline__ const char *uniform_ptr(const void *p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const char *>(((uint64_t)hi << 32) | lo);
+}
+
+// One job: a chunk of tiles of one segment for up to kWaves candidate groups.
+// NC = compile-time number of candidate slots of a group (power of two >= cpg).
+template <uint32_t DT, int NC>
+__device__ void run_job(const SegDesc &sd, uint32_t job_local, uint32_t job_global, float atol,
+                        float rtol, Partial *partials, ExactAcc (*exact_acc)[kG],
+                        Partial (*wave_part)[kG]) {
+    using TL = Tile<DT>;
+    constexpr int kE = TL::kE;
+    constexpr int kNV = TL::kNV;
+    constexpr uint32_t kTileElems = tile_elems(DT);
+    constexpr int kElemBytes = (int)sizeof(typename TL::elem_t);
+    constexpr int D = NC < kDepth ? NC : kDepth;      // candidates whose loads are in flight
+
+    const int lane = (int)(threadIdx.x & (kLanes - 1));
+    const uint32_t lane_off = (uint32_t)lane * 16u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+    const uint32_t gpw = sd.gpw;
+    const uint32_t tpw = kWaves / gpw;                 // tile slots per workgroup
+    const uint32_t gl = wave % gpw;                    // group slot inside the job
+    const uint32_t tl = wave / gpw;                    // tile slot inside the job
+    const uint32_t gblock = job_local / sd.n_chunks;
+    const uint32_t chunk = job_local - gblock * sd.n_chunks;
+    const uint32_t group = gblock * gpw + gl;
+    const bool active = group < sd.n_groups;
+    const uint32_t cand0 = active ? group * sd.cpg : 0u;
+    const uint32_t ncand = active ? min(sd.cpg, sd.P - cand0) : 0u;
+
+    const uint64_t n = sd.n;
+    const uint64_t n_full = n / kTileElems;                         // full tiles
+    const uint64_t n_tiles = (n + kTileElems - 1) / kTileElems;     // with the ragged one
+    const uint64_t t_begin = (uint64_t)chunk * sd.tiles_per_chunk;
+    const uint64_t t_end = min(t_begin + (uint64_t)sd.tiles_per_chunk, n_tiles);
+    const uint64_t t_fend = min(t_end, n_full);
+
+    Acc acc[NC];
+    uint32_t n_mismatch[NC];
+#pragma unroll
+    for (int g = 0; g < NC; ++g) {
+        acc[g] = Acc{0.0f, 0.0f, 0.0, 0.0};
+        n_mismatch[g] = 0;
+    }
+    if (lane < kG) exact_acc[wave][lane] = ExactAcc{0.0, 0.0, 0.0f, 0.0f, 0u, 0u, 0u, 0u};
+
+    // Wave-uniform base pointers; vector loads need every tensor 16-byte aligned.
+    const char *rptr = uniform_ptr(sd.ref);
+    const char *cptr[NC];
+    bool vec_ok = ((uintptr_t)rptr & 15u) == 0;
+#pragma unroll
+    for (int g = 0; g < NC; ++g) {
+        cptr[g] = uniform_ptr(sd.cands[cand0 + min((uint32_t)g, ncand ? ncand - 1 : 0u)]);
+        vec_ok = vec_ok && (((uintptr_t)cptr[g] & 15u) == 0);
+    }
+    const uint32_t all_mask = (ncand >= 32 ? 0xffffffffu : ((1u << ncand) - 1u));
+
+    uint64_t t = t_begin + tl;
+    if (ncand > 0 && vec_ok) {
+        // Software pipeline over (tile, candidate) pairs: while pair i is evaluated the
+        // loads of pairs i+1 .. i+D are in flight, across tile boundaries too.
+        u32x4 ref_raw[kNV];
+        u32x4 buf[D][kNV];
+        if (t < t_fend) {
+            const uint64_t off = t * (uint64_t)(kTileElems * kElemBytes);
+#pragma unroll
+            for (int j = 0; j < kNV; ++j) ref_raw[j] = load16(rptr + off + j * 1024, lane_off);
+#pragma unroll
+            for (int g = 0; g < D; ++g)
+                if ((uint32_t)g < ncand) {
+#pragma unroll
+                    for (int j = 0; j < kNV; ++j) buf[g][j] = load16(cptr[g] + off + j * 1024, lane_off);
+                }
+        }
+        for (; t < t_fend; t += tpw) {
+            const uint64_t off = t * (uint64_t)(kTileElems * kElemBytes);
+            const uint64_t t_next = t + tpw;
+            const bool has_next = t_next < t_fend;
+            const uint64_t off_next = t_next * (uint64_t)(kTileElems * kElemBytes);
+
+            float r[kE], tol[kE], inv[kE];
+            bool ref_finite = true;
+#pragma unroll
+            for (int j = 0; j < kNV; ++j) widen<DT>(ref_raw[j], &r[j * TL::kVec]);
+            if (has_next) {
+#pragma unroll
+                for (int j = 0; j < kNV; ++j) ref_raw[j] = load16(rptr + off_next + j * 1024, lane_off);
+            }
+#pragma unroll
+            for (int e = 0; e < kE; ++e) {
+                const float ar = __builtin_fabsf(r[e]);
+                const float scaled = rtol * ar;
+                tol[e] = atol + scaled;
+                inv[e] = ar >= kFltMin ? 1.0f / ar : 0.0f;
+                ref_finite = ref_finite && (ar < kInf);        // false for NaN and Inf
+            }
+            const bool ref_ok = ballot(!ref_finite) == 0;
+            uint32_t exact_mask = ref_ok ? 0u : all_mask;
+
+#pragma unroll
+            for (int g = 0; g < NC; ++g) {
+                const bool live = (uint32_t)g < ncand;
+                float c[kE];
+                if (live) {
+#pragma unroll
+                    for (int j = 0; j < kNV; ++j) widen<DT>(buf[g % D][j], &c[j * TL::kVec]);
+                }
+                // Refill the slot (whether or not candidate g exists, so that the slot
+                // rotation stays in step): candidate g+D of this tile, or candidate
+                // g+D-NC of the wavefront's next tile.
+                if (g + D < NC) {
+                    if ((uint32_t)(g + D) < ncand) {
+#pragma unroll
+                        for (int j = 0; j < kNV; ++j)
+                            buf[g % D][j] = load16(cptr[(g + D) % NC] + off + j * 1024, lane_off);
+                    }
+                } else if (has_next && (uint32_t)(g + D - NC) < ncand) {
+#pragma unroll
+                    for (int j = 0; j < kNV; ++j)
+                        buf[g % D][j] = load16(cptr[(g + D) % NC] + off_next + j * 1024, lane_off);
+                }
+                if (live && ref_ok) {
+                    float d[kE], q[kE];
+                    uint32_t mism = 0;
+#pragma unroll
+                    for (int e = 0; e < kE; ++e) {
+                        d[e] = c[e] - r[e];
+                        mism += popc64(ballot(!(__builtin_fabsf(d[e]) <= tol[e])));
+                        q[e] = __builtin_fabsf(d[e]) * inv[e];
+                    }
+                    // fp32 tree sums over 8 non-negative terms (3 roundings deep)
+                    float m_abs = acc[g].max_abs, m_rel = acc[g].max_rel;
+                    double s_abs = acc[g].sum_abs, s_rel = acc[g].sum_rel;
+                    float chk = 0.0f;
+#pragma unroll
+                    for (int h = 0; h < kE; h += 8) {
+                        const float sa =
+                            ((__builtin_fabsf(d[h]) + __builtin_fabsf(d[h + 1])) +
+                             (__builtin_fabsf(d[h + 2]) + __builtin_fabsf(d[h + 3]))) +
+                            ((__builtin_fabsf(d[h + 4]) + __builtin_fabsf(d[h + 5])) +
+                             (__builtin_fabsf(d[h + 6]) + __builtin_fabsf(d[h + 7])));
+                        const float sr = ((q[h] + q[h + 1]) + (q[h + 2] + q[h + 3])) +
+                                         ((q[h + 4] + q[h + 5]) + (q[h + 6] + q[h + 7]));
+                        s_abs += (double)sa;
+                        s_rel += (double)sr;
+                        chk += sa + sr;
+#pragma unroll
+                        for (int e = h; e < h + 8; e += 2) {
+                            m_abs = max3_abs(m_abs, d[e], d[e + 1]);
+                            m_rel = max3(m_rel, q[e], q[e + 1]);
+                        }
+                    }
+                    // every d and q finite and no fp32 partial overflowed <=> chk finite
+                    if (ballot(!(chk < kInf)) == 0) {
+                        acc[g].max_abs = m_abs;
+                        acc[g].max_rel = m_rel;
+                        acc[g].sum_abs = s_abs;
+                        acc[g].sum_rel = s_rel;
+                        n_mismatch[g] += mism;
+                    } else {
+                        exact_mask |= 1u << g;
+                    }
+                }
+            }
+            // Tiles with non-finite values or overflow: redo those candidates exactly.
+            while (exact_mask) {
+                const int g = __builtin_ctz(exact_mask);
+                exact_mask &= exact_mask - 1;
+                exact_tile<DT>(rptr, sd.cands[cand0 + g], n, t * (uint64_t)kTileElems, lane,
+                               atol, rtol, &exact_acc[wave][g]);
+            }
+        }
+    } else if (ncand > 0) {
+        // Some tensor is not 16-byte aligned: everything goes through the exact path.
+        for (; t < t_fend; t += tpw)
+            for (uint32_t g = 0; g < ncand; ++g)
+                exact_tile<DT>(rptr, sd.cands[cand0 + g], n, t * (uint64_t)kTileElems, lane, atol,
+                               rtol, &exact_acc[wave][g]);
+    }
+    // The ragged last tile of the segment, if it falls into this job.
+    if (ncand > 0 && tl == 0 && n_full < t_end && n_full >= t_begin && n_full < n_tiles)
+        for (uint32_t g = 0; g < ncand; ++g)
+            exact_tile<DT>(rptr, sd.cands[cand0 + g], n, n_full * (uint64_t)kTileElems, lane, atol,
+                           rtol, &exact_acc[wave][g]);
+
+    // Lanes -> wavefront: maxima and sums by butterfly shuffles (counts are already
+    // wave-uniform), joined with what the exact path left in LDS.
+#pragma unroll
+    for (int g = 0; g < NC; ++g) {
+        float ma = acc[g].max_abs, mr = acc[g].max_rel;
+        double sa = acc[g].sum_abs, sr = acc[g].sum_rel;
+#pragma unroll
+        for (int m = kLanes / 2; m >= 1; m >>= 1) {
+            ma = __builtin_fmaxf(ma, wave_shfl_xor(ma, m));
+            mr = __builtin_fmaxf(mr, wave_shfl_xor(mr, m));
+            sa += wave_shfl_xor(sa, m);
+            sr += wave_shfl_xor(sr, m);
+        }
+        if (lane == 0) {
+            const ExactAcc x = exact_acc[wave][g];
+            Partial p;
+            p.n_mismatch = (uint64_t)n_mismatch[g] + x.n_mismatch;
+            p.n_excluded = x.n_excluded;
+            p.sum_abs = sa + x.sum_abs;
+            p.sum_rel = sr + x.sum_rel;
+            p.max_abs = __builtin_fmaxf(ma, x.max_abs);
+            p.max_rel = __builtin_fmaxf(mr, x.max_rel);
+            p.flags = x.flags;
+            p.pad = 0;
+            wave_part[wave][g] = p;
+        }
+    }
+    __syncthreads();
+
+    // Wavefronts -> workgroup, in wave order, one thread per (group slot, candidate).
+    if (threadIdx.x < (uint32_t)kRowsPerJob) {
+        const uint32_t slot = threadIdx.x / kG;     // group slot
+        const uint32_t gi = threadIdx.x % kG;
+        if (slot < gpw && gi < (uint32_t)NC) {
+            Partial out = wave_part[slot][gi];      // tile slot 0
+            for (uint32_t k = 1; k < tpw; ++k) {
+                const Partial &o = wave_part[k * gpw + slot][gi];
+                out.n_mismatch += o.n_mismatch;
+                out.n_excluded += o.n_excluded;
+                out.sum_abs += o.sum_abs;
+                out.sum_rel += o.sum_rel;
+                out.max_abs = __builtin_fmaxf(out.max_abs, o.max_abs);
+                out.max_rel = __builtin_fmaxf(out.max_rel, o.max_rel);
+                out.flags |= o.flags;
+            }
+            partials[(uint64_t)job_global * kRowsPerJob + slot * kG + gi] = out;
+        }
+    }
+}
+
+template <uint32_t DT>
+__device__ __forceinline__ void run_job_nc(const SegDesc &sd, uint32_t job_local,
+                                           uint32_t job_global, float atol, float rtol,
+                                           Partial *partials, ExactAcc (*exact_acc)[kG],
+                                           Partial (*wave_part)[kG]) {
+    if (sd.cpg > 8)
+        run_job<DT, 16>(sd, job_local, job_global, atol, rtol, partials, exact_acc, wave_part);
+    else if (sd.cpg > 4)
+        run_job<DT, 8>(sd, job_local, job_global, atol, rtol, partials, exact_acc, wave_part);
+    else if (sd.cpg > 2)
+        run_job<DT, 4>(sd, job_local, job_global, atol, rtol, partials, exact_acc, wave_part);
+    else if (sd.cpg > 1)
+        run_job<DT, 2>(sd, job_local, job_global, atol, rtol, partials, exact_acc, wave_part);
+    else
+        run_job<DT, 1>(sd, job_local, job_global, atol, rtol, partials, exact_acc, wave_part);
+}
+
+// Fold of a segment's partial rows by the last workgroup that finished a job of it.
+// Thread layout: R consecutive threads share a candidate and take R consecutive
+// ranges of chunks; their R results are then added in range order.  The order is
+// a function of the launch geometry only.
+__device__ void finalize_segment(const SegDesc &sd, const Partial *partials, evo_stats *stats) {
+    __shared__ Partial fold[kThreads];
+    uint32_t pc = 1;
+    while (pc < sd.P && pc < (uint32_t)kThreads) pc <<= 1;   // candidates per pass (power of 2)
+    const uint32_t R = kThreads / pc;                          // chunk ranges per candidate
+    const uint32_t per = (sd.n_chunks + R - 1) / R;
+    const uint32_t ci = threadIdx.x / R;
+    const uint32_t ri = threadIdx.x % R;
+
+    for (uint32_t p0 = 0; p0 < sd.P; p0 += pc) {
+        const uint32_t p = p0 + ci;
+        Partial a{};
+        if (p < sd.P) {
+            const uint32_t group = p / sd.cpg;
+            const uint32_t gi = p - group * sd.cpg;
+            const uint32_t gblock = group / sd.gpw;
+            const uint32_t slot = group - gblock * sd.gpw;
+            const uint32_t ch_lo = ri * per;
+            const uint32_t ch_hi = min(ch_lo + per, sd.n_chunks);
+            for (uint32_t ch = ch_lo; ch < ch_hi; ++ch) {
+                const uint64_t job = (uint64_t)sd.job0 + (uint64_t)gblock * sd.n_chunks + ch;
+                const Partial *src = partials + job * kRowsPerJob + slot * kG + gi;
+                // device-scope loads: the rows were written by other workgroups,
+                // possibly through another XCD's L2
+                const uint64_t nm = __hip_atomic_load(&src->n_mismatch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const uint64_t nx = __hip_atomic_load(&src->n_excluded, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const double sa = __hip_atomic_load(&src->sum_abs, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const double sr = __hip_atomic_load(&src->sum_rel, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const float ma = __hip_atomic_load(&src->max_abs, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const float mr = __hip_atomic_load(&src->max_rel, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const uint32_t fl = __hip_atomic_load(&src->flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                a.n_mismatch += nm;
+                a.n_excluded += nx;
+                a.sum_abs += sa;
+                a.sum_rel += sr;
+                a.max_abs = __builtin_fmaxf(a.max_abs, ma);
+                a.max_rel = __builtin_fmaxf(a.max_rel, mr);
+                a.flags |= fl;
+            }
+        }
+        fold[threadIdx.x] = a;
+        __syncthreads();
+        if (ri == 0 && p < sd.P) {
+            for (uint32_t k = 1; k < R; ++k) {
+                const Partial &o = fold[threadIdx.x + k];
+                a.n_mismatch += o.n_mismatch;
+                a.n_excluded += o.n_excluded;
+                a.sum_abs += o.sum_abs;
+                a.sum_rel += o.sum_rel;
+                a.max_abs = __builtin_fmaxf(a.max_abs, o.max_abs);
+                a.max_rel = __builtin_fmaxf(a.max_rel, o.max_rel);
+                a.flags |= o.flags;
+            }
+            evo_stats s;
+            s.n_mismatch = a.n_mismatch;
+            s.n_finite = sd.n - a.n_excluded;
+            s.sum_abs_err = a.sum_abs;
+            s.sum_rel_err = a.sum_rel;
+            s.max_abs_err = a.max_abs;
+            s.max_rel_err = a.max_rel;
+            s.flags = a.flags;
+            s.valid = a.n_mismatch == 0 ? 1u : 0u;
+            s.median_ms = 0.0f;
+            s.mean_ms = 0.0f;
+            s.speedup = 0.0f;
+            s.fitness = 0.0f;
+            s.n_elems_lo = (uint32_t)(sd.n & 0xffffffffu);
+            s.n_elems_hi = (uint32_t)(sd.n >> 32);
+            stats[sd.stats_row0 + p] = s;
+        }
+        __syncthreads();
+    }
+}
+
+__global__ void __launch_bounds__(kThreads, 2)
+evo_check_kernel(const SegDesc *__restrict__ descs, uint32_t S, float atol, float rtol,
+                 Partial *__restrict__ partials, uint32_t *__restrict__ tickets,
+                 evo_stats *__restrict__ stats) {
+    // Which segment does this workgroup belong to?  (job0 is ascending.)
+    const uint32_t job = blockIdx.x;
+    uint32_t lo = 0, hi = S;
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (descs[mid].job0 <= job) lo = mid; else hi = mid;
+    }
+    const uint32_t s = lo;
+    const SegDesc sd = descs[s];
+    const uint32_t job_local = job - sd.job0;
+
+    __shared__ ExactAcc exact_acc[kWaves][kG];
+    __shared__ Partial wave_part[kWaves][kG];
+    if (sd.dtype == EVO_BF16)
+        run_job_nc<EVO_BF16>(sd, job_local, job, atol, rtol, partials, exact_acc, wave_part);
+    else
+        run_job_nc<EVO_F32>(sd, job_local, job, atol, rtol, partials, exact_acc, wave_part);
+
+    // Publish this job's partial rows, then take a ticket; the workgroup that draws
+    // the segment's last ticket folds the segment and re-arms the counter.
+    __shared__ uint32_t is_last;
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t prev = __hip_atomic_fetch_add(&tickets[s], 1u, __ATOMIC_ACQ_REL,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+        is_last = (prev == sd.n_jobs - 1) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (is_last) {
+        __threadfence();
+        finalize_segment(sd, partials, stats);
+        if (threadIdx.x == 0)
+            __hip_atomic_store(&tickets[s], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_check(const SegDesc *d_descs, uint32_t S, uint32_t total_jobs, float atol,
+                        float rtol, Partial *partials, uint32_t *tickets, evo_stats *stats,
+                        hipStream_t stream) {
+    hipLaunchKernelGGL(evo_check_kernel, dim3(total_jobs), dim3(kThreads), 0, stream, d_descs, S,
+                       atol, rtol, partials, tickets, stats);
+    return hipGetLastError();
+}
+
+}  // namespace evo

@@ -1,0 +1,275 @@
+"""GPU parity on the awkward cases: ragged sizes, every special value, unaligned
+tensors, odd population sizes, repeatability, argument errors on a live device."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import synth  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def gu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_util
+    return gpu_util
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _mixed(n, P, seed, dtype=torch.float32, special=True):
+    """Reference and P candidates with near values, far values and (optionally) NaN,
+    +-Inf, zeros, subnormals and huge values on both sides."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    ref = 3 * torch.randn(n, generator=g, device="cuda")
+    cands = []
+    for p in range(P):
+        c = ref * (1 + 0.02 * torch.randn(n, generator=g, device="cuda"))
+        far = torch.rand(n, generator=g, device="cuda") < 0.05
+        c = torch.where(far, 20 * torch.rand(n, generator=g, device="cuda") - 10, c)
+        same = torch.rand(n, generator=g, device="cuda") < 0.2
+        c = torch.where(same, ref, c)
+        cands.append(c)
+    if special:
+        vals = [float("nan"), float("inf"), float("-inf"), 0.0, -0.0, 1e-41, -1e-41, 3e38, -3e38,
+                1.17549435e-38]
+        for t in [ref] + cands:
+            k = max(1, n // 40)
+            idx = torch.randint(0, n, (k,), generator=g, device="cuda")
+            v = torch.tensor(vals, device="cuda")[torch.randint(0, len(vals), (k,), generator=g,
+                                                                 device="cuda")]
+            t[idx] = v
+    if dtype == torch.bfloat16:
+        ref = ref.to(torch.bfloat16)
+        cands = [c.to(torch.bfloat16) for c in cands]
+    seg = synth.Segment(ref.contiguous(), [c.contiguous() for c in cands], (n,), [True] * P)
+    T = 8
+    t = 1 + torch.rand(P, T, generator=g, device="cuda")
+    b = 1 + torch.rand(T, generator=g, device="cuda")
+    return synth.Workload("mixed-n%d-P%d" % (n, P), [seg], 1e-2, 1e-2, t, b)
+
+
+SIZES = [1, 3, 4, 5, 63, 64, 65, 255, 256, 257, 511, 512, 513, 1023, 1024, 1025, 2047, 2049,
+         4095, 4097, 65535, 65537, (1 << 20) + 1]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_ragged_sizes_special_values(gu, dtype):
+    for i, n in enumerate(SIZES):
+        _say("mixed n=%d %s" % (n, dtype))
+        w = _mixed(n, 3, 100 + i, dtype)
+        chk, stats, want = gu.check_parity(w, label="sizes")
+        chk.close()
+
+
+@pytest.mark.parametrize("P", [1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 31, 33, 63, 64, 65, 130, 257])
+def test_population_sizes(gu, P):
+    _say("mixed P=%d" % P)
+    w = _mixed(5000, P, 1000 + P, torch.float32)
+    chk, stats, want = gu.check_parity(w, label="P")
+    gu.fitness_parity(chk, stats, w.timings, w.baseline, label="P%d" % P)
+    chk.close()
+    w = _mixed(3000, P, 2000 + P, torch.bfloat16, special=False)
+    chk, stats, want = gu.check_parity(w, label="P-bf16")
+    chk.close()
+
+
+def test_overflowing_differences(gu):
+    """|c - r| and d/|r| overflow binary32 on finite inputs: the statistics keep +Inf."""
+    _say("overflow")
+    n = 4096
+    ref = torch.full((n,), 3e38, device="cuda")
+    ref[::3] = -3e38
+    ref[5::7] = 1e-30
+    c0 = -ref
+    c1 = ref.clone()
+    c1[100] = -3e38 if float(ref[100]) > 0 else 3e38
+    seg = synth.Segment(ref, [c0, c1, ref.clone()], (n,), [True, True, False])
+    w = synth.Workload("overflow", [seg], 1e-2, 1e-2, torch.ones(3, 4, device="cuda"),
+                       torch.ones(4, device="cuda"))
+    chk, stats, want = gu.check_parity(w, label="overflow")
+    assert np.isinf(want[0]["max_abs_err"]) and np.isinf(want[0]["sum_abs_err"])
+    assert want[2]["valid"] == 1
+    chk.close()
+
+
+def test_unaligned_tensors(gu):
+    """Element-aligned but not 16-byte aligned views go through the exact path."""
+    for dtype, offs in ((torch.float32, (1, 2, 3)), (torch.bfloat16, (1, 3, 7))):
+        for k, off in enumerate(offs):
+            _say("unaligned %s +%d" % (dtype, off))
+            n = 3000 + k
+            w = _mixed(n + 8, 4, 300 + k, dtype)
+            seg = w.segments[0]
+            ref = seg.ref[off:off + n] if k != 1 else seg.ref[:n]
+            cands = [c[(off if i % 2 == 0 else 0):][:n] for i, c in enumerate(seg.cands)]
+            assert any(t.data_ptr() % 16 for t in [ref] + cands)
+            seg2 = synth.Segment(ref, cands, (n,), seg.corrupted)
+            w2 = synth.Workload("unaligned", [seg2], w.atol, w.rtol, w.timings, w.baseline)
+            chk, stats, want = gu.check_parity(w2, label="unaligned")
+            chk.close()
+
+
+def test_tolerance_extremes(gu):
+    _say("tolerances")
+    base = _mixed(10000, 4, 77, torch.float32)
+    for atol, rtol in ((0.0, 0.0), (0.0, 1e-2), (1e-3, 0.0), (1e30, 0.0), (0.0, 3e38), (3e38, 3e38)):
+        w = synth.Workload("tol", base.segments, atol, rtol, base.timings, base.baseline)
+        chk, stats, want = gu.check_parity(w, label="tol %g %g" % (atol, rtol))
+        chk.close()
+
+
+def test_segmented_mixed_dtypes_and_row_layout(gu):
+    """Groups of different dtype, size and population in one launch, rows scattered."""
+    _say("segmented mixed")
+    import paper_2510_03760_amd as evo
+    from paper_2510_03760_amd.binding import stats_to_numpy
+    ws = [_mixed(70000, 20, 1, torch.float32), _mixed(513, 3, 2, torch.bfloat16),
+          _mixed(1, 1, 3, torch.float32), _mixed(250000, 40, 4, torch.bfloat16, special=False),
+          _mixed(4096, 16, 5, torch.float32, special=False)]
+    order = [3, 0, 4, 1, 2]           # row ranges in a different order than the segments
+    row0 = {}
+    nxt = 2                           # leave rows 0-1 and a gap untouched
+    for i in order:
+        row0[i] = nxt
+        nxt += ws[i].P + 1
+    n_rows = nxt + 3
+    chk = evo.Checker(evo.EVO_F32, 1, 1e-2, 1e-2)
+    stats = chk.new_stats(n_rows)
+    stats.fill_(0xEE)
+    descs = [{"ref": w.segments[0].ref, "cand_ptrs": w.segments[0].cands, "n_elems": w.segments[0].n,
+              "dtype": gu.dtype_code(w.segments[0]), "stats_row0": row0[i]} for i, w in enumerate(ws)]
+    chk.check_segmented(descs, stats, n_rows)
+    torch.cuda.synchronize()
+    got = stats_to_numpy(stats)
+    raw = stats.cpu().numpy().reshape(n_rows, 72)
+    written = np.zeros(n_rows, bool)
+    for i, w in enumerate(ws):
+        want = gu.oracle_rows(w.segments[0], 1e-2, 1e-2)
+        for p, o in enumerate(want):
+            gu.assert_rows_equal(got[row0[i] + p], o, "seg %d row %d" % (i, p))
+            written[row0[i] + p] = True
+    assert np.all(raw[~written] == 0xEE), "rows outside every group must stay untouched"
+    chk.close()
+
+
+def test_repeatable_and_reusable_context(gu):
+    """Same call twice gives byte-identical rows; a context can be reused for other
+    populations (its counters re-arm themselves)."""
+    _say("repeat")
+    from paper_2510_03760_amd.binding import stats_to_numpy
+    w = _mixed(300000, 16, 9, torch.float32)
+    chk, stats, want = gu.check_parity(w, label="repeat")
+    first = stats.clone()
+    seg = w.segments[0]
+    for _ in range(5):
+        stats.fill_(0)
+        chk.check_batch(seg.ref, seg.cands, stats)
+        torch.cuda.synchronize()
+        assert torch.equal(stats, first)
+    # fewer candidates through the same context
+    stats2 = chk.new_stats(5)
+    chk.check_batch(seg.ref, seg.cands[:5], stats2)
+    torch.cuda.synchronize()
+    assert torch.equal(stats2, first[: 5 * 72])
+    # back-to-back calls on one stream without synchronising in between
+    outs = [chk.new_stats(16) for _ in range(12)]
+    for o in outs:
+        chk.check_batch(seg.ref, seg.cands, o)
+    torch.cuda.synchronize()
+    for o in outs:
+        assert torch.equal(o, first)
+    # on a side stream
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    o = chk.new_stats(16)
+    with torch.cuda.stream(side):
+        chk.check_batch(seg.ref, seg.cands, o, stream=side)
+    side.synchronize()
+    assert torch.equal(o, first)
+    chk.close()
+
+
+@pytest.mark.parametrize("T", [1, 2, 3, 5, 64, 100, 101, 255, 256, 257, 1000, 1001, 4095, 4096])
+def test_fitness_T(gu, T):
+    _say("fitness T=%d" % T)
+    import paper_2510_03760_amd as evo
+    g = torch.Generator(device="cuda")
+    g.manual_seed(T)
+    for P in (1, 9):
+        t = torch.exp(0.1 * torch.randn(P, T, generator=g, device="cuda"))
+        if P > 3 and T > 1:
+            t[3] = t[2]
+            t[4, : max(1, T // 2)] = float(t[4, 0])
+        b = torch.exp(0.1 * torch.randn(T, generator=g, device="cuda"))
+        chk = evo.Checker(evo.EVO_F32, 1, 0.0, 0.0)
+        stats = chk.new_stats(P)
+        view = stats.view(P, 72)
+        valid = (torch.arange(P, device="cuda") % 3 != 1).to(torch.int32)
+        view[:, 44:48] = valid.view(torch.uint8).view(P, 4)
+        gu.fitness_parity(chk, stats, t, b, label="T%d" % T)
+        chk.close()
+
+
+def test_fitness_population_and_unusable_rows(gu):
+    _say("fitness population")
+    import paper_2510_03760_amd as evo
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    for P in (256, 1000, 3000):
+        T = 100
+        t = torch.exp(0.1 * torch.randn(P, T, generator=g, device="cuda"))
+        b = torch.exp(0.1 * torch.randn(T, generator=g, device="cuda"))
+        t[7, 3] = float("nan")
+        t[8, 0] = float("inf")
+        t[9, 99] = 0.0
+        t[10, 50] = -1.0
+        t[20] = t[11]            # equal fitness: the lower index must win if it is the best
+        t[11] *= 0.25
+        t[20] *= 0.25
+        chk = evo.Checker(evo.EVO_F32, 1, 0.0, 0.0)
+        stats = chk.new_stats(P)
+        view = stats.view(P, 72)
+        valid = (torch.arange(P, device="cuda") % 5 != 0).to(torch.int32)
+        view[:, 44:48] = valid.view(torch.uint8).view(P, 4)
+        got, pop, want = gu.fitness_parity(chk, stats, t, b, label="pop%d" % P)
+        assert int(pop["best_idx"]) == 11
+        # nobody valid
+        view[:, 44:48] = 0
+        got, pop, want = gu.fitness_parity(chk, stats, t, b, label="none%d" % P)
+        assert int(pop["best_idx"]) == P and float(pop["best_speedup"]) == 1.0
+        # unusable baseline
+        view[:, 44:48] = 1
+        b2 = b.clone()
+        b2[5] = float("nan")
+        got, pop, want = gu.fitness_parity(chk, stats, t, b2, label="badbase%d" % P)
+        assert np.all(got["speedup"] == 0)
+        chk.close()
+
+
+def test_errors_on_live_device(gu):
+    """Argument errors are reported before anything is enqueued, also with a GPU."""
+    _say("errors")
+    import paper_2510_03760_amd as evo
+    chk = evo.Checker(evo.EVO_F32, 1024, 1e-2, 1e-2)
+    ref = torch.zeros(1024, device="cuda")
+    stats = chk.new_stats(2)
+    with pytest.raises(evo.EvoError) as e:
+        evo.evo_check_batch(chk.ctx, ref, [ref, None], 2, None, stats)
+    assert e.value.code == -1
+    with pytest.raises(evo.EvoError) as e:
+        evo.evo_check_batch(chk.ctx, ref.data_ptr() + 2, [ref], 1, None, stats)
+    assert e.value.code == -5
+    with pytest.raises(evo.EvoError) as e:
+        evo.evo_fitness(chk.ctx, ref, ref, 1, 5000, None, stats, None)
+    assert e.value.code == -3
+    chk.check_batch(ref, [ref, ref], stats)   # still usable afterwards
+    torch.cuda.synchronize()
+    from paper_2510_03760_amd.binding import stats_to_numpy
+    assert stats_to_numpy(stats)["valid"].tolist() == [1, 1]
+    chk.close()
