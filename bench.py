@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the fitness-and-validity evaluation step on one MI355X.
+
+One step = one pass of the whole hot path over one synthetic population: the
+batched (or segmented) tolerance check of every candidate against its reference,
+then the median-timing / speedup / fitness reduction.  Inputs are resident in HBM
+before the timed region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c4|c5]
+                    [--no-cpu-baseline] [--copy-calibration]
+
+--copy-calibration runs only a plain device-to-device copy of known size (used to
+scale the rocprofv3 FETCH_SIZE / WRITE_SIZE counters) and prints its own JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "candidate-elements validated/sec and achieved HBM GB/s vs MI355X peak"
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, vendor figure
+
+
+def build_workload(name: str):
+    import synth
+    if name == "c1":
+        return synth.tiny("cuda")
+    if name == "c2":
+        return synth.dense_f32("cuda", side=8192, P=16, T=100)
+    if name == "c3":
+        return synth.softmax_bf16("cuda", B=32, R=128, C=4096, P=64, T=100)
+    if name == "c4":
+        return synth.ragged_f32("cuda", P_s=32, T=100)
+    if name == "c5":
+        return synth.heavy_tail_f32("cuda", log2n=30, P=8, T=1000)
+    raise SystemExit("unknown workload %r" % name)
+
+
+def cpu_baseline(w, budget_elems: int):
+    """Times the CPU oracle, as it stands, on one thread over a bounded sample of the
+    same population (a prefix of each tensor, all candidates)."""
+    import numpy as np
+    import oracle
+    import synth
+    total = w.cand_elems
+    frac = min(1.0, budget_elems / float(total))
+    t_all = 0.0
+    done = 0
+    rows = []
+    for seg in w.segments:
+        m = seg.n if frac >= 1.0 else max(1, int(seg.n * frac))
+        dt = oracle.BF16 if seg.dtype_name == "bf16" else oracle.F32
+        ref = synth.to_oracle_array(seg.ref[:m])
+        for c in seg.cands:
+            ch = synth.to_oracle_array(c[:m])
+            t0 = time.perf_counter()
+            rows.append(oracle.check_one(ref, ch, dt, w.atol, w.rtol))
+            t_all += time.perf_counter() - t0
+            done += m
+    tim = w.timings.cpu().numpy()
+    base = w.baseline.cpu().numpy()
+    valid = np.array([r["valid"] for r in rows], np.uint32)
+    t0 = time.perf_counter()
+    oracle.fitness(tim, base, valid)
+    t_all += time.perf_counter() - t0
+    sample = ("first %.1f%% of every tensor, all %d candidates, plus the full timing table"
+              % (100.0 * done / total, w.P))
+    return {"value": done / t_all, "unit": "cand-elem/s", "cores": 1, "kind": "oracle",
+            "sample": sample, "seconds": round(t_all, 3)}, rows, frac
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget-elems", type=float, default=2.0e9,
+                    help="candidate-elements the CPU oracle is timed on (about 160 M/s/core)")
+    ap.add_argument("--copy-calibration", action="store_true")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path is built and measured on ONE GPU; --gpus %d is not "
+              "supported (candidates shard trivially across GPUs, see DESIGN.md)" % args.gpus,
+              file=sys.stderr)
+        return 2
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        n = 1 << 30   # bytes
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "launches": args.steps + 3,
+                          "ms_per_copy": ms, "GBps_read_plus_write": 2 * n / ms / 1e6}))
+        return 0
+
+    import paper_2510_03760_amd as evo
+    from paper_2510_03760_amd.binding import stats_to_numpy, summary_to_numpy
+
+    w = build_workload(args.workload)
+    torch.cuda.synchronize()
+    segs = w.segments
+    dcode = lambda s: evo.EVO_BF16 if s.dtype_name == "bf16" else evo.EVO_F32  # noqa: E731
+    chk = evo.Checker(dcode(segs[0]), segs[0].n, w.atol, w.rtol)
+    P = w.P
+    stats = chk.new_stats(P)
+    summary = chk.new_summary()
+    stream = torch.cuda.current_stream()
+    seg_descs = None
+    if len(segs) > 1:
+        row0, seg_descs = 0, []
+        for s in segs:
+            seg_descs.append({"ref": s.ref, "cand_ptrs": s.cands, "n_elems": s.n,
+                              "dtype": dcode(s), "stats_row0": row0})
+            row0 += len(s.cands)
+
+    def check():
+        if seg_descs is None:
+            chk.check_batch(segs[0].ref, segs[0].cands, stats, stream=stream)
+        else:
+            chk.check_segmented(seg_descs, stats, P, stream=stream)
+
+    def step(ev=None):
+        if ev is not None:
+            ev[0].record(stream)
+        check()
+        if ev is not None:
+            ev[1].record(stream)
+        chk.fitness(w.timings, w.baseline, stats, summary, stream=stream)
+        if ev is not None:
+            ev[2].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_per_step = wall * 1e3 / args.steps
+    check_ms = sorted(e[0].elapsed_time(e[1]) for e in events)
+    fit_ms = sorted(e[1].elapsed_time(e[2]) for e in events)
+    check_avg = sum(check_ms) / len(check_ms)
+    alg_bytes = w.algorithmic_bytes
+    achieved = alg_bytes / (check_avg * 1e-3) / 1e9
+
+    out = {
+        "metric": METRIC,
+        "value": w.cand_elems / (wall / args.steps),
+        "unit": "cand-elem/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16->f32" if segs[0].dtype_name == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "P": P, "cand_elems": w.cand_elems,
+                   "algorithmic_bytes": alg_bytes, "T": int(w.timings.shape[1]),
+                   "atol": w.atol, "rtol": w.rtol,
+                   "entry": "evo_check_batch+evo_fitness" if seg_descs is None
+                   else "evo_check_segmented+evo_fitness"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "evo_check_kernel", "avg_ms": check_avg,
+                     "median_ms": check_ms[len(check_ms) // 2], "min_ms": check_ms[0]},
+        "fitness_kernel_us": {"avg": 1e3 * sum(fit_ms) / len(fit_ms),
+                              "median": 1e3 * fit_ms[len(fit_ms) // 2]},
+        "hbm_gbps_whole_step": alg_bytes / (wall / args.steps) / 1e9,
+    }
+
+    got = stats_to_numpy(stats)
+    pop = summary_to_numpy(summary)[0]
+    out["result"] = {"n_valid": int(pop["n_valid"]), "best_idx": int(pop["best_idx"]),
+                     "best_speedup": float(pop["best_speedup"]),
+                     "n_mismatch_total": int(got["n_mismatch"].sum())}
+
+    if not args.no_cpu_baseline:
+        base, rows, frac = cpu_baseline(w, int(args.cpu_budget_elems))
+        out["cpu_baseline"] = base
+        if frac >= 1.0:   # the sample was the whole population: report agreement too
+            same = all(int(g["n_mismatch"]) == r["n_mismatch"] and
+                       g["max_abs_err"].tobytes() == r["max_abs_err"].tobytes() and
+                       g["max_rel_err"].tobytes() == r["max_rel_err"].tobytes()
+                       for g, r in zip(got, rows))
+            out["cpu_baseline"]["agrees_with_gpu"] = bool(same)
+    chk.close()
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
