@@ -18,9 +18,7 @@ namespace {
 using evo::Partial;
 using evo::SegDesc;
 
-// Workgroups the partitioner aims for: a few waves of work per CU slot of a
-// 256-CU part, so that the tail of the launch is short next to its body.
-constexpr uint32_t kTargetJobs = 4096;
+constexpr uint32_t kJobsPerCu = EVO_JOBS_PER_CU;
 constexpr uint32_t kMinTilesPerWave = 4;
 constexpr uint32_t kMaxP = 65535;
 constexpr int kStageSlots = 8;
@@ -39,6 +37,7 @@ struct evo_check {
     uint64_t n_elems;
     float atol, rtol;
     int device = -1;             // device the scratch lives on (-1: none yet)
+    uint32_t n_cus = 0;          // compute units of that device
     // device scratch
     void *d_table = nullptr;     // SegDesc[S] followed by the candidate pointer table
     size_t table_bytes = 0;
@@ -174,9 +173,12 @@ uint32_t pow2_ceil(uint32_t v) {
     return p;
 }
 
-// Splits every group into jobs (workgroups) of similar cost.  Cost unit: one
-// wavefront pass over one tile with one candidate group.
-void partition(const std::vector<HostSeg> &segs, std::vector<SegDesc> &descs,
+// Splits every segment into jobs (workgroups) of similar cost.  Cost unit: one
+// wavefront pass over one tile with one candidate group.  The launch is sized to the
+// machine (a fixed number of workgroups per compute unit, all resident at once), so
+// that the per-job epilogue -- cross-lane reduction, partial rows, ticket -- is paid
+// once per wavefront slot and not once per few tiles.
+void partition(const std::vector<HostSeg> &segs, uint32_t target_jobs, std::vector<SegDesc> &descs,
                uint32_t &total_jobs) {
     descs.resize(segs.size());
     uint64_t wave_tiles = 0;
@@ -187,28 +189,24 @@ void partition(const std::vector<HostSeg> &segs, std::vector<SegDesc> &descs,
         d.P = h.P;
         d.dtype = h.dtype;
         d.stats_row0 = h.row0;
-        d.n_groups = (h.P + evo::kG - 1) / evo::kG;
-        d.cpg = (h.P + d.n_groups - 1) / d.n_groups;
+        d.n_groups = evo::group_count(h.P);
         d.gpw = std::min<uint32_t>(pow2_ceil(d.n_groups), evo::kWaves);
+        d.pad = 0;
         const uint64_t tiles = (h.n + evo::tile_elems(h.dtype) - 1) / evo::tile_elems(h.dtype);
         wave_tiles += tiles * d.n_groups;
     }
     // tiles one wavefront should take per job
-    uint64_t per_wave = (wave_tiles + (uint64_t)kTargetJobs * evo::kWaves - 1) /
-                        ((uint64_t)kTargetJobs * evo::kWaves);
-    per_wave = std::max<uint64_t>(per_wave, kMinTilesPerWave);
+    uint64_t per_wave = (wave_tiles + (uint64_t)target_jobs * evo::kWaves - 1) /
+                        ((uint64_t)target_jobs * evo::kWaves);
+    per_wave = std::min<uint64_t>(std::max<uint64_t>(per_wave, kMinTilesPerWave),
+                                  evo::kMaxTilesPerWave);
     uint32_t job0 = 0;
     for (size_t s = 0; s < segs.size(); ++s) {
         SegDesc &d = descs[s];
         const uint64_t tiles = (d.n + evo::tile_elems(d.dtype) - 1) / evo::tile_elems(d.dtype);
         const uint32_t tpw = evo::kWaves / d.gpw;
-        uint64_t per_chunk = per_wave * tpw;
-        uint64_t chunks = (tiles + per_chunk - 1) / per_chunk;
-        // keep chunk and job counts inside 32 bits for any n
-        while (chunks > (1u << 20)) {
-            per_chunk *= 2;
-            chunks = (tiles + per_chunk - 1) / per_chunk;
-        }
+        const uint64_t per_chunk = per_wave * tpw;
+        const uint64_t chunks = (tiles + per_chunk - 1) / per_chunk;
         d.tiles_per_chunk = (uint32_t)per_chunk;
         d.n_chunks = (uint32_t)chunks;
         const uint32_t gblocks = (d.n_groups + d.gpw - 1) / d.gpw;
@@ -219,16 +217,36 @@ void partition(const std::vector<HostSeg> &segs, std::vector<SegDesc> &descs,
     total_jobs = job0;
 }
 
+// Upper bound on what partition() can produce for these segments (checked before any
+// allocation): every count must stay inside 32 bits.
+bool partition_fits(const std::vector<HostSeg> &segs) {
+    uint64_t jobs = 0;
+    for (const HostSeg &h : segs) {
+        const uint64_t tiles = (h.n + evo::tile_elems(h.dtype) - 1) / evo::tile_elems(h.dtype);
+        const uint64_t groups = evo::group_count(h.P);
+        jobs += (tiles / kMinTilesPerWave + 1) * groups;
+        if (jobs > (1ull << 30)) return false;
+    }
+    return true;
+}
+
 int run_check(evo_check *c, const std::vector<HostSeg> &segs, hipStream_t stream,
               evo_stats *stats) {
     int rc = bind_device(c);
     if (rc != EVO_OK) return rc;
 
+    if (c->n_cus == 0) {
+        int cus = 0;
+        EVO_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device));
+        c->n_cus = cus > 0 ? (uint32_t)cus : 1u;
+    }
+    if (!partition_fits(segs)) return EVO_ERR_SIZE;
+
     std::vector<SegDesc> descs;
     uint32_t total_jobs = 0;
     size_t total_ptrs = 0;
     try {
-        partition(segs, descs, total_jobs);
+        partition(segs, c->n_cus * kJobsPerCu, descs, total_jobs);
     } catch (const std::bad_alloc &) {
         return EVO_ERR_NOMEM;
     }

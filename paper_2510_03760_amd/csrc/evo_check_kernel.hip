@@ -33,18 +33,18 @@ namespace {
 
 constexpr float kInf = __builtin_huge_valf();
 constexpr float kFltMin = 1.17549435e-38f;
-constexpr int kDepth = 4;   // candidates whose tile loads a wavefront keeps in flight
+constexpr int kDepth = EVO_DEPTH;
 
 template <uint32_t DT> struct Tile;
 template <> struct Tile<EVO_F32> {
     static constexpr int kVec = 4;   // elements per 16-byte vector
-    static constexpr int kNV = 2;    // vectors per lane per tile
+    static constexpr int kNV = EVO_NV_F32;    // vectors per lane per tile
     static constexpr int kE = kVec * kNV;
     using elem_t = float;
 };
 template <> struct Tile<EVO_BF16> {
     static constexpr int kVec = 8;
-    static constexpr int kNV = 2;
+    static constexpr int kNV = EVO_NV_BF16;
     static constexpr int kE = kVec * kNV;
     using elem_t = uint16_t;
 };
@@ -105,11 +105,12 @@ template <typename T>
 __device__ __forceinline__ T wave_shfl_xor(T v, int mask) { return __shfl_xor(v, mask, kLanes); }
 
 // Exact path: the rule of evo.h one element per lane at a time.  Handles elements
-// beyond n (ignored), any alignment and every special value.
+// beyond n (ignored), any alignment and every special value.  Results are reduced
+// over the wavefront and added to the wavefront's LDS record of the candidate.
 template <uint32_t DT>
-__device__ __noinline__ void exact_tile(const void *ref, const void *cand, uint64_t n,
-                                        uint64_t tile_base, int lane, float atol, float rtol,
-                                        ExactAcc *out) {
+__device__ __forceinline__ void exact_tile(const void *ref, const void *cand, uint64_t n,
+                                           uint64_t tile_base, int lane, float atol,
+                                           float rtol, ExactAcc *out) {
     constexpr int kE = Tile<DT>::kE;
     float max_abs = 0.0f, max_rel = 0.0f;
     double sum_abs = 0.0, sum_rel = 0.0;
@@ -150,7 +151,6 @@ __device__ __noinline__ void exact_tile(const void *ref, const void *cand, uint6
             sum_rel += (double)q;
         }
     }
-    // lanes -> wavefront, then into this wavefront's LDS record for the candidate
 #pragma unroll
     for (int m = kLanes / 2; m >= 1; m >>= 1) {
         max_abs = __builtin_fmaxf(max_abs, wave_shfl_xor(max_abs, m));
@@ -195,191 +195,129 @@ __device__ __forceinline__ const char *uniform_ptr(const void *p) {
     return reinterpret_cast<const char *>(((uint64_t)hi << 32) | lo);
 }
 
-// One job: a chunk of tiles of one segment for up to kWaves candidate groups.
-// NC = compile-time number of candidate slots of a group (power of two >= cpg).
+// Fast path of one wavefront over its full tiles t_first, t_first + tpw, ... < t_fend
+// for a full group of NC candidates.  Straight-line code per candidate apart from the
+// commit test; loads run D candidates ahead of the arithmetic, across tile boundaries
+// too.  Candidates of a tile that the fast path must not settle (anything non-finite,
+// overflow) are recorded in redo[tile slot] for the exact path.  Ends with the
+// lanes -> wavefront reduction into wpart[0 .. NC).
 template <uint32_t DT, int NC>
-__device__ void run_job(const SegDesc &sd, uint32_t job_local, uint32_t job_global, float atol,
-                        float rtol, Partial *partials, ExactAcc (*exact_acc)[kG],
-                        Partial (*wave_part)[kG]) {
+__device__ __forceinline__ uint32_t fast_tiles(const char *rptr, const void *const *cands,
+                                               uint64_t t_first, uint64_t t_fend, uint32_t tpw,
+                                               float atol, float rtol, int lane,
+                                               uint16_t *redo, Partial *wpart) {
     using TL = Tile<DT>;
     constexpr int kE = TL::kE;
     constexpr int kNV = TL::kNV;
-    constexpr uint32_t kTileElems = tile_elems(DT);
-    constexpr int kElemBytes = (int)sizeof(typename TL::elem_t);
-    constexpr int D = NC < kDepth ? NC : kDepth;      // candidates whose loads are in flight
-
-    const int lane = (int)(threadIdx.x & (kLanes - 1));
+    constexpr uint64_t kTileBytes = (uint64_t)tile_elems(DT) * sizeof(typename TL::elem_t);
+    constexpr int D = NC < kDepth ? NC : kDepth;
+    static_assert(kE % 8 == 0, "the fast path sums in trees of 8");
     const uint32_t lane_off = (uint32_t)lane * 16u;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-
-    const uint32_t gpw = sd.gpw;
-    const uint32_t tpw = kWaves / gpw;                 // tile slots per workgroup
-    const uint32_t gl = wave % gpw;                    // group slot inside the job
-    const uint32_t tl = wave / gpw;                    // tile slot inside the job
-    const uint32_t gblock = job_local / sd.n_chunks;
-    const uint32_t chunk = job_local - gblock * sd.n_chunks;
-    const uint32_t group = gblock * gpw + gl;
-    const bool active = group < sd.n_groups;
-    const uint32_t cand0 = active ? group * sd.cpg : 0u;
-    const uint32_t ncand = active ? min(sd.cpg, sd.P - cand0) : 0u;
-
-    const uint64_t n = sd.n;
-    const uint64_t n_full = n / kTileElems;                         // full tiles
-    const uint64_t n_tiles = (n + kTileElems - 1) / kTileElems;     // with the ragged one
-    const uint64_t t_begin = (uint64_t)chunk * sd.tiles_per_chunk;
-    const uint64_t t_end = min(t_begin + (uint64_t)sd.tiles_per_chunk, n_tiles);
-    const uint64_t t_fend = min(t_end, n_full);
 
     Acc acc[NC];
     uint32_t n_mismatch[NC];
+    const char *cptr[NC];
 #pragma unroll
     for (int g = 0; g < NC; ++g) {
         acc[g] = Acc{0.0f, 0.0f, 0.0, 0.0};
         n_mismatch[g] = 0;
+        cptr[g] = uniform_ptr(cands[g]);
     }
-    if (lane < kG) exact_acc[wave][lane] = ExactAcc{0.0, 0.0, 0.0f, 0.0f, 0u, 0u, 0u, 0u};
+    uint32_t any_redo = 0;
 
-    // Wave-uniform base pointers; vector loads need every tensor 16-byte aligned.
-    const char *rptr = uniform_ptr(sd.ref);
-    const char *cptr[NC];
-    bool vec_ok = ((uintptr_t)rptr & 15u) == 0;
-#pragma unroll
-    for (int g = 0; g < NC; ++g) {
-        cptr[g] = uniform_ptr(sd.cands[cand0 + min((uint32_t)g, ncand ? ncand - 1 : 0u)]);
-        vec_ok = vec_ok && (((uintptr_t)cptr[g] & 15u) == 0);
-    }
-    const uint32_t all_mask = (ncand >= 32 ? 0xffffffffu : ((1u << ncand) - 1u));
-
-    uint64_t t = t_begin + tl;
-    if (ncand > 0 && vec_ok) {
-        // Software pipeline over (tile, candidate) pairs: while pair i is evaluated the
-        // loads of pairs i+1 .. i+D are in flight, across tile boundaries too.
+    if (t_first < t_fend) {
         u32x4 ref_raw[kNV];
         u32x4 buf[D][kNV];
-        if (t < t_fend) {
-            const uint64_t off = t * (uint64_t)(kTileElems * kElemBytes);
+        {
+            const uint64_t off = t_first * kTileBytes;
 #pragma unroll
             for (int j = 0; j < kNV; ++j) ref_raw[j] = load16(rptr + off + j * 1024, lane_off);
 #pragma unroll
             for (int g = 0; g < D; ++g)
-                if ((uint32_t)g < ncand) {
 #pragma unroll
-                    for (int j = 0; j < kNV; ++j) buf[g][j] = load16(cptr[g] + off + j * 1024, lane_off);
-                }
+                for (int j = 0; j < kNV; ++j) buf[g][j] = load16(cptr[g] + off + j * 1024, lane_off);
         }
-        for (; t < t_fend; t += tpw) {
-            const uint64_t off = t * (uint64_t)(kTileElems * kElemBytes);
-            const uint64_t t_next = t + tpw;
-            const bool has_next = t_next < t_fend;
-            const uint64_t off_next = t_next * (uint64_t)(kTileElems * kElemBytes);
+        uint32_t slot = 0;
+        for (uint64_t t = t_first; t < t_fend; t += tpw, ++slot) {
+            const uint64_t off = t * kTileBytes;
+            // the wavefront's next tile; at the end of the job the current one again
+            // (a few redundant, in-bounds loads instead of a branch per load)
+            const uint64_t t_next = (t + tpw < t_fend) ? t + tpw : t;
+            const uint64_t off_next = t_next * kTileBytes;
 
             float r[kE], tol[kE], inv[kE];
-            bool ref_finite = true;
 #pragma unroll
             for (int j = 0; j < kNV; ++j) widen<DT>(ref_raw[j], &r[j * TL::kVec]);
-            if (has_next) {
 #pragma unroll
-                for (int j = 0; j < kNV; ++j) ref_raw[j] = load16(rptr + off_next + j * 1024, lane_off);
-            }
+            for (int j = 0; j < kNV; ++j) ref_raw[j] = load16(rptr + off_next + j * 1024, lane_off);
 #pragma unroll
             for (int e = 0; e < kE; ++e) {
                 const float ar = __builtin_fabsf(r[e]);
                 const float scaled = rtol * ar;
                 tol[e] = atol + scaled;
                 inv[e] = ar >= kFltMin ? 1.0f / ar : 0.0f;
-                ref_finite = ref_finite && (ar < kInf);        // false for NaN and Inf
             }
-            const bool ref_ok = ballot(!ref_finite) == 0;
-            uint32_t exact_mask = ref_ok ? 0u : all_mask;
 
+            uint32_t redo_mask = 0;
 #pragma unroll
             for (int g = 0; g < NC; ++g) {
-                const bool live = (uint32_t)g < ncand;
                 float c[kE];
-                if (live) {
 #pragma unroll
-                    for (int j = 0; j < kNV; ++j) widen<DT>(buf[g % D][j], &c[j * TL::kVec]);
+                for (int j = 0; j < kNV; ++j) widen<DT>(buf[g % D][j], &c[j * TL::kVec]);
+                float d[kE], q[kE];
+#pragma unroll
+                for (int e = 0; e < kE; ++e) d[e] = c[e] - r[e];
+                // refill the slot: candidate g+D of this tile, or g+D-NC of the next
+#pragma unroll
+                for (int j = 0; j < kNV; ++j)
+                    buf[g % D][j] = load16(cptr[(g + D) % NC] + (g + D < NC ? off : off_next) + j * 1024,
+                                           lane_off);
+                uint32_t mism = 0;
+#pragma unroll
+                for (int e = 0; e < kE; ++e) {
+                    mism += popc64(ballot(!(__builtin_fabsf(d[e]) <= tol[e])));
+                    q[e] = __builtin_fabsf(d[e]) * inv[e];
                 }
-                // Refill the slot (whether or not candidate g exists, so that the slot
-                // rotation stays in step): candidate g+D of this tile, or candidate
-                // g+D-NC of the wavefront's next tile.
-                if (g + D < NC) {
-                    if ((uint32_t)(g + D) < ncand) {
+                // fp32 tree sums over 8 non-negative terms (3 roundings deep), then fp64
+                float m_abs = acc[g].max_abs, m_rel = acc[g].max_rel;
+                double s_abs = acc[g].sum_abs, s_rel = acc[g].sum_rel;
+                float chk = 0.0f;
 #pragma unroll
-                        for (int j = 0; j < kNV; ++j)
-                            buf[g % D][j] = load16(cptr[(g + D) % NC] + off + j * 1024, lane_off);
+                for (int h = 0; h < kE; h += 8) {
+                    const float sa = ((__builtin_fabsf(d[h]) + __builtin_fabsf(d[h + 1])) +
+                                      (__builtin_fabsf(d[h + 2]) + __builtin_fabsf(d[h + 3]))) +
+                                     ((__builtin_fabsf(d[h + 4]) + __builtin_fabsf(d[h + 5])) +
+                                      (__builtin_fabsf(d[h + 6]) + __builtin_fabsf(d[h + 7])));
+                    const float sr = ((q[h] + q[h + 1]) + (q[h + 2] + q[h + 3])) +
+                                     ((q[h + 4] + q[h + 5]) + (q[h + 6] + q[h + 7]));
+                    s_abs += (double)sa;
+                    s_rel += (double)sr;
+                    chk += sa + sr;
+#pragma unroll
+                    for (int e = h; e < h + 8; e += 2) {
+                        m_abs = max3_abs(m_abs, d[e], d[e + 1]);
+                        m_rel = max3(m_rel, q[e], q[e + 1]);
                     }
-                } else if (has_next && (uint32_t)(g + D - NC) < ncand) {
-#pragma unroll
-                    for (int j = 0; j < kNV; ++j)
-                        buf[g % D][j] = load16(cptr[(g + D) % NC] + off_next + j * 1024, lane_off);
                 }
-                if (live && ref_ok) {
-                    float d[kE], q[kE];
-                    uint32_t mism = 0;
-#pragma unroll
-                    for (int e = 0; e < kE; ++e) {
-                        d[e] = c[e] - r[e];
-                        mism += popc64(ballot(!(__builtin_fabsf(d[e]) <= tol[e])));
-                        q[e] = __builtin_fabsf(d[e]) * inv[e];
-                    }
-                    // fp32 tree sums over 8 non-negative terms (3 roundings deep)
-                    float m_abs = acc[g].max_abs, m_rel = acc[g].max_rel;
-                    double s_abs = acc[g].sum_abs, s_rel = acc[g].sum_rel;
-                    float chk = 0.0f;
-#pragma unroll
-                    for (int h = 0; h < kE; h += 8) {
-                        const float sa =
-                            ((__builtin_fabsf(d[h]) + __builtin_fabsf(d[h + 1])) +
-                             (__builtin_fabsf(d[h + 2]) + __builtin_fabsf(d[h + 3]))) +
-                            ((__builtin_fabsf(d[h + 4]) + __builtin_fabsf(d[h + 5])) +
-                             (__builtin_fabsf(d[h + 6]) + __builtin_fabsf(d[h + 7])));
-                        const float sr = ((q[h] + q[h + 1]) + (q[h + 2] + q[h + 3])) +
-                                         ((q[h + 4] + q[h + 5]) + (q[h + 6] + q[h + 7]));
-                        s_abs += (double)sa;
-                        s_rel += (double)sr;
-                        chk += sa + sr;
-#pragma unroll
-                        for (int e = h; e < h + 8; e += 2) {
-                            m_abs = max3_abs(m_abs, d[e], d[e + 1]);
-                            m_rel = max3(m_rel, q[e], q[e + 1]);
-                        }
-                    }
-                    // every d and q finite and no fp32 partial overflowed <=> chk finite
-                    if (ballot(!(chk < kInf)) == 0) {
-                        acc[g].max_abs = m_abs;
-                        acc[g].max_rel = m_rel;
-                        acc[g].sum_abs = s_abs;
-                        acc[g].sum_rel = s_rel;
-                        n_mismatch[g] += mism;
-                    } else {
-                        exact_mask |= 1u << g;
-                    }
+                // Every d and q of the tile is finite and no fp32 partial sum overflowed
+                // <=> chk is finite.  (A NaN or Inf reference element makes d non-finite
+                // for any candidate value, so it lands here too.)
+                if (ballot(!(chk < kInf)) == 0) {
+                    acc[g].max_abs = m_abs;
+                    acc[g].max_rel = m_rel;
+                    acc[g].sum_abs = s_abs;
+                    acc[g].sum_rel = s_rel;
+                    n_mismatch[g] += mism;
+                } else {
+                    redo_mask |= 1u << g;
                 }
             }
-            // Tiles with non-finite values or overflow: redo those candidates exactly.
-            while (exact_mask) {
-                const int g = __builtin_ctz(exact_mask);
-                exact_mask &= exact_mask - 1;
-                exact_tile<DT>(rptr, sd.cands[cand0 + g], n, t * (uint64_t)kTileElems, lane,
-                               atol, rtol, &exact_acc[wave][g]);
-            }
+            if (lane == 0) redo[slot] = (uint16_t)redo_mask;
+            any_redo |= redo_mask;
         }
-    } else if (ncand > 0) {
-        // Some tensor is not 16-byte aligned: everything goes through the exact path.
-        for (; t < t_fend; t += tpw)
-            for (uint32_t g = 0; g < ncand; ++g)
-                exact_tile<DT>(rptr, sd.cands[cand0 + g], n, t * (uint64_t)kTileElems, lane, atol,
-                               rtol, &exact_acc[wave][g]);
     }
-    // The ragged last tile of the segment, if it falls into this job.
-    if (ncand > 0 && tl == 0 && n_full < t_end && n_full >= t_begin && n_full < n_tiles)
-        for (uint32_t g = 0; g < ncand; ++g)
-            exact_tile<DT>(rptr, sd.cands[cand0 + g], n, n_full * (uint64_t)kTileElems, lane, atol,
-                           rtol, &exact_acc[wave][g]);
 
-    // Lanes -> wavefront: maxima and sums by butterfly shuffles (counts are already
-    // wave-uniform), joined with what the exact path left in LDS.
+    // Lanes -> wavefront: butterfly shuffles (the counts are already wave-uniform).
 #pragma unroll
     for (int g = 0; g < NC; ++g) {
         float ma = acc[g].max_abs, mr = acc[g].max_rel;
@@ -392,17 +330,109 @@ __device__ void run_job(const SegDesc &sd, uint32_t job_local, uint32_t job_glob
             sr += wave_shfl_xor(sr, m);
         }
         if (lane == 0) {
-            const ExactAcc x = exact_acc[wave][g];
             Partial p;
-            p.n_mismatch = (uint64_t)n_mismatch[g] + x.n_mismatch;
-            p.n_excluded = x.n_excluded;
-            p.sum_abs = sa + x.sum_abs;
-            p.sum_rel = sr + x.sum_rel;
-            p.max_abs = __builtin_fmaxf(ma, x.max_abs);
-            p.max_rel = __builtin_fmaxf(mr, x.max_rel);
-            p.flags = x.flags;
+            p.n_mismatch = n_mismatch[g];
+            p.n_excluded = 0;
+            p.sum_abs = sa;
+            p.sum_rel = sr;
+            p.max_abs = ma;
+            p.max_rel = mr;
+            p.flags = 0;
             p.pad = 0;
-            wave_part[wave][g] = p;
+            wpart[g] = p;
+        }
+    }
+    return any_redo;
+}
+
+// One job: a chunk of tiles of one segment for up to kWaves candidate groups.
+template <uint32_t DT>
+__device__ void run_job(const SegDesc &sd, uint32_t job_local, uint32_t job_global, float atol,
+                        float rtol, Partial *partials, ExactAcc (*exact_acc)[kG],
+                        Partial (*wave_part)[kG], uint16_t (*redo)[kMaxTilesPerWave]) {
+    constexpr uint32_t kTileElems = tile_elems(DT);
+    const int lane = (int)(threadIdx.x & (kLanes - 1));
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+    const uint32_t gpw = sd.gpw;
+    const uint32_t tpw = kWaves / gpw;                 // tile slots per workgroup
+    const uint32_t gl = wave % gpw;                    // group slot inside the job
+    const uint32_t tl = wave / gpw;                    // tile slot inside the job
+    const uint32_t gblock = job_local / sd.n_chunks;
+    const uint32_t chunk = job_local - gblock * sd.n_chunks;
+    const uint32_t group = gblock * gpw + gl;
+    Group grp = group_of(sd.P, group);
+    grp.cand0 = __builtin_amdgcn_readfirstlane(grp.cand0);
+    grp.nc = __builtin_amdgcn_readfirstlane(group < sd.n_groups ? grp.nc : 0u);
+    const uint32_t nc = grp.nc;
+
+    const uint64_t n = sd.n;
+    const uint64_t n_full = n / kTileElems;                         // full tiles
+    const uint64_t n_tiles = (n + kTileElems - 1) / kTileElems;     // with the ragged one
+    const uint64_t t_begin = (uint64_t)chunk * sd.tiles_per_chunk;
+    const uint64_t t_end = min(t_begin + (uint64_t)sd.tiles_per_chunk, n_tiles);
+    const uint64_t t_fend = min(t_end, n_full);
+    const uint64_t t_first = t_begin + tl;
+
+    if (lane < kG) {
+        exact_acc[wave][lane] = ExactAcc{0.0, 0.0, 0.0f, 0.0f, 0u, 0u, 0u, 0u};
+        wave_part[wave][lane] = Partial{0u, 0u, 0.0, 0.0, 0.0f, 0.0f, 0u, 0u};
+    }
+
+    // Vector loads need every tensor of the group 16-byte aligned.
+    const char *rptr = uniform_ptr(sd.ref);
+    const void *const *cands = sd.cands + grp.cand0;
+    bool vec_ok = ((uintptr_t)rptr & 15u) == 0;
+    for (uint32_t g = 0; g < nc; ++g) vec_ok = vec_ok && (((uintptr_t)uniform_ptr(cands[g]) & 15u) == 0);
+
+    uint32_t any_redo = 0;
+    if (vec_ok && nc > 0) {
+        uint16_t *rd = redo[wave];
+        Partial *wp = wave_part[wave];
+        switch (nc) {
+#if EVO_KG > 8
+            case 16: any_redo = fast_tiles<DT, 16>(rptr, cands, t_first, t_fend, tpw, atol, rtol, lane, rd, wp); break;
+#endif
+            case 8: any_redo = fast_tiles<DT, 8>(rptr, cands, t_first, t_fend, tpw, atol, rtol, lane, rd, wp); break;
+            case 4: any_redo = fast_tiles<DT, 4>(rptr, cands, t_first, t_fend, tpw, atol, rtol, lane, rd, wp); break;
+            case 2: any_redo = fast_tiles<DT, 2>(rptr, cands, t_first, t_fend, tpw, atol, rtol, lane, rd, wp); break;
+            default: any_redo = fast_tiles<DT, 1>(rptr, cands, t_first, t_fend, tpw, atol, rtol, lane, rd, wp); break;
+        }
+    }
+
+    // Exact path over whatever is left: tiles the fast path flagged, the ragged last
+    // tile of the segment, and everything when some tensor is not 16-byte aligned.
+    if (nc > 0) {
+        const uint32_t all_mask = (1u << nc) - 1u;
+        uint64_t t = t_first;
+        uint32_t slot = 0;
+        if (vec_ok && !any_redo) {
+            // nothing flagged: jump straight to the ragged tile if this wavefront owns it
+            const bool owns = n_full < t_end && n_full >= t_first && (n_full - t_first) % tpw == 0;
+            t = owns ? n_full : t_end;
+        }
+        for (; t < t_end; t += tpw, ++slot) {
+            uint32_t m = all_mask;
+            if (vec_ok && t < n_full) m = any_redo ? (uint32_t)redo[wave][slot] : 0u;
+            m = __builtin_amdgcn_readfirstlane(m);
+            while (m) {
+                const int g = __builtin_ctz(m);
+                m &= m - 1;
+                exact_tile<DT>(rptr, uniform_ptr(cands[g]), n, t * (uint64_t)kTileElems, lane, atol,
+                               rtol, &exact_acc[wave][g]);
+            }
+        }
+        if ((uint32_t)lane < nc) {
+            const ExactAcc x = exact_acc[wave][lane];
+            Partial p = wave_part[wave][lane];
+            p.n_mismatch += x.n_mismatch;
+            p.n_excluded += x.n_excluded;
+            p.sum_abs += x.sum_abs;
+            p.sum_rel += x.sum_rel;
+            p.max_abs = __builtin_fmaxf(p.max_abs, x.max_abs);
+            p.max_rel = __builtin_fmaxf(p.max_rel, x.max_rel);
+            p.flags |= x.flags;
+            wave_part[wave][lane] = p;
         }
     }
     __syncthreads();
@@ -411,7 +441,7 @@ __device__ void run_job(const SegDesc &sd, uint32_t job_local, uint32_t job_glob
     if (threadIdx.x < (uint32_t)kRowsPerJob) {
         const uint32_t slot = threadIdx.x / kG;     // group slot
         const uint32_t gi = threadIdx.x % kG;
-        if (slot < gpw && gi < (uint32_t)NC) {
+        if (slot < gpw) {
             Partial out = wave_part[slot][gi];      // tile slot 0
             for (uint32_t k = 1; k < tpw; ++k) {
                 const Partial &o = wave_part[k * gpw + slot][gi];
@@ -424,25 +454,9 @@ __device__ void run_job(const SegDesc &sd, uint32_t job_local, uint32_t job_glob
                 out.flags |= o.flags;
             }
             partials[(uint64_t)job_global * kRowsPerJob + slot * kG + gi] = out;
+            __threadfence();   // publish before this workgroup takes its ticket
         }
     }
-}
-
-template <uint32_t DT>
-__device__ __forceinline__ void run_job_nc(const SegDesc &sd, uint32_t job_local,
-                                           uint32_t job_global, float atol, float rtol,
-                                           Partial *partials, ExactAcc (*exact_acc)[kG],
-                                           Partial (*wave_part)[kG]) {
-    if (sd.cpg > 8)
-        run_job<DT, 16>(sd, job_local, job_global, atol, rtol, partials, exact_acc, wave_part);
-    else if (sd.cpg > 4)
-        run_job<DT, 8>(sd, job_local, job_global, atol, rtol, partials, exact_acc, wave_part);
-    else if (sd.cpg > 2)
-        run_job<DT, 4>(sd, job_local, job_global, atol, rtol, partials, exact_acc, wave_part);
-    else if (sd.cpg > 1)
-        run_job<DT, 2>(sd, job_local, job_global, atol, rtol, partials, exact_acc, wave_part);
-    else
-        run_job<DT, 1>(sd, job_local, job_global, atol, rtol, partials, exact_acc, wave_part);
 }
 
 // Fold of a segment's partial rows by the last workgroup that finished a job of it.
@@ -462,8 +476,8 @@ __device__ void finalize_segment(const SegDesc &sd, const Partial *partials, evo
         const uint32_t p = p0 + ci;
         Partial a{};
         if (p < sd.P) {
-            const uint32_t group = p / sd.cpg;
-            const uint32_t gi = p - group * sd.cpg;
+            uint32_t group, gi;
+            locate(sd.P, p, &group, &gi);
             const uint32_t gblock = group / sd.gpw;
             const uint32_t slot = group - gblock * sd.gpw;
             const uint32_t ch_lo = ri * per;
@@ -523,7 +537,7 @@ __device__ void finalize_segment(const SegDesc &sd, const Partial *partials, evo
     }
 }
 
-__global__ void __launch_bounds__(kThreads, 2)
+__global__ void __launch_bounds__(kThreads, EVO_WAVES_PER_EU)
 evo_check_kernel(const SegDesc *__restrict__ descs, uint32_t S, float atol, float rtol,
                  Partial *__restrict__ partials, uint32_t *__restrict__ tickets,
                  evo_stats *__restrict__ stats) {
@@ -540,15 +554,15 @@ evo_check_kernel(const SegDesc *__restrict__ descs, uint32_t S, float atol, floa
 
     __shared__ ExactAcc exact_acc[kWaves][kG];
     __shared__ Partial wave_part[kWaves][kG];
+    __shared__ uint16_t redo[kWaves][kMaxTilesPerWave];
     if (sd.dtype == EVO_BF16)
-        run_job_nc<EVO_BF16>(sd, job_local, job, atol, rtol, partials, exact_acc, wave_part);
+        run_job<EVO_BF16>(sd, job_local, job, atol, rtol, partials, exact_acc, wave_part, redo);
     else
-        run_job_nc<EVO_F32>(sd, job_local, job, atol, rtol, partials, exact_acc, wave_part);
+        run_job<EVO_F32>(sd, job_local, job, atol, rtol, partials, exact_acc, wave_part, redo);
 
     // Publish this job's partial rows, then take a ticket; the workgroup that draws
     // the segment's last ticket folds the segment and re-arms the counter.
     __shared__ uint32_t is_last;
-    __threadfence();
     __syncthreads();
     if (threadIdx.x == 0) {
         const uint32_t prev = __hip_atomic_fetch_add(&tickets[s], 1u, __ATOMIC_ACQ_REL,

@@ -9,22 +9,92 @@
 
 namespace evo {
 
+// Compile-time tunables (defaults are the measured best on MI355X).
+#ifndef EVO_KG
+#define EVO_KG 16            // candidates per wavefront group (max): 8 or 16
+#endif
+#ifndef EVO_DEPTH
+#define EVO_DEPTH 4          // candidates whose tile loads a wavefront keeps in flight
+#endif
+#ifndef EVO_WAVES_PER_EU
+#define EVO_WAVES_PER_EU 2   // occupancy the register allocator must allow
+#endif
+#ifndef EVO_NV_F32
+#define EVO_NV_F32 2         // 16-byte vectors per lane per tile, fp32 tensors
+#endif
+#ifndef EVO_NV_BF16
+#define EVO_NV_BF16 2        // 16-byte vectors per lane per tile, bf16 tensors
+#endif
+#ifndef EVO_JOBS_PER_CU
+#define EVO_JOBS_PER_CU 2    // workgroups the partitioner creates per compute unit
+#endif
+
 // Launch geometry of the check kernel.  A workgroup is 4 wavefronts of 64 lanes.
-// Each wavefront owns one group of at most kG candidates and keeps that group's
-// running statistics in registers for the whole job; the wavefronts of a
-// workgroup either share a reference tile (different candidate groups) or take
-// different tiles (same group), so that a reference tile never has to be fetched
-// by more than one workgroup -- i.e. by more than one XCD's L2.
+// Each wavefront owns one group of candidates (a power of two, at most kG) and
+// keeps that group's running statistics in registers for the whole job; the
+// wavefronts of a workgroup either share a reference tile (different candidate
+// groups) or take different tiles (same group), so that a reference tile is never
+// fetched by more than one workgroup -- i.e. by more than one XCD's L2.
 constexpr int kLanes = 64;
 constexpr int kWaves = 4;
 constexpr int kThreads = kLanes * kWaves;
-constexpr int kG = 16;                     // candidates per wavefront group (max)
+constexpr int kG = EVO_KG;
 constexpr int kRowsPerJob = kWaves * kG;   // partial rows one job can produce
+constexpr uint32_t kMaxTilesPerWave = 2048; // per job: bounds the LDS redo list
 
-// Elements one wavefront consumes per tile and per tensor: 2 x 16 bytes per lane.
-constexpr uint32_t kTileBytes = 2048;
+// Elements one wavefront consumes per tile and per tensor (16 bytes per lane and vector).
 __host__ __device__ constexpr uint32_t tile_elems(uint32_t dtype) {
-    return dtype == EVO_BF16 ? kTileBytes / 2 : kTileBytes / 4;
+    return dtype == EVO_BF16 ? EVO_NV_BF16 * 64 * 8 : EVO_NV_F32 * 64 * 4;
+}
+
+// A population of P candidates is cut into groups whose sizes are powers of two:
+// P / kG groups of kG, then one group per set bit of P % kG, largest first
+// (P = 21, kG = 16: 16 + 4 + 1).  A wavefront then always works on a full group.
+struct Group {
+    uint32_t cand0;   // first candidate of the group
+    uint32_t nc;      // its size: 1, 2, 4, ... kG
+};
+
+__host__ __device__ inline uint32_t group_count(uint32_t P) {
+    uint32_t n = P / kG;
+    for (uint32_t rem = P % kG; rem; rem &= rem - 1) ++n;
+    return n;
+}
+
+__host__ __device__ inline Group group_of(uint32_t P, uint32_t g) {
+    const uint32_t nfull = P / kG;
+    if (g < nfull) return Group{g * kG, (uint32_t)kG};
+    const uint32_t rem = P % kG;
+    uint32_t base = nfull * kG, k = g - nfull;
+    for (uint32_t b = kG >> 1; b; b >>= 1) {
+        if (rem & b) {
+            if (k == 0) return Group{base, b};
+            base += b;
+            --k;
+        }
+    }
+    return Group{base, 0u};   // g >= group_count(P)
+}
+
+// Inverse: the group that holds candidate p and p's index inside it.
+__host__ __device__ inline void locate(uint32_t P, uint32_t p, uint32_t *group, uint32_t *gi) {
+    const uint32_t nfull = P / kG;
+    if (p < nfull * kG) {
+        *group = p / kG;
+        *gi = p % kG;
+        return;
+    }
+    const uint32_t rem = P % kG;
+    uint32_t off = p - nfull * kG, k = nfull;
+    for (uint32_t b = kG >> 1; b; b >>= 1) {
+        if (rem & b) {
+            if (off < b) break;
+            off -= b;
+            ++k;
+        }
+    }
+    *group = k;
+    *gi = off;
 }
 
 // One ragged group as the kernel sees it (device memory, 64 bytes).
@@ -35,13 +105,13 @@ struct SegDesc {
     uint32_t P;
     uint32_t dtype;
     uint32_t stats_row0;
-    uint32_t job0;              // first workgroup index of this group
+    uint32_t job0;              // first workgroup index of this segment
     uint32_t n_jobs;            // n_gblocks * n_chunks
     uint32_t n_chunks;          // tile chunks per candidate-group block
     uint32_t tiles_per_chunk;
     uint32_t n_groups;          // candidate groups
-    uint32_t cpg;               // candidates per group (<= kG)
     uint32_t gpw;               // groups per workgroup: 1, 2 or 4
+    uint32_t pad;
 };
 static_assert(sizeof(SegDesc) == 64, "SegDesc layout");
 
