@@ -207,8 +207,9 @@ void partition(const std::vector<HostSeg> &segs, uint32_t target_jobs, std::vect
         const uint32_t tpw = evo::kWaves / d.gpw;
         const uint64_t per_chunk = per_wave * tpw;
         const uint64_t chunks = (tiles + per_chunk - 1) / per_chunk;
-        d.tiles_per_chunk = (uint32_t)per_chunk;
         d.n_chunks = (uint32_t)chunks;
+        // tiles are dealt round-robin over chunks * tpw wavefront slots
+        d.tiles_per_wave = (uint32_t)((tiles + chunks * tpw - 1) / (chunks * tpw));
         const uint32_t gblocks = (d.n_groups + d.gpw - 1) / d.gpw;
         d.n_jobs = gblocks * d.n_chunks;
         d.job0 = job0;

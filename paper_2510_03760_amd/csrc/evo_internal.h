@@ -14,7 +14,7 @@ namespace evo {
 #define EVO_KG 16            // candidates per wavefront group (max): 8 or 16
 #endif
 #ifndef EVO_DEPTH
-#define EVO_DEPTH 4          // candidates whose tile loads a wavefront keeps in flight
+#define EVO_DEPTH 2          // candidates whose tile loads a wavefront keeps in flight
 #endif
 #ifndef EVO_WAVES_PER_EU
 #define EVO_WAVES_PER_EU 2   // occupancy the register allocator must allow
@@ -24,6 +24,12 @@ namespace evo {
 #endif
 #ifndef EVO_NV_BF16
 #define EVO_NV_BF16 2        // 16-byte vectors per lane per tile, bf16 tensors
+#endif
+#ifndef EVO_NT_LOADS
+#define EVO_NT_LOADS 1       // non-temporal loads for data that is read once
+#endif
+#ifndef EVO_ROTATE
+#define EVO_ROTATE 61        // per-step rotation of the workgroup -> tile map (0 = fixed map)
 #endif
 #ifndef EVO_JOBS_PER_CU
 #define EVO_JOBS_PER_CU 2    // workgroups the partitioner creates per compute unit
@@ -107,8 +113,8 @@ struct SegDesc {
     uint32_t stats_row0;
     uint32_t job0;              // first workgroup index of this segment
     uint32_t n_jobs;            // n_gblocks * n_chunks
-    uint32_t n_chunks;          // tile chunks per candidate-group block
-    uint32_t tiles_per_chunk;
+    uint32_t n_chunks;          // workgroups that share the tiles of one group block
+    uint32_t tiles_per_wave;    // upper bound on the tiles one wavefront visits
     uint32_t n_groups;          // candidate groups
     uint32_t gpw;               // groups per workgroup: 1, 2 or 4
     uint32_t pad;

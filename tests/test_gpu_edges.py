@@ -195,6 +195,35 @@ def test_repeatable_and_reusable_context(gu):
     chk.close()
 
 
+def test_alternating_populations_one_context(gu):
+    """Two different populations of the same shape go through one context in turn, with
+    no host synchronisation in between: every launch reuses the scratch rows of the
+    previous one, so a stale read of those rows would show up as the other result."""
+    _say("alternating")
+    from paper_2510_03760_amd.binding import stats_to_numpy
+    wa = _mixed(700001, 16, 21, torch.float32)
+    wb = _mixed(700001, 16, 22, torch.float32)
+    chk, stats_a, want_a = gu.check_parity(wa, label="alt-a")
+    sa, sb = wa.segments[0], wb.segments[0]
+    stats_b = chk.new_stats(16)
+    chk.check_batch(sb.ref, sb.cands, stats_b)
+    torch.cuda.synchronize()
+    want_b = gu.oracle_rows(sb, wb.atol, wb.rtol)
+    for p, (g, o) in enumerate(zip(stats_to_numpy(stats_b), want_b)):
+        gu.assert_rows_equal(g, o, "alt-b row %d" % p)
+    assert not torch.equal(stats_a, stats_b)
+    outs = []
+    for k in range(40):
+        o = chk.new_stats(16)
+        seg = sa if k % 2 == 0 else sb
+        chk.check_batch(seg.ref, seg.cands, o)
+        outs.append(o)
+    torch.cuda.synchronize()
+    for k, o in enumerate(outs):
+        assert torch.equal(o, stats_a if k % 2 == 0 else stats_b), "launch %d" % k
+    chk.close()
+
+
 @pytest.mark.parametrize("T", [1, 2, 3, 5, 64, 100, 101, 255, 256, 257, 1000, 1001, 4095, 4096])
 def test_fitness_T(gu, T):
     _say("fitness T=%d" % T)
