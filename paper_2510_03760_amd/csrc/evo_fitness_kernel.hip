@@ -7,13 +7,18 @@
 // Sec. 4.3.  Exact definitions are in evo.h (evo_fitness).
 //
 // One launch.  Workgroup p < P reduces timing row p, workgroup P reduces the baseline
-// row; each holds its row in LDS and finds the middle order statistics by rank
-// counting (the rank of sample i is the number of samples that are smaller, or equal
-// with a lower index -- unique per sample, so exactly one sample has each rank; no
-// sort, no data-dependent control flow).  The last workgroup to finish turns medians
-// into speedups and fitness and reduces the population figures.  The whole input is
-// at most a few tens of KiB: this kernel is bound by launch and dependency latency,
-// not by bandwidth.
+// row: the row is sorted in LDS by a bitonic network (padded with +Inf to a power of
+// two; O(T log^2 T) compare-exchanges, no data-dependent control flow) and the middle
+// order statistics are read off.  The last workgroup to finish turns medians into
+// speedups and fitness and reduces the population figures.  The whole input is at
+// most a few tens of KiB: this kernel is bound by launch and dependency latency, not
+// by bandwidth.
+//
+// The mean is defined as the binary64 sum of the samples IN SAMPLE ORDER.  When the
+// largest sample is below 2^16 times the smallest, every partial sum of at most 4096
+// binary32 values is exactly representable in binary64 (24 + 12 + 17 = 53 bits), so
+// the sum does not depend on the order and is taken by a parallel tree; otherwise one
+// thread adds the row sequentially.
 
 #include "evo_internal.h"
 
@@ -22,6 +27,7 @@ namespace {
 
 constexpr int kMaxPerThread = EVO_FITNESS_MAX_T / kThreads;   // 16 samples per thread
 constexpr uint32_t kQuietNan = 0x7fc00000u;
+constexpr float kInf = __builtin_huge_valf();
 
 struct Best {
     float fitness;
@@ -38,8 +44,8 @@ evo_fitness_kernel(const float *__restrict__ timings, const float *__restrict__ 
                    uint32_t P, uint32_t T, evo_stats *__restrict__ stats,
                    evo_pop_summary *__restrict__ summary, float *__restrict__ base_median,
                    uint32_t *__restrict__ ticket) {
-    __shared__ float samples[EVO_FITNESS_MAX_T];
-    __shared__ float mid[2];
+    __shared__ float sorted[EVO_FITNESS_MAX_T];
+    __shared__ double psum[kThreads];
     __shared__ uint32_t is_last;
     __shared__ Best best_lds[kThreads];
 
@@ -47,50 +53,47 @@ evo_fitness_kernel(const float *__restrict__ timings, const float *__restrict__ 
     const float *src = row < P ? timings + (uint64_t)row * T : baseline;
     const uint32_t tid = threadIdx.x;
 
-    // Row into LDS and into registers; usable iff every sample is finite and > 0.
-    float x[kMaxPerThread];
+    uint32_t Tpad = 2;
+    while (Tpad < T) Tpad <<= 1;
+
+    // Row into LDS (+Inf padding); per-thread binary64 sum of its own samples; usable
+    // iff every sample is finite and > 0.
+    double mysum = 0.0;
     int bad = 0;
-#pragma unroll
-    for (int e = 0; e < kMaxPerThread; ++e) {
-        const uint32_t i = tid + (uint32_t)e * kThreads;
-        x[e] = 0.0f;
+    for (uint32_t i = tid; i < Tpad; i += kThreads) {
+        float x = kInf;
         if (i < T) {
-            x[e] = src[i];
-            samples[i] = x[e];
-            if (!(x[e] > 0.0f) || x[e] == __builtin_huge_valf()) bad = 1;
+            x = src[i];
+            mysum += (double)x;
+            if (!(x > 0.0f) || x == kInf) bad = 1;
         }
+        sorted[i] = x;
     }
+    psum[tid] = mysum;
     const int row_bad = __syncthreads_or(bad);
 
-    // Rank counting against every sample, and the row sum in sample order (each
-    // thread carries the same sequential fp64 sum; thread 0 reports it).
-    const uint32_t per_thread = (T + kThreads - 1) / kThreads;
-    uint32_t rank[kMaxPerThread];
-#pragma unroll
-    for (int e = 0; e < kMaxPerThread; ++e) rank[e] = 0;
-    double sum = 0.0;
-    for (uint32_t j = 0; j < T; ++j) {
-        const float sj = samples[j];
-        sum += (double)sj;
-#pragma unroll
-        for (int e = 0; e < kMaxPerThread; ++e) {
-            if ((uint32_t)e < per_thread) {
-                const uint32_t i = tid + (uint32_t)e * kThreads;
-                rank[e] += (sj < x[e] || (sj == x[e] && j < i)) ? 1u : 0u;
+    // Bitonic sort, ascending.
+    for (uint32_t k = 2; k <= Tpad; k <<= 1) {
+        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+            for (uint32_t i = tid; i < (Tpad >> 1); i += kThreads) {
+                const uint32_t a = ((i & ~(j - 1)) << 1) | (i & (j - 1));
+                const uint32_t b = a | j;
+                const bool up = (a & k) == 0;
+                const float x = sorted[a], y = sorted[b];
+                if ((x > y) == up) {
+                    sorted[a] = y;
+                    sorted[b] = x;
+                }
             }
+            __syncthreads();
         }
     }
-    const uint32_t k_hi = T / 2;                         // middle (odd T) or upper middle
-    const uint32_t k_lo = (T & 1u) ? k_hi : k_hi - 1;    // lower middle for even T
-#pragma unroll
-    for (int e = 0; e < kMaxPerThread; ++e) {
-        const uint32_t i = tid + (uint32_t)e * kThreads;
-        if (i < T) {
-            if (rank[e] == k_hi) mid[1] = x[e];
-            if (rank[e] == k_lo) mid[0] = x[e];
-        }
+
+    // Tree sum of the per-thread sums (used only when it is exact, see the header).
+    for (uint32_t stride = kThreads / 2; stride >= 1; stride >>= 1) {
+        if (tid < stride) psum[tid] += psum[tid + stride];
+        __syncthreads();
     }
-    __syncthreads();
 
     if (tid == 0) {
         float median, mean;
@@ -98,11 +101,17 @@ evo_fitness_kernel(const float *__restrict__ timings, const float *__restrict__ 
             median = __builtin_bit_cast(float, kQuietNan);
             mean = median;
         } else {
+            const float hi = sorted[T / 2];
             if (T & 1u) {
-                median = mid[1];
+                median = hi;
             } else {
-                const float s = mid[0] + mid[1];
+                const float s = sorted[T / 2 - 1] + hi;
                 median = 0.5f * s;
+            }
+            double sum = psum[0];
+            if (!(sorted[T - 1] < sorted[0] * 65536.0f)) {
+                sum = 0.0;   // wide dynamic range: the defining order
+                for (uint32_t i = 0; i < T; ++i) sum += (double)src[i];
             }
             mean = (float)(sum / (double)T);
         }
@@ -112,12 +121,7 @@ evo_fitness_kernel(const float *__restrict__ timings, const float *__restrict__ 
         } else {
             *base_median = median;
         }
-    }
-
-    // Ticket: the last of the P+1 workgroups finishes the population.
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
+        __threadfence();   // publish before the ticket
         const uint32_t prev = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL,
                                                      __HIP_MEMORY_SCOPE_AGENT);
         is_last = (prev == P) ? 1u : 0u;
@@ -126,6 +130,7 @@ evo_fitness_kernel(const float *__restrict__ timings, const float *__restrict__ 
     if (!is_last) return;
     __threadfence();
 
+    // The last of the P+1 workgroups: speedups, fitness, population figures.
     const float bm = __hip_atomic_load(base_median, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const bool base_ok = bm == bm;
     Best mine{0.0f, P, 0u};

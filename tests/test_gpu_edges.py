@@ -258,6 +258,12 @@ def test_fitness_population_and_unusable_rows(gu):
         t[8, 0] = float("inf")
         t[9, 99] = 0.0
         t[10, 50] = -1.0
+        # dynamic range above 2^16: the mean has to be summed in sample order
+        t[30, ::2] = 1e-20
+        t[30, 1::2] = 3e20
+        t[31, 0] = 1e-6
+        t[32, 5] = 7e7
+        t[35] = t[35] * 1e-42    # subnormal samples (candidate 35 is not valid below)
         t[20] = t[11]            # equal fitness: the lower index must win if it is the best
         t[11] *= 0.25
         t[20] *= 0.25

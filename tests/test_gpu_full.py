@@ -1,0 +1,70 @@
+"""GPU parity at the full sizes of the five workloads, through the same entry points and
+launch configuration that bench.py times.  Every row is compared with the CPU oracle
+(large tensors are copied to the host and fed to the oracle in chunks)."""
+import time
+
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import synth  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def gu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_util
+    return gpu_util
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _full(gu, w, label):
+    t0 = time.time()
+    _say("%s: generated %s, checking on the GPU and on the CPU oracle" % (label, w.name))
+    chk, stats, want = gu.check_parity(w, label=label)
+    _say("%s: check rows agree (%.1f s), fitness" % (label, time.time() - t0))
+    got, pop, fit = gu.fitness_parity(chk, stats, w.timings, w.baseline, label=label)
+    chk.close()
+    return want, pop
+
+
+def test_config2_full(gu):
+    w = synth.dense_f32("cuda", side=8192, P=16, T=100)
+    want, pop = _full(gu, w, "C2")
+    seg = w.segments[0]
+    for p, r in enumerate(want):
+        if seg.corrupted[p]:
+            k = seg.notes["replaced"][p]
+            assert 0.98 * k <= r["n_mismatch"] <= k
+        else:
+            assert r["n_mismatch"] == 0
+    assert int(pop["n_valid"]) == 12
+
+
+def test_config3_full(gu):
+    w = synth.softmax_bf16("cuda", B=32, R=128, C=4096, P=64, T=100)
+    want, pop = _full(gu, w, "C3")
+    assert [r["valid"] for r in want] == [0 if (p % 8) == 7 else 1 for p in range(64)]
+    assert int(pop["n_valid"]) == 56
+
+
+def test_config4_full(gu):
+    w = synth.ragged_f32("cuda", P_s=32, T=100)
+    want, pop = _full(gu, w, "C4")
+    assert sum(r["valid"] for r in want) == 192 and int(pop["n_valid"]) == 192
+    assert sorted(set(r["n_elems"] for r in want)) == sorted(
+        [12845056, 16777216, 128, 1048576, 1204224, 262144, 2097152, 1000])
+
+
+def test_config5_full(gu):
+    w = synth.heavy_tail_f32("cuda", log2n=30, P=8, T=1000)
+    want, pop = _full(gu, w, "C5")
+    k = w.segments[0].notes["n_ref_nan"]
+    assert k == 1024
+    assert [r["n_mismatch"] for r in want] == [k, k, 2 * k, k, k, 2 * k, 3 * k, k]
+    assert int(pop["n_valid"]) == 0 and int(pop["best_idx"]) == 8
