@@ -27,6 +27,27 @@ METRIC = "candidate-elements validated/sec and achieved HBM GB/s vs MI355X peak"
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, vendor figure
 
 
+def measured_traffic(workload_name: str):
+    """HBM bytes per launch of the check kernel from the committed rocprofv3 counter
+    summary, or None when there is none for this workload or the kernel sources have
+    changed since the counters were taken."""
+    import glob
+    import hashlib
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as fh:
+            table = json.load(fh)
+        entry = table[workload_name]
+        h = hashlib.sha256()
+        for f in sorted(glob.glob(os.path.join(ROOT, "paper_2510_03760_amd", "csrc", "*"))):
+            with open(f, "rb") as src:
+                h.update(src.read())
+        if h.hexdigest()[:16] != entry["src_hash"]:
+            return None
+        return entry["traffic_bytes"]
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def build_workload(name: str):
     import synth
     if name == "c1":
@@ -191,7 +212,7 @@ def main() -> int:
                    "entry": "evo_check_batch+evo_fitness" if seg_descs is None
                    else "evo_check_segmented+evo_fitness"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
                      "kernel": "evo_check_kernel", "avg_ms": check_avg,
                      "median_ms": check_ms[len(check_ms) // 2], "min_ms": check_ms[0]},
         "fitness_kernel_us": {"avg": 1e3 * sum(fit_ms) / len(fit_ms),

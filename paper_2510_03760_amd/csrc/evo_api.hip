@@ -254,38 +254,50 @@ int run_check(evo_check *c, const std::vector<HostSeg> &segs, hipStream_t stream
     for (const HostSeg &h : segs) total_ptrs += h.P;
 
     const size_t S = segs.size();
-    const size_t desc_bytes = S * sizeof(SegDesc);
-    const size_t blob_bytes = desc_bytes + total_ptrs * sizeof(void *);
-
-    if ((rc = ensure_table(c, blob_bytes)) != EVO_OK) return rc;
     if ((rc = ensure_partials(c, (size_t)total_jobs * evo::kRowsPerJob)) != EVO_OK) return rc;
     if ((rc = ensure_tickets(c, S, stream)) != EVO_OK) return rc;
 
-    StageSlot *slot = nullptr;
-    if ((rc = acquire_slot(c, blob_bytes, &slot)) != EVO_OK) return rc;
-
-    // blob = descriptors, then all candidate pointers; descriptors point into the
-    // device copy of the pointer part
-    char *hb = static_cast<char *>(slot->host);
-    const void **hptrs = reinterpret_cast<const void **>(hb + desc_bytes);
-    const void *const *dptrs =
-        reinterpret_cast<const void *const *>(static_cast<char *>(c->d_table) + desc_bytes);
     size_t off = 0;
     for (size_t s = 0; s < S; ++s) {
         descs[s].ref = segs[s].ref;
-        descs[s].cands = dptrs + off;
-        for (uint32_t p = 0; p < segs[s].P; ++p) hptrs[off + p] = segs[s].cand_ptrs[p];
+        descs[s].ptr0 = off;
         off += segs[s].P;
     }
+
+    if (S <= evo::kInlineSegs && total_ptrs <= evo::kInlinePtrs) {
+        // everything fits into the kernel argument block: no staging, no copy
+        evo::InlineTable tab;
+        std::memset(&tab, 0, sizeof tab);
+        for (size_t s = 0; s < S; ++s) {
+            tab.descs[s] = descs[s];
+            for (uint32_t p = 0; p < segs[s].P; ++p)
+                tab.ptrs[descs[s].ptr0 + p] = reinterpret_cast<uint64_t>(segs[s].cand_ptrs[p]);
+        }
+        return dev(evo::launch_check_inline(tab, (uint32_t)S, total_jobs, c->atol, c->rtol,
+                                            c->d_partials, c->d_tickets, stats, stream));
+    }
+
+    // blob = descriptors, then all candidate pointers, staged through pinned memory
+    const size_t desc_bytes = S * sizeof(SegDesc);
+    const size_t blob_bytes = desc_bytes + total_ptrs * sizeof(uint64_t);
+    if ((rc = ensure_table(c, blob_bytes)) != EVO_OK) return rc;
+    StageSlot *slot = nullptr;
+    if ((rc = acquire_slot(c, blob_bytes, &slot)) != EVO_OK) return rc;
+    char *hb = static_cast<char *>(slot->host);
+    uint64_t *hptrs = reinterpret_cast<uint64_t *>(hb + desc_bytes);
+    for (size_t s = 0; s < S; ++s)
+        for (uint32_t p = 0; p < segs[s].P; ++p)
+            hptrs[descs[s].ptr0 + p] = reinterpret_cast<uint64_t>(segs[s].cand_ptrs[p]);
     std::memcpy(hb, descs.data(), desc_bytes);
 
     EVO_TRY(hipMemcpyAsync(c->d_table, hb, blob_bytes, hipMemcpyHostToDevice, stream));
     EVO_TRY(hipEventRecord(slot->done, stream));
     slot->in_flight = true;
 
-    return dev(evo::launch_check(static_cast<const SegDesc *>(c->d_table), (uint32_t)S,
-                                 total_jobs, c->atol, c->rtol, c->d_partials, c->d_tickets,
-                                 stats, stream));
+    return dev(evo::launch_check(
+        static_cast<const SegDesc *>(c->d_table),
+        reinterpret_cast<const uint64_t *>(static_cast<char *>(c->d_table) + desc_bytes), (uint32_t)S,
+        total_jobs, c->atol, c->rtol, c->d_partials, c->d_tickets, stats, stream));
 }
 
 }  // namespace

@@ -393,8 +393,9 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_p
 
 // One job: a chunk of tiles of one segment for up to kWaves candidate groups.
 template <uint32_t DT>
-__device__ void run_job(const SegDesc &sd, uint32_t job_local, uint32_t job_global, float atol,
-                        float rtol, Partial *partials, ExactAcc (*exact_acc)[kG],
+__device__ void run_job(const SegDesc &sd, const uint64_t *ptr_table, uint32_t job_local,
+                        uint32_t job_global, float atol, float rtol, Partial *partials,
+                        ExactAcc (*exact_acc)[kG],
                         Partial (*wave_part)[kG], uint16_t (*redo)[kMaxTilesPerWave]) {
     constexpr uint32_t kTileElems = tile_elems(DT);
     const int lane = (int)(threadIdx.x & (kLanes - 1));
@@ -428,7 +429,7 @@ __device__ void run_job(const SegDesc &sd, uint32_t job_local, uint32_t job_glob
     uint64_t cand_ptr_of_lane = 0;
     if ((uint32_t)lane < nc) {
         typedef __attribute__((address_space(1))) const uint64_t global_u64;
-        cand_ptr_of_lane = ((global_u64 *)(uintptr_t)sd.cands)[grp.cand0 + lane];
+        cand_ptr_of_lane = ((global_u64 *)(uintptr_t)ptr_table)[sd.ptr0 + grp.cand0 + lane];
     }
     const bool vec_ok = ((uintptr_t)rptr & 15u) == 0 && ballot((cand_ptr_of_lane & 15u) != 0) == 0;
 
@@ -600,10 +601,9 @@ __device__ void finalize_segment(const SegDesc &sd, const Partial *partials, evo
     }
 }
 
-__global__ void __launch_bounds__(kThreads, EVO_WAVES_PER_EU)
-evo_check_kernel(const SegDesc *__restrict__ descs, uint32_t S, float atol, float rtol,
-                 Partial *__restrict__ partials, uint32_t *__restrict__ tickets,
-                 evo_stats *__restrict__ stats) {
+__device__ __forceinline__ void check_body(const SegDesc *descs, const uint64_t *ptr_table,
+                                           uint32_t S, float atol, float rtol, Partial *partials,
+                                           uint32_t *tickets, evo_stats *stats) {
     // Which segment does this workgroup belong to?  (job0 is ascending.)
     const uint32_t job = blockIdx.x;
     uint32_t lo = 0, hi = S;
@@ -619,12 +619,13 @@ evo_check_kernel(const SegDesc *__restrict__ descs, uint32_t S, float atol, floa
     __shared__ Partial wave_part[kWaves][kG];
     __shared__ uint16_t redo[kWaves][kMaxTilesPerWave];
     if (sd.dtype == EVO_BF16)
-        run_job<EVO_BF16>(sd, job_local, job, atol, rtol, partials, exact_acc, wave_part, redo);
+        run_job<EVO_BF16>(sd, ptr_table, job_local, job, atol, rtol, partials, exact_acc, wave_part, redo);
     else
-        run_job<EVO_F32>(sd, job_local, job, atol, rtol, partials, exact_acc, wave_part, redo);
+        run_job<EVO_F32>(sd, ptr_table, job_local, job, atol, rtol, partials, exact_acc, wave_part, redo);
 
-    // Publish this job's partial rows, then take a ticket; the workgroup that draws
-    // the segment's last ticket folds the segment and re-arms the counter.
+    // This job's partial rows are published (run_job fences after writing them); take a
+    // ticket.  The workgroup that draws the segment's last ticket folds the segment
+    // and re-arms the counter.
     __shared__ uint32_t is_last;
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -641,13 +642,40 @@ evo_check_kernel(const SegDesc *__restrict__ descs, uint32_t S, float atol, floa
     }
 }
 
+__global__ void __launch_bounds__(kThreads, EVO_WAVES_PER_EU)
+evo_check_kernel(const SegDesc *__restrict__ descs, const uint64_t *__restrict__ ptr_table,
+                 uint32_t S, float atol, float rtol, Partial *__restrict__ partials,
+                 uint32_t *__restrict__ tickets, evo_stats *__restrict__ stats) {
+    check_body(descs, ptr_table, S, atol, rtol, partials, tickets, stats);
+}
+
+// Same kernel with the table inside the kernel argument block.  The block is read in
+// place through the kernel-argument segment pointer (the table is the first argument,
+// at offset 0); naming the by-value parameter would make the compiler copy all of it
+// into per-lane scratch memory.
+__global__ void __launch_bounds__(kThreads, EVO_WAVES_PER_EU)
+evo_check_kernel_inline(const InlineTable /*read via the segment pointer*/, uint32_t S, float atol,
+                        float rtol, Partial *__restrict__ partials,
+                        uint32_t *__restrict__ tickets, evo_stats *__restrict__ stats) {
+    const InlineTable *tab = (const InlineTable *)__builtin_amdgcn_kernarg_segment_ptr();
+    check_body(tab->descs, tab->ptrs, S, atol, rtol, partials, tickets, stats);
+}
+
 }  // namespace
 
-hipError_t launch_check(const SegDesc *d_descs, uint32_t S, uint32_t total_jobs, float atol,
-                        float rtol, Partial *partials, uint32_t *tickets, evo_stats *stats,
-                        hipStream_t stream) {
-    hipLaunchKernelGGL(evo_check_kernel, dim3(total_jobs), dim3(kThreads), 0, stream, d_descs, S,
-                       atol, rtol, partials, tickets, stats);
+hipError_t launch_check(const SegDesc *d_descs, const uint64_t *d_ptrs, uint32_t S,
+                        uint32_t total_jobs, float atol, float rtol, Partial *partials,
+                        uint32_t *tickets, evo_stats *stats, hipStream_t stream) {
+    hipLaunchKernelGGL(evo_check_kernel, dim3(total_jobs), dim3(kThreads), 0, stream, d_descs,
+                       d_ptrs, S, atol, rtol, partials, tickets, stats);
+    return hipGetLastError();
+}
+
+hipError_t launch_check_inline(const InlineTable &tab, uint32_t S, uint32_t total_jobs,
+                               float atol, float rtol, Partial *partials, uint32_t *tickets,
+                               evo_stats *stats, hipStream_t stream) {
+    hipLaunchKernelGGL(evo_check_kernel_inline, dim3(total_jobs), dim3(kThreads), 0, stream, tab,
+                       S, atol, rtol, partials, tickets, stats);
     return hipGetLastError();
 }
 

@@ -25,7 +25,6 @@
 namespace evo {
 namespace {
 
-constexpr int kMaxPerThread = EVO_FITNESS_MAX_T / kThreads;   // 16 samples per thread
 constexpr uint32_t kQuietNan = 0x7fc00000u;
 constexpr float kInf = __builtin_huge_valf();
 

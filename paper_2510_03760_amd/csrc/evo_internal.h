@@ -106,7 +106,7 @@ __host__ __device__ inline void locate(uint32_t P, uint32_t p, uint32_t *group, 
 // One ragged group as the kernel sees it (device memory, 64 bytes).
 struct SegDesc {
     const void *ref;
-    const void *const *cands;   // device array of P pointers
+    uint64_t ptr0;              // index of the segment's first candidate pointer in the table
     uint64_t n;                 // elements per tensor
     uint32_t P;
     uint32_t dtype;
@@ -134,9 +134,24 @@ struct Partial {
 };
 static_assert(sizeof(Partial) == 48, "Partial layout");
 
-hipError_t launch_check(const SegDesc *d_descs, uint32_t S, uint32_t total_jobs, float atol,
-                        float rtol, Partial *partials, uint32_t *tickets, evo_stats *stats,
-                        hipStream_t stream);
+// Small launches carry their descriptors and candidate pointers in the kernel
+// argument block itself (no staging copy precedes the kernel); larger ones read them
+// from a device table.
+constexpr uint32_t kInlineSegs = 8;
+constexpr uint32_t kInlinePtrs = 384;
+struct InlineTable {
+    SegDesc descs[kInlineSegs];
+    uint64_t ptrs[kInlinePtrs];
+};
+static_assert(sizeof(InlineTable) <= 3600, "kernel argument block must stay below 4 KiB");
+
+hipError_t launch_check(const SegDesc *d_descs, const uint64_t *d_ptrs, uint32_t S,
+                        uint32_t total_jobs, float atol, float rtol, Partial *partials,
+                        uint32_t *tickets, evo_stats *stats, hipStream_t stream);
+
+hipError_t launch_check_inline(const InlineTable &tab, uint32_t S, uint32_t total_jobs,
+                               float atol, float rtol, Partial *partials, uint32_t *tickets,
+                               evo_stats *stats, hipStream_t stream);
 
 hipError_t launch_fitness(const float *timings, const float *baseline, uint32_t P, uint32_t T,
                           evo_stats *stats, evo_pop_summary *summary, float *base_median,
