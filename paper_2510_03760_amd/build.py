@@ -35,11 +35,27 @@ def sources() -> list:
     return [os.path.join(CSRC, s) for s in SOURCES]
 
 
+RCP_CHECK_PATH = os.path.join(_PKG, "rcp_check")
+
+
+def build_rcp_check() -> str:
+    """Compiles the stand-alone device check of the reciprocal shortcut (evo_rcp.h)."""
+    tmp = RCP_CHECK_PATH + ".tmp.%d" % os.getpid()
+    flags = [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC", "-fvisibility=hidden")]
+    cmd = [hipcc(), *flags, "-I", CSRC, "-o", tmp, os.path.join(CSRC, "rcp_check.hip")]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout)
+    os.replace(tmp, RCP_CHECK_PATH)
+    return RCP_CHECK_PATH
+
+
 def is_stale() -> bool:
     if not os.path.exists(LIB_PATH):
         return True
     built = os.path.getmtime(LIB_PATH)
-    deps = sources() + [os.path.join(CSRC, "evo_internal.h"), os.path.join(INCLUDE, "evo.h")]
+    deps = sources() + [os.path.join(CSRC, "evo_internal.h"), os.path.join(CSRC, "evo_rcp.h"),
+                        os.path.join(INCLUDE, "evo.h")]
     return any(os.path.getmtime(d) > built for d in deps)
 
 
@@ -59,6 +75,8 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     if verbose and out.strip():
         print(out)
     os.replace(tmp, LIB_PATH)
+    if not extra_flags:
+        build_rcp_check()
     return LIB_PATH
 
 

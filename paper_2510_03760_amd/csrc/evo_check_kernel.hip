@@ -27,6 +27,7 @@
 // then fp64), which stays far inside the 1e-6 relative budget of evo_stats.
 
 #include "evo_internal.h"
+#include "evo_rcp.h"
 
 namespace evo {
 namespace {
@@ -198,6 +199,16 @@ __device__ __forceinline__ float max3(float m, float a, float b) {
     return o;
 }
 
+// Pairwise sum of N values (of their magnitudes when ABS), N a power of two.
+template <int N, bool ABS>
+__device__ __forceinline__ float tree_sum(const float *v) {
+    if constexpr (N == 1) {
+        return ABS ? __builtin_fabsf(v[0]) : v[0];
+    } else {
+        return tree_sum<N / 2, ABS>(v) + tree_sum<N / 2, ABS>(v + N / 2);
+    }
+}
+
 __device__ __forceinline__ const char *uniform_ptr(const void *p) {
     const uint64_t v = reinterpret_cast<uint64_t>(p);
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
@@ -248,7 +259,8 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_p
     constexpr int kNV = TL::kNV;
     constexpr uint64_t kTileBytes = (uint64_t)tile_elems(DT) * sizeof(typename TL::elem_t);
     constexpr int D = NC < kDepth ? NC : kDepth;
-    static_assert(kE % 8 == 0, "the fast path sums in trees of 8");
+    static_assert(kE >= 2 && (kE & (kE - 1)) == 0 && kE <= 16,
+                  "pairwise fp32 trees: at most 4 roundings deep keeps the sums inside 1e-6");
     const uint32_t lane_off = (uint32_t)lane * 16u;
 
     Acc acc[NC];
@@ -288,12 +300,21 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_p
             for (int j = 0; j < kNV; ++j) widen<DT>(ref_raw[j], &r[j * TL::kVec]);
 #pragma unroll
             for (int j = 0; j < kNV; ++j) ref_raw[j] = load16<REF_STREAM>(rptr + off_next + j * 1024, lane_off);
+            bool huge = false;
 #pragma unroll
             for (int e = 0; e < kE; ++e) {
                 const float ar = __builtin_fabsf(r[e]);
                 const float scaled = rtol * ar;
                 tol[e] = atol + scaled;
-                inv[e] = ar >= kFltMin ? 1.0f / ar : 0.0f;
+                inv[e] = ar >= kFltMin ? recip_shortcut(ar) : 0.0f;
+                huge = huge || !(ar < kRecipShortcutBelow);
+            }
+            if (ballot(huge) != 0) {   // |r| >= 2^126 somewhere in the tile: true division
+#pragma unroll
+                for (int e = 0; e < kE; ++e) {
+                    const float ar = __builtin_fabsf(r[e]);
+                    inv[e] = ar >= kFltMin ? 1.0f / ar : 0.0f;
+                }
             }
 
             uint32_t redo_mask = 0;
@@ -316,26 +337,18 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_p
                     mism += popc64(ballot(!(__builtin_fabsf(d[e]) <= tol[e])));
                     q[e] = __builtin_fabsf(d[e]) * inv[e];
                 }
-                // fp32 tree sums over 8 non-negative terms (3 roundings deep), then fp64
+                // fp32 pairwise trees over the tile's kE non-negative terms (log2 kE
+                // roundings deep: 3 for fp32 tiles, 4 for bf16 tiles), then fp64
                 float m_abs = acc[g].max_abs, m_rel = acc[g].max_rel;
-                double s_abs = acc[g].sum_abs, s_rel = acc[g].sum_rel;
-                float chk = 0.0f;
+                const float sa = tree_sum<kE, true>(d);
+                const float sr = tree_sum<kE, false>(q);
+                const double s_abs = acc[g].sum_abs + (double)sa;
+                const double s_rel = acc[g].sum_rel + (double)sr;
+                const float chk = sa + sr;
 #pragma unroll
-                for (int h = 0; h < kE; h += 8) {
-                    const float sa = ((__builtin_fabsf(d[h]) + __builtin_fabsf(d[h + 1])) +
-                                      (__builtin_fabsf(d[h + 2]) + __builtin_fabsf(d[h + 3]))) +
-                                     ((__builtin_fabsf(d[h + 4]) + __builtin_fabsf(d[h + 5])) +
-                                      (__builtin_fabsf(d[h + 6]) + __builtin_fabsf(d[h + 7])));
-                    const float sr = ((q[h] + q[h + 1]) + (q[h + 2] + q[h + 3])) +
-                                     ((q[h + 4] + q[h + 5]) + (q[h + 6] + q[h + 7]));
-                    s_abs += (double)sa;
-                    s_rel += (double)sr;
-                    chk += sa + sr;
-#pragma unroll
-                    for (int e = h; e < h + 8; e += 2) {
-                        m_abs = max3_abs(m_abs, d[e], d[e + 1]);
-                        m_rel = max3(m_rel, q[e], q[e + 1]);
-                    }
+                for (int e = 0; e < kE; e += 2) {
+                    m_abs = max3_abs(m_abs, d[e], d[e + 1]);
+                    m_rel = max3(m_rel, q[e], q[e + 1]);
                 }
                 // Every d and q of the tile is finite and no fp32 partial sum overflowed
                 // <=> chk is finite.  (A NaN or Inf reference element makes d non-finite

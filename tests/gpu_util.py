@@ -11,8 +11,8 @@ import paper_2510_03760_amd as evo
 from paper_2510_03760_amd.binding import stats_to_numpy, summary_to_numpy
 
 # Relative tolerance of the two error sums (everything else is compared exactly).
-# The kernel adds fp32 trees of 8 non-negative terms (<= 3 roundings, 3*2^-24 =
-# 1.8e-7 relative) into fp64; the oracle adds every term in fp64.
+# The kernel adds fp32 pairwise trees of a tile's 8 (fp32) or 16 (bf16) non-negative terms
+# (<= 4 roundings, 4*2^-24 = 2.4e-7 relative) into fp64; the oracle adds every term in fp64.
 SUM_RTOL = 1e-6
 
 EXACT_INT_FIELDS = ("n_mismatch", "n_finite", "flags", "valid")

@@ -79,6 +79,41 @@ def test_population_sizes(gu, P):
     chk.close()
 
 
+def test_reciprocal_shortcut_is_exact_on_this_device(gu):
+    """The kernel's 1/|r| shortcut (rcp + one FMA Newton step) equals the correctly rounded
+    division for every binary32 input it is used on; checked exhaustively on the device."""
+    _say("reciprocal shortcut")
+    import os
+    import subprocess
+    import paper_2510_03760_amd as evo
+    exe = os.path.join(os.path.dirname(evo.lib_path), "rcp_check")
+    assert os.path.exists(exe), "build the package first (python -m paper_2510_03760_amd.build)"
+    res = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+    assert res.returncode == 0, res.stdout
+    assert " 0 mismatches" in res.stdout, res.stdout
+
+
+def test_huge_reference_values(gu):
+    """|r| at and above 2^126 (subnormal reciprocals) next to ordinary values."""
+    _say("huge refs")
+    n = 8192
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3)
+    ref = torch.randn(n, generator=g, device="cuda")
+    big = torch.tensor([2.0 ** 126, -(2.0 ** 126), 2.0 ** 127, 3e38, 1.7e38, 2.0 ** 125, 8.5e37],
+                       device="cuda")
+    idx = torch.randint(0, n, (64,), generator=g, device="cuda")
+    ref[idx] = big[torch.randint(0, 7, (64,), generator=g, device="cuda")]
+    cands = [ref * (1 + 1e-3 * torch.randn(n, generator=g, device="cuda")) for _ in range(3)]
+    cands = [torch.nan_to_num(c, posinf=3e38, neginf=-3e38) for c in cands]
+    seg = synth.Segment(ref, cands, (n,), [False] * 3)
+    w = synth.Workload("huge", [seg], 1e-2, 1e-2, torch.ones(3, 4, device="cuda"),
+                       torch.ones(4, device="cuda"))
+    chk, stats, want = gu.check_parity(w, label="huge")
+    assert all(r["max_rel_err"] > 0 for r in want)
+    chk.close()
+
+
 def test_overflowing_differences(gu):
     """|c - r| and d/|r| overflow binary32 on finite inputs: the statistics keep +Inf."""
     _say("overflow")
