@@ -254,8 +254,10 @@ int run_check(evo_check *c, const std::vector<HostSeg> &segs, hipStream_t stream
     for (const HostSeg &h : segs) total_ptrs += h.P;
 
     const size_t S = segs.size();
-    if ((rc = ensure_partials(c, (size_t)total_jobs * evo::kRowsPerJob)) != EVO_OK) return rc;
-    if ((rc = ensure_tickets(c, S, stream)) != EVO_OK) return rc;
+    // first-level rows (one set per job) and second-level rows (at most one set per job);
+    // bundle tickets (indexed like jobs) and segment tickets
+    if ((rc = ensure_partials(c, 2 * (size_t)total_jobs * evo::kRowsPerJob)) != EVO_OK) return rc;
+    if ((rc = ensure_tickets(c, (size_t)total_jobs + S, stream)) != EVO_OK) return rc;
 
     size_t off = 0;
     for (size_t s = 0; s < S; ++s) {

@@ -527,16 +527,83 @@ __device__ void run_job(const SegDesc &sd, const uint64_t *ptr_table, uint32_t j
     }
 }
 
-// Fold of a segment's partial rows by the last workgroup that finished a job of it.
-// Thread layout: R consecutive threads share a candidate and take R consecutive
-// ranges of chunks; their R results are then added in range order.  The order is
-// a function of the launch geometry only.
-__device__ void finalize_segment(const SegDesc &sd, const Partial *partials, evo_stats *stats) {
-    __shared__ Partial fold[kThreads];
+// Reduction tree over the jobs of a segment.  Level 1: the jobs of a group block are
+// taken kFold consecutive chunks at a time; the last workgroup of such a bundle to finish
+// adds the bundle's rows (in chunk order) into one second-level row per candidate.
+// Level 2: the last bundle of the segment to be folded adds the second-level rows (in
+// bundle order) and writes the evo_stats rows.  Every order is a function of the launch
+// geometry only, so the sums are reproducible; and no workgroup ever has to read more
+// than a few dozen rows per candidate after the last tile has been streamed.
+constexpr uint32_t kFold = 16;
+
+__device__ __forceinline__ void add_row(Partial &a, const uint64_t (&w)[6]) {
+    a.n_mismatch += w[0];
+    a.n_excluded += w[1];
+    a.sum_abs += __builtin_bit_cast(double, w[2]);
+    a.sum_rel += __builtin_bit_cast(double, w[3]);
+    a.max_abs = __builtin_fmaxf(a.max_abs, as_f32((uint32_t)w[4]));
+    a.max_rel = __builtin_fmaxf(a.max_rel, as_f32((uint32_t)(w[4] >> 32)));
+    a.flags |= (uint32_t)w[5];
+}
+
+__device__ __forceinline__ void add_partial(Partial &a, const Partial &o) {
+    a.n_mismatch += o.n_mismatch;
+    a.n_excluded += o.n_excluded;
+    a.sum_abs += o.sum_abs;
+    a.sum_rel += o.sum_rel;
+    a.max_abs = __builtin_fmaxf(a.max_abs, o.max_abs);
+    a.max_rel = __builtin_fmaxf(a.max_rel, o.max_rel);
+    a.flags |= o.flags;
+}
+
+// Device-scope load of one 48-byte row (it was written by another workgroup, possibly
+// through another XCD's L2).
+__device__ __forceinline__ void load_row(const Partial *row, uint64_t (&w)[6]) {
+    const uint64_t *src = reinterpret_cast<const uint64_t *>(row);
+#pragma unroll
+    for (int q = 0; q < 6; ++q)
+        w[q] = __hip_atomic_load(src + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Level 1: rows of chunks [first, first + count) of group block `gblock` -> one row per
+// candidate slot in rows1[bundle].  Thread t: slot row t % 64, quarter t / 64 of the bundle.
+__device__ void fold_bundle(const SegDesc &sd, uint32_t gblock, uint32_t first, uint32_t count,
+                            const Partial *rows0, Partial *row1, Partial *fold) {
+    static_assert(kRowsPerJob <= 64 && kThreads == 256 && kFold == 16, "thread layout");
+    const uint32_t slot_row = threadIdx.x % 64u;
+    const uint32_t quarter = threadIdx.x / 64u;
+    Partial a{};
+    if (slot_row < (uint32_t)kRowsPerJob) {
+        uint64_t w[4][6];
+#pragma unroll
+        for (uint32_t k = 0; k < 4; ++k) {
+            const uint32_t ch = first + min(quarter * 4u + k, count - 1u);
+            const uint64_t job = (uint64_t)sd.job0 + (uint64_t)gblock * sd.n_chunks + ch;
+            load_row(rows0 + job * kRowsPerJob + slot_row, w[k]);
+        }
+#pragma unroll
+        for (uint32_t k = 0; k < 4; ++k)
+            if (quarter * 4u + k < count) add_row(a, w[k]);
+    }
+    fold[threadIdx.x] = a;
+    __syncthreads();
+    if (quarter == 0 && slot_row < (uint32_t)kRowsPerJob) {
+        for (uint32_t k = 1; k < 4; ++k) add_partial(a, fold[threadIdx.x + 64u * k]);
+        row1[slot_row] = a;
+        __threadfence();   // publish before the segment ticket
+    }
+    __syncthreads();
+}
+
+// Level 2.  Thread layout: R consecutive threads share a candidate and take R consecutive
+// ranges of the candidate's `units` second-level rows; their R results are then added in
+// range order.
+__device__ void finalize_segment(const SegDesc &sd, const Partial *rows1, uint32_t units,
+                                 evo_stats *stats, Partial *fold) {
     uint32_t pc = 1;
     while (pc < sd.P && pc < (uint32_t)kThreads) pc <<= 1;   // candidates per pass (power of 2)
     const uint32_t R = kThreads / pc;                          // chunk ranges per candidate
-    const uint32_t per = (sd.n_chunks + R - 1) / R;
+    const uint32_t per = (units + R - 1) / R;
     const uint32_t ci = threadIdx.x / R;
     const uint32_t ri = threadIdx.x % R;
 
@@ -549,50 +616,27 @@ __device__ void finalize_segment(const SegDesc &sd, const Partial *partials, evo
             const uint32_t gblock = group / sd.gpw;
             const uint32_t slot = group - gblock * sd.gpw;
             const uint32_t ch_lo = ri * per;
-            const uint32_t ch_hi = min(ch_lo + per, sd.n_chunks);
-            // Rows are fetched eight chunks at a time so that their loads overlap; they
-            // are added in chunk order.  Device-scope loads: the rows were written by
-            // other workgroups, possibly through another XCD's L2.
+            const uint32_t ch_hi = min(ch_lo + per, units);
+            // Rows are fetched eight at a time so that their loads overlap; they are
+            // added in bundle order.
             constexpr uint32_t kBatch = 8;
             for (uint32_t ch = ch_lo; ch < ch_hi; ch += kBatch) {
                 uint64_t w[kBatch][6];
 #pragma unroll
                 for (uint32_t k = 0; k < kBatch; ++k) {
                     const uint32_t c2 = min(ch + k, ch_hi - 1);
-                    const uint64_t job = (uint64_t)sd.job0 + (uint64_t)gblock * sd.n_chunks + c2;
-                    const uint64_t *src = reinterpret_cast<const uint64_t *>(
-                        partials + job * kRowsPerJob + slot * kG + gi);
-#pragma unroll
-                    for (int q = 0; q < 6; ++q)
-                        w[k][q] = __hip_atomic_load(src + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const uint64_t unit = (uint64_t)sd.job0 + (uint64_t)gblock * units + c2;
+                    load_row(rows1 + unit * kRowsPerJob + slot * kG + gi, w[k]);
                 }
 #pragma unroll
-                for (uint32_t k = 0; k < kBatch; ++k) {
-                    if (ch + k < ch_hi) {
-                        a.n_mismatch += w[k][0];
-                        a.n_excluded += w[k][1];
-                        a.sum_abs += __builtin_bit_cast(double, w[k][2]);
-                        a.sum_rel += __builtin_bit_cast(double, w[k][3]);
-                        a.max_abs = __builtin_fmaxf(a.max_abs, as_f32((uint32_t)w[k][4]));
-                        a.max_rel = __builtin_fmaxf(a.max_rel, as_f32((uint32_t)(w[k][4] >> 32)));
-                        a.flags |= (uint32_t)w[k][5];
-                    }
-                }
+                for (uint32_t k = 0; k < kBatch; ++k)
+                    if (ch + k < ch_hi) add_row(a, w[k]);
             }
         }
         fold[threadIdx.x] = a;
         __syncthreads();
         if (ri == 0 && p < sd.P) {
-            for (uint32_t k = 1; k < R; ++k) {
-                const Partial &o = fold[threadIdx.x + k];
-                a.n_mismatch += o.n_mismatch;
-                a.n_excluded += o.n_excluded;
-                a.sum_abs += o.sum_abs;
-                a.sum_rel += o.sum_rel;
-                a.max_abs = __builtin_fmaxf(a.max_abs, o.max_abs);
-                a.max_rel = __builtin_fmaxf(a.max_rel, o.max_rel);
-                a.flags |= o.flags;
-            }
+            for (uint32_t k = 1; k < R; ++k) add_partial(a, fold[threadIdx.x + k]);
             evo_stats s;
             s.n_mismatch = a.n_mismatch;
             s.n_finite = sd.n - a.n_excluded;
@@ -636,23 +680,43 @@ __device__ __forceinline__ void check_body(const SegDesc *descs, const uint64_t 
     else
         run_job<EVO_F32>(sd, ptr_table, job_local, job, atol, rtol, partials, exact_acc, wave_part, redo);
 
-    // This job's partial rows are published (run_job fences after writing them); take a
-    // ticket.  The workgroup that draws the segment's last ticket folds the segment
-    // and re-arms the counter.
+    // This job's rows are published (run_job fences after writing them).  Two tickets:
+    // the bundle of kFold chunks this job belongs to, then the segment (see fold_bundle).
+    // Second-level rows and tickets follow the first-level ones in the same buffers; all
+    // counters re-arm themselves.
     __shared__ uint32_t is_last;
+    __shared__ Partial fold[kThreads];
+    Partial *rows1 = partials + (uint64_t)gridDim.x * kRowsPerJob;
+    uint32_t *seg_tickets = tickets + gridDim.x;
+    const uint32_t gblock = job_local / sd.n_chunks;
+    const uint32_t chunk = job_local - gblock * sd.n_chunks;
+    const uint32_t units = (sd.n_chunks + kFold - 1) / kFold;        // bundles per group block
+    const uint32_t bundle = sd.job0 + gblock * units + chunk / kFold; // unique in the launch
+    const uint32_t first = (chunk / kFold) * kFold;
+    const uint32_t count = min(kFold, sd.n_chunks - first);
     __syncthreads();
     if (threadIdx.x == 0) {
-        const uint32_t prev = __hip_atomic_fetch_add(&tickets[s], 1u, __ATOMIC_ACQ_REL,
+        const uint32_t prev = __hip_atomic_fetch_add(&tickets[bundle], 1u, __ATOMIC_ACQ_REL,
                                                      __HIP_MEMORY_SCOPE_AGENT);
-        is_last = (prev == sd.n_jobs - 1) ? 1u : 0u;
+        is_last = (prev == count - 1) ? 1u : 0u;
     }
     __syncthreads();
-    if (is_last) {
-        __threadfence();
-        finalize_segment(sd, partials, stats);
-        if (threadIdx.x == 0)
-            __hip_atomic_store(&tickets[s], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!is_last) return;
+    __threadfence();
+    fold_bundle(sd, gblock, first, count, partials, rows1 + (uint64_t)bundle * kRowsPerJob, fold);
+    if (threadIdx.x == 0) {
+        __hip_atomic_store(&tickets[bundle], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t n_bundles = units * ((sd.n_groups + sd.gpw - 1) / sd.gpw);
+        const uint32_t prev = __hip_atomic_fetch_add(&seg_tickets[s], 1u, __ATOMIC_ACQ_REL,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+        is_last = (prev == n_bundles - 1) ? 1u : 0u;
     }
+    __syncthreads();
+    if (!is_last) return;
+    __threadfence();
+    finalize_segment(sd, rows1, units, stats, fold);
+    if (threadIdx.x == 0)
+        __hip_atomic_store(&seg_tickets[s], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __global__ void __launch_bounds__(kThreads, EVO_WAVES_PER_EU)
