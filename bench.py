@@ -6,7 +6,7 @@ batched (or segmented) tolerance check of every candidate against its reference,
 then the median-timing / speedup / fitness reduction.  Inputs are resident in HBM
 before the timed region starts.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c4|c5]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c4|c5|cases]
                     [--no-cpu-baseline] [--copy-calibration]
 
 --copy-calibration runs only a plain device-to-device copy of known size (used to
@@ -60,6 +60,8 @@ def build_workload(name: str):
         return synth.ragged_f32("cuda", P_s=32, T=100)
     if name == "c5":
         return synth.heavy_tail_f32("cuda", log2n=30, P=8, T=1000)
+    if name == "cases":
+        return synth.multi_case_f32("cuda", K=5, side=4096, P=16, T=100)
     raise SystemExit("unknown workload %r" % name)
 
 
@@ -86,7 +88,12 @@ def cpu_baseline(w, budget_elems: int):
             done += m
     tim = w.timings.cpu().numpy()
     base = w.baseline.cpu().numpy()
-    valid = np.array([r["valid"] for r in rows], np.uint32)
+    if w.notes.get("cases"):   # a candidate is valid iff it passes every case
+        P = w.P
+        valid = np.array([int(all(rows[k * P + p]["valid"] for k in range(len(w.segments))))
+                          for p in range(P)], np.uint32)
+    else:
+        valid = np.array([r["valid"] for r in rows], np.uint32)
     t0 = time.perf_counter()
     oracle.fitness(tim, base, valid)
     t_all += time.perf_counter() - t0
@@ -151,7 +158,11 @@ def main() -> int:
     summary = chk.new_summary()
     stream = torch.cuda.current_stream()
     seg_descs = None
-    if len(segs) > 1:
+    is_cases = bool(w.notes.get("cases"))
+    if is_cases:
+        seg_descs = [{"ref": s.ref, "cand_ptrs": s.cands, "n_elems": s.n, "dtype": dcode(s)}
+                     for s in segs]
+    elif len(segs) > 1:
         row0, seg_descs = 0, []
         for s in segs:
             seg_descs.append({"ref": s.ref, "cand_ptrs": s.cands, "n_elems": s.n,
@@ -161,6 +172,8 @@ def main() -> int:
     def check():
         if seg_descs is None:
             chk.check_batch(segs[0].ref, segs[0].cands, stats, stream=stream)
+        elif is_cases:
+            chk.check_cases(seg_descs, stats, stream=stream)
         else:
             chk.check_segmented(seg_descs, stats, P, stream=stream)
 
@@ -209,8 +222,8 @@ def main() -> int:
         "config": {"workload": w.name, "P": P, "cand_elems": w.cand_elems,
                    "algorithmic_bytes": alg_bytes, "T": int(w.timings.shape[1]),
                    "atol": w.atol, "rtol": w.rtol,
-                   "entry": "evo_check_batch+evo_fitness" if seg_descs is None
-                   else "evo_check_segmented+evo_fitness"},
+                   "entry": ("evo_check_batch" if seg_descs is None else
+                             "evo_check_cases" if is_cases else "evo_check_segmented") + "+evo_fitness"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
                      "kernel": "evo_check_kernel", "avg_ms": check_avg,
@@ -229,7 +242,7 @@ def main() -> int:
     if not args.no_cpu_baseline:
         base, rows, frac = cpu_baseline(w, int(args.cpu_budget_elems))
         out["cpu_baseline"] = base
-        if frac >= 1.0:   # the sample was the whole population: report agreement too
+        if frac >= 1.0 and not is_cases:   # the sample was the whole population: report agreement too
             same = all(int(g["n_mismatch"]) == r["n_mismatch"] and
                        g["max_abs_err"].tobytes() == r["max_abs_err"].tobytes() and
                        g["max_rel_err"].tobytes() == r["max_rel_err"].tobytes()

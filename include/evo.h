@@ -168,6 +168,23 @@ EVO_API int evo_check_segmented(evo_check_t *c, const evo_segment *segs, uint32_
                         void *stream, evo_stats *stats, uint32_t n_rows);
 
 /*
+ * Functional testing over several test cases at once (Sec. 4.3 runs five test cases per
+ * candidate; the AI-CUDA-Engineer replication appendix checks five random inputs): K
+ * cases, each a reference and the SAME P candidates' outputs for that case, checked in
+ * ONE launch.  Row p of stats describes candidate p over all cases together, exactly as
+ * if the K tensors of a candidate were one tensor fed case after case: counts and
+ * n_elems add, maxima are taken over all cases, the error sums add, flags are OR-ed, and
+ * valid = 1 iff no element of any case mismatches.
+ *   cases  HOST array of K descriptors with equal P_s (and the host pointer arrays they
+ *          name); n_elems and dtype may differ per case; stats_row0 must be 0
+ *   stats  device, P_s rows, completely overwritten
+ * Errors: as evo_check_segmented, plus EVO_ERR_SIZE for K == 0, unequal P_s or a non-zero
+ * stats_row0.
+ */
+EVO_API int evo_check_cases(evo_check_t *c, const evo_segment *cases, uint32_t K, void *stream,
+                            evo_stats *stats);
+
+/*
  * Performance objective of Sec. 3.1 with the metric of Sec. 5.1.  For each of the
  * P candidates: median of its T timing samples (even T: 0.5f*(lo+hi) of the two
  * middle order statistics), mean (binary64 sum in sample order, divided by T,

@@ -78,11 +78,13 @@ def _load() -> ctypes.CDLL:
     h.evo_check_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, u64, f32, f32]
     h.evo_check_batch.argtypes = [vp, vp, ctypes.POINTER(vp), u32, vp, vp]
     h.evo_check_segmented.argtypes = [vp, ctypes.POINTER(EvoSegment), u32, vp, vp, u32]
+    h.evo_check_cases.argtypes = [vp, ctypes.POINTER(EvoSegment), u32, vp, vp]
     h.evo_fitness.argtypes = [vp, vp, vp, u32, u32, vp, vp, vp]
     h.evo_check_destroy.argtypes = [vp]
     h.evo_strerror.argtypes = [ctypes.c_int]
     h.evo_strerror.restype = ctypes.c_char_p
-    for name in ("evo_check_create", "evo_check_batch", "evo_check_segmented", "evo_fitness",
+    for name in ("evo_check_create", "evo_check_batch", "evo_check_segmented", "evo_check_cases",
+                 "evo_fitness",
                  "evo_check_destroy"):
         getattr(h, name).restype = ctypes.c_int
     return h
@@ -129,8 +131,9 @@ def evo_check_batch(ctx: int, ref, cand_ptrs: Sequence, P: int, stream, stats) -
         raise EvoError(rc, "evo_check_batch")
 
 
-def evo_check_segmented(ctx: int, segs: Sequence[dict], S: int, stream, stats, n_rows: int) -> None:
-    """``segs``: dicts with keys ref, cand_ptrs, n_elems, dtype, stats_row0."""
+def _segment_array(segs: Sequence[dict]):
+    """ctypes evo_segment array for dicts with keys ref, cand_ptrs, n_elems, dtype and
+    (optionally) stats_row0, P_s; also returns the objects that must stay alive."""
     keep: List[object] = []
     c_segs = (EvoSegment * max(1, len(segs)))()
     for i, sg in enumerate(segs):
@@ -142,11 +145,28 @@ def evo_check_segmented(ctx: int, segs: Sequence[dict], S: int, stream, stats, n
         c_segs[i].n_elems = int(sg["n_elems"])
         c_segs[i].P_s = int(sg.get("P_s", len(ptrs)))
         c_segs[i].dtype = int(sg["dtype"])
-        c_segs[i].stats_row0 = int(sg["stats_row0"])
+        c_segs[i].stats_row0 = int(sg.get("stats_row0", 0))
         c_segs[i].reserved = 0
+    return c_segs, keep
+
+
+def evo_check_segmented(ctx: int, segs: Sequence[dict], S: int, stream, stats, n_rows: int) -> None:
+    """``segs``: dicts with keys ref, cand_ptrs, n_elems, dtype, stats_row0."""
+    c_segs, keep = _segment_array(segs)
     rc = lib.evo_check_segmented(ctx, c_segs, int(S), _stream(stream), _ptr(stats), int(n_rows))
+    del keep
     if rc != 0:
         raise EvoError(rc, "evo_check_segmented")
+
+
+def evo_check_cases(ctx: int, cases: Sequence[dict], K: int, stream, stats) -> None:
+    """``cases``: dicts with keys ref, cand_ptrs, n_elems, dtype (same candidates, one
+    dict per test case)."""
+    c_segs, keep = _segment_array(cases)
+    rc = lib.evo_check_cases(ctx, c_segs, int(K), _stream(stream), _ptr(stats))
+    del keep
+    if rc != 0:
+        raise EvoError(rc, "evo_check_cases")
 
 
 def evo_fitness(ctx: int, timings, baseline, P: int, T: int, stream, stats, summary=None) -> None:
@@ -203,6 +223,10 @@ class Checker:
         evo_check_segmented(self.ctx, segs, len(segs),
                             stream if stream is not None else torch.cuda.current_stream(),
                             stats, n_rows)
+
+    def check_cases(self, cases: Sequence[dict], stats: torch.Tensor, stream=None) -> None:
+        evo_check_cases(self.ctx, cases, len(cases),
+                        stream if stream is not None else torch.cuda.current_stream(), stats)
 
     def fitness(self, timings: torch.Tensor, baseline: torch.Tensor, stats: torch.Tensor,
                 summary: Optional[torch.Tensor] = None, stream=None) -> None:

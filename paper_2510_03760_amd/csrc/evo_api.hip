@@ -151,6 +151,7 @@ struct HostSeg {
     const void *const *cand_ptrs;
     uint64_t n;
     uint32_t P, dtype, row0;
+    uint32_t case0 = 0, n_cases = 1;   // case group (evo_check_cases), else the segment alone
 };
 
 // Pure host validation of one group (no device call).
@@ -191,7 +192,8 @@ void partition(const std::vector<HostSeg> &segs, uint32_t target_jobs, std::vect
         d.stats_row0 = h.row0;
         d.n_groups = evo::group_count(h.P);
         d.gpw = std::min<uint32_t>(pow2_ceil(d.n_groups), evo::kWaves);
-        d.pad = 0;
+        d.case0 = h.n_cases > 1 ? h.case0 : (uint32_t)s;
+        d.n_cases = h.n_cases;
         const uint64_t tiles = (h.n + evo::tile_elems(h.dtype) - 1) / evo::tile_elems(h.dtype);
         wave_tiles += tiles * d.n_groups;
     }
@@ -200,20 +202,29 @@ void partition(const std::vector<HostSeg> &segs, uint32_t target_jobs, std::vect
                         ((uint64_t)target_jobs * evo::kWaves);
     per_wave = std::min<uint64_t>(std::max<uint64_t>(per_wave, kMinTilesPerWave),
                                   evo::kMaxTilesPerWave);
+    // The rounding up per segment can push the total past the number of workgroups the
+    // machine holds at once, and the surplus would run as a second round after everything
+    // else: coarsen until the launch fits (it cannot when there are more segments than
+    // slots; then every segment still gets its one workgroup).
     uint32_t job0 = 0;
-    for (size_t s = 0; s < segs.size(); ++s) {
-        SegDesc &d = descs[s];
-        const uint64_t tiles = (d.n + evo::tile_elems(d.dtype) - 1) / evo::tile_elems(d.dtype);
-        const uint32_t tpw = evo::kWaves / d.gpw;
-        const uint64_t per_chunk = per_wave * tpw;
-        const uint64_t chunks = (tiles + per_chunk - 1) / per_chunk;
-        d.n_chunks = (uint32_t)chunks;
-        // tiles are dealt round-robin over chunks * tpw wavefront slots
-        d.tiles_per_wave = (uint32_t)((tiles + chunks * tpw - 1) / (chunks * tpw));
-        const uint32_t gblocks = (d.n_groups + d.gpw - 1) / d.gpw;
-        d.n_jobs = gblocks * d.n_chunks;
-        d.job0 = job0;
-        job0 += d.n_jobs;
+    for (int attempt = 0; attempt < 64; ++attempt) {
+        job0 = 0;
+        for (size_t s = 0; s < segs.size(); ++s) {
+            SegDesc &d = descs[s];
+            const uint64_t tiles = (d.n + evo::tile_elems(d.dtype) - 1) / evo::tile_elems(d.dtype);
+            const uint32_t tpw = evo::kWaves / d.gpw;
+            const uint64_t per_chunk = per_wave * tpw;
+            const uint64_t chunks = (tiles + per_chunk - 1) / per_chunk;
+            d.n_chunks = (uint32_t)chunks;
+            const uint32_t gblocks = (d.n_groups + d.gpw - 1) / d.gpw;
+            d.n_jobs = gblocks * d.n_chunks;
+            d.job0 = job0;
+            job0 += d.n_jobs;
+        }
+        if (job0 <= target_jobs || per_wave >= evo::kMaxTilesPerWave) break;
+        // next candidate: scale by the overshoot, at least one tile more
+        per_wave = std::min<uint64_t>(std::max<uint64_t>(per_wave + 1, per_wave * job0 / target_jobs),
+                                      evo::kMaxTilesPerWave);
     }
     total_jobs = job0;
 }
@@ -256,8 +267,10 @@ int run_check(evo_check *c, const std::vector<HostSeg> &segs, hipStream_t stream
     const size_t S = segs.size();
     // first-level rows (one set per job) and second-level rows (at most one set per job);
     // bundle tickets (indexed like jobs) and segment tickets
-    if ((rc = ensure_partials(c, 2 * (size_t)total_jobs * evo::kRowsPerJob)) != EVO_OK) return rc;
-    if ((rc = ensure_tickets(c, (size_t)total_jobs + S, stream)) != EVO_OK) return rc;
+    // (layout: see evo_internal.h)
+    if ((rc = ensure_partials(c, 2 * (size_t)total_jobs * evo::kRowsPerJob + total_ptrs)) != EVO_OK)
+        return rc;
+    if ((rc = ensure_tickets(c, (size_t)total_jobs + 2 * S, stream)) != EVO_OK) return rc;
 
     size_t off = 0;
     for (size_t s = 0; s < S; ++s) {
@@ -335,7 +348,7 @@ int evo_check_batch(evo_check_t *c, const void *ref, const void *const *cand_ptr
                     void *stream, evo_stats *stats) {
     if (!is_live(c)) return EVO_ERR_HANDLE;
     if (!stats) return EVO_ERR_NULL;
-    HostSeg h{ref, cand_ptrs, c->n_elems, P, (uint32_t)c->dtype, 0u};
+    HostSeg h{ref, cand_ptrs, c->n_elems, P, (uint32_t)c->dtype, 0u, 0u, 1u};
     const int rc = validate_seg(h);
     if (rc != EVO_OK) return rc;
     try {
@@ -356,7 +369,7 @@ int evo_check_segmented(evo_check_t *c, const evo_segment *segs, uint32_t S, voi
         std::vector<std::pair<uint64_t, uint64_t>> ranges(S);
         for (uint32_t s = 0; s < S; ++s) {
             hs[s] = HostSeg{segs[s].ref, segs[s].cand_ptrs, segs[s].n_elems, segs[s].P_s,
-                            segs[s].dtype, segs[s].stats_row0};
+                            segs[s].dtype, segs[s].stats_row0, 0u, 1u};
             const int rc = validate_seg(hs[s]);
             if (rc != EVO_OK) return rc;
             const uint64_t lo = segs[s].stats_row0, hi = lo + segs[s].P_s;
@@ -366,6 +379,26 @@ int evo_check_segmented(evo_check_t *c, const evo_segment *segs, uint32_t S, voi
         std::sort(ranges.begin(), ranges.end());
         for (uint32_t s = 1; s < S; ++s)
             if (ranges[s].first < ranges[s - 1].second) return EVO_ERR_SIZE;
+        return run_check(c, hs, static_cast<hipStream_t>(stream), stats);
+    } catch (const std::bad_alloc &) {
+        return EVO_ERR_NOMEM;
+    }
+}
+
+int evo_check_cases(evo_check_t *c, const evo_segment *cases, uint32_t K, void *stream,
+                    evo_stats *stats) {
+    if (!is_live(c)) return EVO_ERR_HANDLE;
+    if (!cases || !stats) return EVO_ERR_NULL;
+    if (K == 0) return EVO_ERR_SIZE;
+    try {
+        std::vector<HostSeg> hs(K);
+        for (uint32_t k = 0; k < K; ++k) {
+            hs[k] = HostSeg{cases[k].ref, cases[k].cand_ptrs, cases[k].n_elems, cases[k].P_s,
+                            cases[k].dtype, 0u, 0u, K};
+            const int rc = validate_seg(hs[k]);
+            if (rc != EVO_OK) return rc;
+            if (cases[k].P_s != cases[0].P_s || cases[k].stats_row0 != 0) return EVO_ERR_SIZE;
+        }
         return run_check(c, hs, static_cast<hipStream_t>(stream), stats);
     } catch (const std::bad_alloc &) {
         return EVO_ERR_NOMEM;

@@ -598,8 +598,29 @@ __device__ void fold_bundle(const SegDesc &sd, uint32_t gblock, uint32_t first, 
 // Level 2.  Thread layout: R consecutive threads share a candidate and take R consecutive
 // ranges of the candidate's `units` second-level rows; their R results are then added in
 // range order.
+// A segment that stands alone writes its evo_stats rows; one that is a case of a case
+// group leaves one row per candidate in case_rows for write_case_group.
+__device__ __forceinline__ void write_stats(evo_stats *dst, const Partial &a, uint64_t n_elems) {
+    evo_stats s;
+    s.n_mismatch = a.n_mismatch;
+    s.n_finite = n_elems - a.n_excluded;
+    s.sum_abs_err = a.sum_abs;
+    s.sum_rel_err = a.sum_rel;
+    s.max_abs_err = a.max_abs;
+    s.max_rel_err = a.max_rel;
+    s.flags = a.flags;
+    s.valid = a.n_mismatch == 0 ? 1u : 0u;
+    s.median_ms = 0.0f;
+    s.mean_ms = 0.0f;
+    s.speedup = 0.0f;
+    s.fitness = 0.0f;
+    s.n_elems_lo = (uint32_t)(n_elems & 0xffffffffu);
+    s.n_elems_hi = (uint32_t)(n_elems >> 32);
+    *dst = s;
+}
+
 __device__ void finalize_segment(const SegDesc &sd, const Partial *rows1, uint32_t units,
-                                 evo_stats *stats, Partial *fold) {
+                                 evo_stats *stats, Partial *case_rows, Partial *fold) {
     uint32_t pc = 1;
     while (pc < sd.P && pc < (uint32_t)kThreads) pc <<= 1;   // candidates per pass (power of 2)
     const uint32_t R = kThreads / pc;                          // chunk ranges per candidate
@@ -637,24 +658,32 @@ __device__ void finalize_segment(const SegDesc &sd, const Partial *rows1, uint32
         __syncthreads();
         if (ri == 0 && p < sd.P) {
             for (uint32_t k = 1; k < R; ++k) add_partial(a, fold[threadIdx.x + k]);
-            evo_stats s;
-            s.n_mismatch = a.n_mismatch;
-            s.n_finite = sd.n - a.n_excluded;
-            s.sum_abs_err = a.sum_abs;
-            s.sum_rel_err = a.sum_rel;
-            s.max_abs_err = a.max_abs;
-            s.max_rel_err = a.max_rel;
-            s.flags = a.flags;
-            s.valid = a.n_mismatch == 0 ? 1u : 0u;
-            s.median_ms = 0.0f;
-            s.mean_ms = 0.0f;
-            s.speedup = 0.0f;
-            s.fitness = 0.0f;
-            s.n_elems_lo = (uint32_t)(sd.n & 0xffffffffu);
-            s.n_elems_hi = (uint32_t)(sd.n >> 32);
-            stats[sd.stats_row0 + p] = s;
+            if (sd.n_cases <= 1) {
+                write_stats(&stats[sd.stats_row0 + p], a, sd.n);
+            } else {
+                case_rows[sd.ptr0 + p] = a;
+                __threadfence();   // publish before the case-group ticket
+            }
         }
         __syncthreads();
+    }
+}
+
+// Level 3 (case groups only): candidate p over all cases of the group, cases added in
+// case order.
+__device__ void write_case_group(const SegDesc *descs, const SegDesc &sd, const Partial *case_rows,
+                                 evo_stats *stats) {
+    for (uint32_t p = threadIdx.x; p < sd.P; p += kThreads) {
+        Partial a{};
+        uint64_t n_elems = 0;
+        for (uint32_t k = 0; k < sd.n_cases; ++k) {
+            const SegDesc &dk = descs[sd.case0 + k];
+            uint64_t w[6];
+            load_row(case_rows + dk.ptr0 + p, w);
+            add_row(a, w);
+            n_elems += dk.n;
+        }
+        write_stats(&stats[sd.stats_row0 + p], a, n_elems);
     }
 }
 
@@ -714,9 +743,26 @@ __device__ __forceinline__ void check_body(const SegDesc *descs, const uint64_t 
     __syncthreads();
     if (!is_last) return;
     __threadfence();
-    finalize_segment(sd, rows1, units, stats, fold);
+    Partial *case_rows = rows1 + (uint64_t)gridDim.x * kRowsPerJob;
+    finalize_segment(sd, rows1, units, stats, case_rows, fold);
     if (threadIdx.x == 0)
         __hip_atomic_store(&seg_tickets[s], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (sd.n_cases <= 1) return;
+
+    // The segment is one case of a case group: third ticket, and the last case merges.
+    uint32_t *case_tickets = seg_tickets + S;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t prev = __hip_atomic_fetch_add(&case_tickets[sd.case0], 1u, __ATOMIC_ACQ_REL,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+        is_last = (prev == sd.n_cases - 1) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!is_last) return;
+    __threadfence();
+    write_case_group(descs, sd, case_rows, stats);
+    if (threadIdx.x == 0)
+        __hip_atomic_store(&case_tickets[sd.case0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __global__ void __launch_bounds__(kThreads, EVO_WAVES_PER_EU)

@@ -114,10 +114,10 @@ struct SegDesc {
     uint32_t job0;              // first workgroup index of this segment
     uint32_t n_jobs;            // n_gblocks * n_chunks
     uint32_t n_chunks;          // workgroups that share the tiles of one group block
-    uint32_t tiles_per_wave;    // upper bound on the tiles one wavefront visits
+    uint32_t case0;             // first segment of the case group this segment belongs to
     uint32_t n_groups;          // candidate groups
     uint32_t gpw;               // groups per workgroup: 1, 2 or 4
-    uint32_t pad;
+    uint32_t n_cases;           // segments in that case group (1: the segment stands alone)
 };
 static_assert(sizeof(SegDesc) == 64, "SegDesc layout");
 
@@ -145,6 +145,9 @@ struct InlineTable {
 };
 static_assert(sizeof(InlineTable) <= 3600, "kernel argument block must stay below 4 KiB");
 
+// Scratch layout of one launch (J = workgroups, S = segments, C = candidate pointers):
+//   partials: J*kRowsPerJob first-level rows | J*kRowsPerJob second-level rows | C case rows
+//   tickets:  J bundle tickets | S segment tickets | S case-group tickets
 hipError_t launch_check(const SegDesc *d_descs, const uint64_t *d_ptrs, uint32_t S,
                         uint32_t total_jobs, float atol, float rtol, Partial *partials,
                         uint32_t *tickets, evo_stats *stats, hipStream_t stream);

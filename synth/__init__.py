@@ -58,6 +58,10 @@ class Workload:
 
     @property
     def P(self) -> int:
+        """Rows of results: every segment has its own candidates, unless the segments
+        are test cases of the same candidates (notes["cases"])."""
+        if self.notes.get("cases"):
+            return len(self.segments[0].cands)
         return sum(len(s.cands) for s in self.segments)
 
     @property
@@ -285,6 +289,40 @@ def heavy_tail_f32(device="cpu", log2n: int = 30, P: int = 8, T: int = 1000,
                    "extra_nan": {p: k for p in extra if p < P},
                    "inf_flipped": [p for p in range(P) if p == 6]})
     return Workload("C5-heavy-f32-2^%d-P%d" % (log2n, P), [seg], 1e-4, 1e-4, t, b)
+
+
+def multi_case_f32(device="cpu", K: int = 5, side: int = 4096, P: int = 16, T: int = 100) -> Workload:
+    """Five-test-case workload (the paper's functional testing runs five cases per
+    candidate): K independent fp32 side x side references ~N(0,1); candidate p's output for
+    case k = ref_k*(1 + N(0, sd 1e-4)); candidates with (p mod 4) == 3 fail exactly one case
+    (case p mod K) through a Bernoulli(1e-3) set of elements replaced by U(-10, 10)."""
+    cfg = 6
+    n = side * side
+    segs = []
+    for k in range(K):
+        ref = torch.randn(n, generator=_gen(device, cfg, 10000 * k), device=device, dtype=torch.float32)
+        cands, corrupted = [], []
+        for p in range(P):
+            z = torch.randn(n, generator=_gen(device, cfg, 10000 * k + 1 + p), device=device,
+                            dtype=torch.float32)
+            c = ref * (1.0 + 1e-4 * z)
+            del z
+            bad = (p % 4) == 3 and (p % K) == k
+            if bad:
+                gs = _gen(device, cfg, 10000 * k + 1000 + p)
+                mask = torch.rand(n, generator=gs, device=device) < 1e-3
+                if not bool(mask.any()):
+                    mask[int(torch.randint(0, n, (1,), generator=gs, device=device))] = True
+                u = torch.rand(n, generator=gs, device=device, dtype=torch.float32) * 20.0 - 10.0
+                c = torch.where(mask, u, c)
+                del mask, u
+            cands.append(c.contiguous())
+            corrupted.append(bad)
+        segs.append(Segment(ref, cands, (side, side), corrupted))
+    t, b = _timings(device, cfg, P, T, "lognormal")
+    w = Workload("C6-cases-f32-%dx%dx%d-P%d" % (K, side, side, P), segs, 1e-2, 1e-2, t, b,
+                 {"cases": True})
+    return w
 
 
 def to_oracle_array(x: torch.Tensor):

@@ -27,8 +27,9 @@ def declared_functions():
 
 
 def test_header_declares_the_documented_entry_points():
-    assert declared_functions() == ["evo_check_batch", "evo_check_create", "evo_check_destroy",
-                                    "evo_check_segmented", "evo_fitness", "evo_strerror"]
+    assert declared_functions() == ["evo_check_batch", "evo_check_cases", "evo_check_create",
+                                    "evo_check_destroy", "evo_check_segmented", "evo_fitness",
+                                    "evo_strerror"]
 
 
 def test_library_exports_every_declared_symbol(evo):
@@ -125,6 +126,31 @@ def test_check_segmented_validates_before_any_launch(evo):
     assert call([seg(row0=7)]) == -3                                   # rows 7,8 exceed n_rows
     assert call([seg(row0=0), seg(row0=1)]) == -3                      # overlapping rows
     assert call([seg(row0=2), seg(row0=0), seg(row0=3)]) == -3         # overlap, unsorted
+    assert evo.lib.evo_check_destroy(h) == 0
+
+
+def test_check_cases_validates_before_any_launch(evo):
+    rc, h = _create(evo, 0, 1, 1e-2, 1e-2)
+    ptrs = (ctypes.c_void_p * 2)(64, 128)
+    pp = ctypes.cast(ptrs, ctypes.POINTER(ctypes.c_void_p))
+
+    def case(P=2, row0=0, ref=64, n=10, dtype=0):
+        s = evo.EvoSegment()
+        s.ref, s.cand_ptrs, s.n_elems, s.P_s, s.dtype, s.stats_row0 = ref, pp, n, P, dtype, row0
+        return s
+
+    def call(cases, stats=512):
+        arr = (evo.EvoSegment * len(cases))(*cases)
+        return evo.lib.evo_check_cases(h, arr, len(cases), None, stats)
+
+    assert evo.lib.evo_check_cases(h, None, 1, None, 512) == -1
+    assert call([case()], stats=None) == -1
+    assert evo.lib.evo_check_cases(h, (evo.EvoSegment * 1)(case()), 0, None, 512) == -3
+    assert call([case(), case(P=1)]) == -3           # unequal populations
+    assert call([case(), case(row0=2)]) == -3        # rows must start at 0
+    assert call([case(), case(n=0)]) == -3
+    assert call([case(), case(dtype=9)]) == -2
+    assert call([case(), case(ref=None)]) == -1
     assert evo.lib.evo_check_destroy(h) == 0
 
 

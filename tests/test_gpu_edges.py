@@ -193,6 +193,58 @@ def test_segmented_mixed_dtypes_and_row_layout(gu):
     chk.close()
 
 
+def test_check_cases_equals_one_accumulator_over_all_cases(gu):
+    """K test cases of the same candidates in one launch: row p equals the oracle's single
+    accumulator fed with candidate p's K (reference, output) pairs one after the other."""
+    _say("cases")
+    import oracle
+    import paper_2510_03760_amd as evo
+    from paper_2510_03760_amd.binding import stats_to_numpy
+    for P, sizes, dts in ((16, (70001, 4096, 1, 300000, 513), [torch.float32] * 5),
+                          (5, (1000, 65537), [torch.bfloat16, torch.float32]),
+                          (40, (20000, 20000, 20000), [torch.float32, torch.bfloat16, torch.float32]),
+                          (3, (12345,), [torch.float32])):
+        ws = [_mixed(n, P, 7000 + 13 * i + P, dt, special=(i % 2 == 0))
+              for i, (n, dt) in enumerate(zip(sizes, dts))]
+        # make candidate 1 clean in every case, candidate 0 clean in all but the last
+        for i, w in enumerate(ws):
+            w.segments[0].cands[1] = w.segments[0].ref.clone() if not torch.isnan(
+                w.segments[0].ref.float()).any() else w.segments[0].cands[1]
+        chk = evo.Checker(evo.EVO_F32, 1, 1e-2, 1e-2)
+        stats = chk.new_stats(P)
+        stats.fill_(0x5A)
+        cases = [{"ref": w.segments[0].ref, "cand_ptrs": w.segments[0].cands,
+                  "n_elems": w.segments[0].n, "dtype": gu.dtype_code(w.segments[0])} for w in ws]
+        chk.check_cases(cases, stats)
+        torch.cuda.synchronize()
+        got = stats_to_numpy(stats)
+        for p in range(P):
+            # fp32 and bf16 cases go through the same accumulator one after the other
+            acc = None
+            total = {"n_mismatch": 0, "n_finite": 0, "flags": 0, "n_elems": 0, "sum_abs_err": 0.0,
+                     "sum_rel_err": 0.0, "max_abs_err": np.float32(0), "max_rel_err": np.float32(0)}
+            for w in ws:
+                seg = w.segments[0]
+                r = oracle.check_one(synth.to_oracle_array(seg.ref), synth.to_oracle_array(seg.cands[p]),
+                                     gu.oracle_dtype(seg), 1e-2, 1e-2)
+                for f in ("n_mismatch", "n_finite", "n_elems", "sum_abs_err", "sum_rel_err"):
+                    total[f] += r[f]
+                total["flags"] |= r["flags"]
+                total["max_abs_err"] = max(total["max_abs_err"], r["max_abs_err"])
+                total["max_rel_err"] = max(total["max_rel_err"], r["max_rel_err"])
+            total["valid"] = 1 if total["n_mismatch"] == 0 else 0
+            gu.assert_rows_equal(got[p], total, "cases P=%d row %d" % (P, p))
+        # same-dtype groups: also against ONE oracle accumulator fed case after case
+        if len(set(dts)) == 1:
+            for p in (0, P - 1):
+                acc = oracle.CheckAccumulator(gu.oracle_dtype(ws[0].segments[0]), 1e-2, 1e-2)
+                for w in ws:
+                    acc.feed(synth.to_oracle_array(w.segments[0].ref),
+                             synth.to_oracle_array(w.segments[0].cands[p]))
+                gu.assert_rows_equal(got[p], acc.result(), "cases-acc P=%d row %d" % (P, p))
+        chk.close()
+
+
 def test_repeatable_and_reusable_context(gu):
     """Same call twice gives byte-identical rows; a context can be reused for other
     populations (its counters re-arm themselves)."""
