@@ -82,6 +82,9 @@ def _load(path: str = None):
         lib.oracle_check_chunk.restype = None
         lib.oracle_fitness.argtypes = [ctypes.c_void_p] * 2 + [ctypes.c_uint32] * 2 + [ctypes.c_void_p] * 7
         lib.oracle_fitness.restype = ctypes.c_int
+        lib.oracle_select_elite.argtypes = [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint32,
+                                            ctypes.c_void_p]
+        lib.oracle_select_elite.restype = ctypes.c_uint32
         lib.oracle_acc_size.restype = ctypes.c_uint32
         assert lib.oracle_acc_size() == ctypes.sizeof(_Acc)
         _libs[key] = lib
@@ -185,6 +188,15 @@ def fitness(timings, baseline, valid, lib_path: str = None) -> dict:
     }
 
 
+def select_elite(fitness_values, k: int, lib_path: str = None) -> dict:
+    """Indices of the k best feasible candidates (fitness > 0), best first."""
+    lib = _load(lib_path)
+    f = np.ascontiguousarray(fitness_values, dtype=np.float32).reshape(-1)
+    out = np.empty(max(1, k), np.uint32)
+    n = lib.oracle_select_elite(f.ctypes.data, f.size, k, out.ctypes.data)
+    return {"elite": out[:k].copy(), "n_elite": int(n)}
+
+
 class Variant:
     """The same interface bound to another build of the C file (used by the tests
     that check the pins catch planted mistakes)."""
@@ -207,3 +219,6 @@ class Variant:
 
     def fitness(self, timings, baseline, valid):
         return fitness(timings, baseline, valid, self.lib_path)
+
+    def select_elite(self, fitness_values, k):
+        return select_elite(fitness_values, k, self.lib_path)

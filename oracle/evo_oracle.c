@@ -257,4 +257,38 @@ int oracle_fitness(const float *timings, const float *baseline, uint32_t P,
     return 0;
 }
 
+/*
+ * Elite preservation (population management, Sec. 3.2.2; the EoH-style baseline of the
+ * parameter-settings appendix keeps the best 4 of parents plus offspring): the indices of
+ * the k candidates with the largest fitness, best first, equal fitness in index order.
+ * Only feasible candidates (fitness > 0) qualify; unused slots hold P.  Selection by
+ * repeated scan -- O(P*k), no sort.  Returns the number of slots filled.
+ */
+uint32_t oracle_select_elite(const float *fitness, uint32_t P, uint32_t k, uint32_t *elite)
+{
+    uint32_t filled = 0;
+    for (uint32_t r = 0; r < k; ++r)
+        elite[r] = P;
+    for (uint32_t r = 0; r < k; ++r) {
+        uint32_t best = P;
+        for (uint32_t i = 0; i < P; ++i) {
+            int taken = 0;
+            if (!(fitness[i] > 0.0f))
+                continue;
+            for (uint32_t q = 0; q < r; ++q)
+                if (elite[q] == i)
+                    taken = 1;
+            if (taken)
+                continue;
+            if (best == P || fitness[i] > fitness[best])
+                best = i; /* strict: the first of equal fitness wins */
+        }
+        if (best == P)
+            break;
+        elite[r] = best;
+        filled = r + 1;
+    }
+    return filled;
+}
+
 uint32_t oracle_acc_size(void) { return (uint32_t)sizeof(oracle_check_acc); }

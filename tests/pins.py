@@ -312,8 +312,31 @@ def pin_unusable_timing_rows(orc):
     assert bad_base["median_ms"][0] == 2.5
 
 
+def pin_select_elite(orc):
+    """Elite selection against a stable library sort and a hand-made case."""
+    f = np.array([0.5, 2.0, 0.0, 2.0, 1.5, 0.0, 3.0, 2.0], np.float32)
+    got = orc.select_elite(f, 4)
+    assert got["elite"].tolist() == [6, 1, 3, 7] and got["n_elite"] == 4   # ties in index order
+    got = orc.select_elite(f, 8)
+    assert got["elite"].tolist() == [6, 1, 3, 7, 4, 0, 8, 8] and got["n_elite"] == 6
+    got = orc.select_elite(np.zeros(5, np.float32), 3)
+    assert got["elite"].tolist() == [5, 5, 5] and got["n_elite"] == 0
+    got = orc.select_elite(np.array([1.0], np.float32), 1)
+    assert got["elite"].tolist() == [0] and got["n_elite"] == 1
+    rng = np.random.default_rng(3)
+    for P, k in ((1, 1), (17, 4), (256, 8), (1000, 1000), (333, 50)):
+        f = rng.choice(np.array([0, 0.5, 0.75, 1, 1.25, 2, np.inf], np.float32), P)
+        some = rng.random(P) < 0.3
+        f[some] = rng.random(int(some.sum())).astype(np.float32)
+        order = np.lexsort((np.arange(P), -f.astype(np.float64)))   # stable: fitness desc, index asc
+        order = [int(i) for i in order if f[i] > 0][:k]
+        got = orc.select_elite(f, k)
+        assert got["n_elite"] == len(order)
+        assert got["elite"].tolist() == order + [P] * (k - len(order)), (P, k)
+
+
 ALL_PINS = [
     pin_truth_table, pin_flag_classes, pin_worked_check_examples, pin_worked_fitness_examples,
     pin_numpy_isclose, pin_sums_and_maxima, pin_invariants, pin_bf16_widening,
-    pin_median_and_speedup, pin_unusable_timing_rows,
+    pin_median_and_speedup, pin_unusable_timing_rows, pin_select_elite,
 ]

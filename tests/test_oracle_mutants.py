@@ -41,6 +41,9 @@ MUTANTS = [
     ("no_floor", "pop->best_speedup = (best_fit > 1.0f) ? best_fit : 1.0f;", "pop->best_speedup = best_fit;"),
     ("zero_sample_accepted", "if (!(row[k] > 0.0f) || isinf(row[k]))", "if (!(row[k] >= 0.0f) || isinf(row[k]))"),
     ("inf_sample_accepted", "if (!(row[k] > 0.0f) || isinf(row[k]))", "if (!(row[k] > 0.0f))"),
+    ("elite_last_of_ties", "if (best == P || fitness[i] > fitness[best])", "if (best == P || fitness[i] >= fitness[best])"),
+    ("elite_takes_infeasible", "            if (!(fitness[i] > 0.0f))\n                continue;", "            if (0)\n                continue;"),
+    ("elite_worst_first", "if (best == P || fitness[i] > fitness[best])", "if (best == P || fitness[i] < fitness[best])"),
     ("valid_rate_over_T", "(float)n_valid / (float)P", "(float)n_valid / (float)T"),
 ]
 
