@@ -233,6 +233,22 @@ def main() -> int:
         "hbm_gbps_whole_step": alg_bytes / (wall / args.steps) / 1e9,
     }
 
+    # Outside the timed step: elite selection (population management) on the same rows.
+    k_elite = min(4, P)
+    elite = torch.zeros(k_elite, dtype=torch.int32, device="cuda")
+    n_elite = torch.zeros(1, dtype=torch.int32, device="cuda")
+    sel = []
+    for _ in range(10):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        chk.select_elite(stats, P, k_elite, elite, n_elite, stream=stream)
+        b.record(stream)
+        sel.append((a, b))
+    torch.cuda.synchronize()
+    sel_us = sorted(1e3 * a.elapsed_time(b) for a, b in sel)
+    out["elite_select_us"] = {"median": sel_us[len(sel_us) // 2], "k": k_elite,
+                              "elite": elite.cpu().tolist()}
+
     got = stats_to_numpy(stats)
     pop = summary_to_numpy(summary)[0]
     out["result"] = {"n_valid": int(pop["n_valid"]), "best_idx": int(pop["best_idx"]),

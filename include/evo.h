@@ -207,6 +207,21 @@ EVO_API int evo_fitness(evo_check_t *c, const float *timings, const float *basel
                 evo_pop_summary *summary);
 
 /*
+ * Population management of Sec. 3.2.2 (elite preservation): the indices of the k
+ * candidates with the largest fitness, best first, equal fitness in index order.  Only
+ * feasible candidates (fitness > 0: valid, with usable timings) qualify; slots beyond
+ * their number are set to P.
+ *   stats     device, P rows; `fitness` is read (as left by an evo_fitness call that
+ *             precedes this one in stream order)
+ *   elite     device, k entries, all written
+ *   n_elite   device, one entry: min(k, number of feasible candidates); may be NULL
+ * Errors: EVO_ERR_HANDLE, EVO_ERR_NULL (stats, elite), EVO_ERR_SIZE (P == 0, k == 0,
+ * k > P, P > 65535), EVO_ERR_ALIGN, EVO_ERR_DEVICE.
+ */
+EVO_API int evo_select_elite(evo_check_t *c, const evo_stats *stats, uint32_t P, uint32_t k,
+                             void *stream, uint32_t *elite, uint32_t *n_elite);
+
+/*
  * Destroys a context: waits for the device to go idle, frees the library's scratch
  * memory.  NULL, unknown and already destroyed handles are ignored
  * (evo_check_destroy returns EVO_ERR_HANDLE for them and does nothing else).

@@ -80,11 +80,12 @@ def _load() -> ctypes.CDLL:
     h.evo_check_segmented.argtypes = [vp, ctypes.POINTER(EvoSegment), u32, vp, vp, u32]
     h.evo_check_cases.argtypes = [vp, ctypes.POINTER(EvoSegment), u32, vp, vp]
     h.evo_fitness.argtypes = [vp, vp, vp, u32, u32, vp, vp, vp]
+    h.evo_select_elite.argtypes = [vp, vp, u32, u32, vp, vp, vp]
     h.evo_check_destroy.argtypes = [vp]
     h.evo_strerror.argtypes = [ctypes.c_int]
     h.evo_strerror.restype = ctypes.c_char_p
     for name in ("evo_check_create", "evo_check_batch", "evo_check_segmented", "evo_check_cases",
-                 "evo_fitness",
+                 "evo_fitness", "evo_select_elite",
                  "evo_check_destroy"):
         getattr(h, name).restype = ctypes.c_int
     return h
@@ -176,6 +177,13 @@ def evo_fitness(ctx: int, timings, baseline, P: int, T: int, stream, stats, summ
         raise EvoError(rc, "evo_fitness")
 
 
+def evo_select_elite(ctx: int, stats, P: int, k: int, stream, elite, n_elite=None) -> None:
+    rc = lib.evo_select_elite(ctx, _ptr(stats), int(P), int(k), _stream(stream), _ptr(elite),
+                              _ptr(n_elite))
+    if rc != 0:
+        raise EvoError(rc, "evo_select_elite")
+
+
 def evo_check_destroy(ctx: int) -> int:
     return lib.evo_check_destroy(ctx)
 
@@ -233,6 +241,13 @@ class Checker:
         P, T = timings.shape
         evo_fitness(self.ctx, timings, baseline, P, T,
                     stream if stream is not None else torch.cuda.current_stream(), stats, summary)
+
+
+    def select_elite(self, stats: torch.Tensor, P: int, k: int, elite: torch.Tensor,
+                     n_elite: Optional[torch.Tensor] = None, stream=None) -> None:
+        evo_select_elite(self.ctx, stats, P, k,
+                         stream if stream is not None else torch.cuda.current_stream(), elite,
+                         n_elite)
 
 
 def stats_to_numpy(stats: torch.Tensor) -> np.ndarray:

@@ -421,6 +421,19 @@ int evo_fitness(evo_check_t *c, const float *timings, const float *baseline, uin
                                    c->d_fit_ticket, st));
 }
 
+int evo_select_elite(evo_check_t *c, const evo_stats *stats, uint32_t P, uint32_t k, void *stream,
+                     uint32_t *elite, uint32_t *n_elite) {
+    if (!is_live(c)) return EVO_ERR_HANDLE;
+    if (!stats || !elite) return EVO_ERR_NULL;
+    if (P == 0 || k == 0 || k > P || P > kMaxP) return EVO_ERR_SIZE;
+    if ((reinterpret_cast<uintptr_t>(stats) & 7u) || (reinterpret_cast<uintptr_t>(elite) & 3u) ||
+        (reinterpret_cast<uintptr_t>(n_elite) & 3u))
+        return EVO_ERR_ALIGN;
+    const int rc = bind_device(c);
+    if (rc != EVO_OK) return rc;
+    return dev(evo::launch_select(stats, P, k, elite, n_elite, static_cast<hipStream_t>(stream)));
+}
+
 int evo_check_destroy(evo_check_t *c) {
     {
         std::lock_guard<std::mutex> lk(g_mu);

@@ -160,4 +160,7 @@ hipError_t launch_fitness(const float *timings, const float *baseline, uint32_t 
                           evo_stats *stats, evo_pop_summary *summary, float *base_median,
                           uint32_t *ticket, hipStream_t stream);
 
+hipError_t launch_select(const evo_stats *stats, uint32_t P, uint32_t k, uint32_t *elite,
+                         uint32_t *n_elite, hipStream_t stream);
+
 }  // namespace evo

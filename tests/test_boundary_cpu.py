@@ -29,7 +29,7 @@ def declared_functions():
 def test_header_declares_the_documented_entry_points():
     assert declared_functions() == ["evo_check_batch", "evo_check_cases", "evo_check_create",
                                     "evo_check_destroy", "evo_check_segmented", "evo_fitness",
-                                    "evo_strerror"]
+                                    "evo_select_elite", "evo_strerror"]
 
 
 def test_library_exports_every_declared_symbol(evo):
@@ -165,6 +165,20 @@ def test_fitness_validates_before_any_launch(evo):
     assert call(h, 64, 64, 4, 4097, None, 512, None) == -3
     assert call(h, 66, 64, 4, 10, None, 512, None) == -5
     assert call(h, 64, 64, 4, 10, None, 516, None) == -5
+    assert evo.lib.evo_check_destroy(h) == 0
+
+
+def test_select_elite_validates_before_any_launch(evo):
+    rc, h = _create(evo, 0, 1, 0.0, 0.0)
+    call = evo.lib.evo_select_elite
+    assert call(h, None, 4, 2, None, 64, None) == -1
+    assert call(h, 64, 4, 2, None, None, None) == -1
+    assert call(h, 64, 0, 1, None, 64, None) == -3
+    assert call(h, 64, 4, 0, None, 64, None) == -3
+    assert call(h, 64, 4, 5, None, 64, None) == -3
+    assert call(h, 64, 70000, 5, None, 64, None) == -3
+    assert call(h, 68, 4, 2, None, 64, None) == -5
+    assert call(h, 64, 4, 2, None, 66, None) == -5
     assert evo.lib.evo_check_destroy(h) == 0
 
 

@@ -374,6 +374,37 @@ def test_fitness_population_and_unusable_rows(gu):
         chk.close()
 
 
+@pytest.mark.parametrize("P,k", [(1, 1), (5, 5), (8, 4), (256, 4), (300, 17), (1000, 1000),
+                                 (4097, 64), (65535, 300)])
+def test_select_elite(gu, P, k):
+    """Top-k feasible candidates by fitness, ties in index order, against the oracle."""
+    _say("elite P=%d k=%d" % (P, k))
+    import oracle
+    import paper_2510_03760_amd as evo
+    g = torch.Generator(device="cuda")
+    g.manual_seed(P * 31 + k)
+    levels = torch.tensor([0.0, 0.0, 0.5, 0.75, 1.0, 1.25, 2.0, float("inf")], device="cuda")
+    fit = levels[torch.randint(0, 8, (P,), generator=g, device="cuda")]
+    some = torch.rand(P, generator=g, device="cuda") < 0.4
+    fit = torch.where(some, torch.rand(P, generator=g, device="cuda") * 3, fit)
+    for variant in range(3):
+        if variant == 1:
+            fit = torch.zeros(P, device="cuda")           # nobody feasible
+        if variant == 2:
+            fit = torch.full((P,), 1.5, device="cuda")    # everybody equal
+        chk = evo.Checker(evo.EVO_F32, 1, 0.0, 0.0)
+        stats = chk.new_stats(P)
+        stats.view(P, 72)[:, 60:64] = fit.contiguous().view(torch.uint8).view(P, 4)
+        elite = torch.full((k,), 0x7FFFFFFF, dtype=torch.int32, device="cuda")
+        n_elite = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+        chk.select_elite(stats, P, k, elite, n_elite)
+        torch.cuda.synchronize()
+        want = oracle.select_elite(fit.cpu().numpy(), k)
+        assert elite.cpu().numpy().astype(np.uint32).tolist() == want["elite"].tolist()
+        assert int(n_elite[0]) == want["n_elite"]
+        chk.close()
+
+
 def test_errors_on_live_device(gu):
     """Argument errors are reported before anything is enqueued, also with a GPU."""
     _say("errors")
