@@ -21,6 +21,7 @@ _LIB = os.path.join(_HERE, "libevo_oracle.so")
 
 F32 = 0
 BF16 = 1
+F16 = 2
 
 F_CAND_NAN = 1 << 0
 F_CAND_INF = 1 << 1
@@ -85,6 +86,8 @@ def _load(path: str = None):
         lib.oracle_select_elite.argtypes = [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint32,
                                             ctypes.c_void_p]
         lib.oracle_select_elite.restype = ctypes.c_uint32
+        lib.oracle_half_to_float.argtypes = [ctypes.c_uint16]
+        lib.oracle_half_to_float.restype = ctypes.c_float
         lib.oracle_acc_size.restype = ctypes.c_uint32
         assert lib.oracle_acc_size() == ctypes.sizeof(_Acc)
         _libs[key] = lib
@@ -92,8 +95,10 @@ def _load(path: str = None):
 
 
 def _as_elems(x, dtype: int) -> np.ndarray:
-    """Flat contiguous view: float32 for F32, uint16 bit patterns for BF16."""
+    """Flat contiguous view: float32 for F32, uint16 bit patterns for BF16 and F16."""
     a = np.ascontiguousarray(x).reshape(-1)
+    if dtype == F16 and a.dtype == np.float16:
+        a = a.view(np.uint16)
     want = np.float32 if dtype == F32 else np.uint16
     if a.dtype != want:
         raise TypeError("oracle expects %s elements, got %s" % (np.dtype(want), a.dtype))
@@ -188,6 +193,10 @@ def fitness(timings, baseline, valid, lib_path: str = None) -> dict:
     }
 
 
+def half_to_float(bits: int, lib_path: str = None) -> np.float32:
+    return np.float32(_load(lib_path).oracle_half_to_float(int(bits)))
+
+
 def select_elite(fitness_values, k: int, lib_path: str = None) -> dict:
     """Indices of the k best feasible candidates (fitness > 0), best first."""
     lib = _load(lib_path)
@@ -201,7 +210,7 @@ class Variant:
     """The same interface bound to another build of the C file (used by the tests
     that check the pins catch planted mistakes)."""
 
-    F32, BF16 = F32, BF16
+    F32, BF16, F16 = F32, BF16, F16
     F_CAND_NAN, F_CAND_INF, F_REF_NAN, F_REF_INF = F_CAND_NAN, F_CAND_INF, F_REF_NAN, F_REF_INF
     F_NAN_SITE_DIFF, F_INF_DIFF = F_NAN_SITE_DIFF, F_INF_DIFF
 
@@ -222,3 +231,6 @@ class Variant:
 
     def select_elite(self, fitness_values, k):
         return select_elite(fitness_values, k, self.lib_path)
+
+    def half_to_float(self, bits):
+        return half_to_float(bits, self.lib_path)

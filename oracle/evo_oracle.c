@@ -39,7 +39,7 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
 
 enum {
     ORACLE_F_CAND_NAN      = 1u << 0, /* some candidate element is NaN          */
@@ -78,9 +78,41 @@ void oracle_check_init(oracle_check_acc *a)
     a->valid = 1u; /* an empty tensor has no mismatch */
 }
 
+/* IEEE-754 binary16 -> binary32, exact: 1 sign, 5 exponent (bias 15), 10 fraction bits.
+ * Subnormal halves are normalised by hand; Inf/NaN keep their payload. */
+static float half_to_float(uint16_t h)
+{
+    const uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    uint32_t exp = (h >> 10) & 0x1fu;
+    uint32_t frac = h & 0x3ffu;
+    uint32_t w;
+    float f;
+    if (exp == 0x1fu) {                 /* Inf or NaN */
+        w = sign | 0x7f800000u | (frac << 13);
+    } else if (exp != 0) {              /* normal: rebias 15 -> 127 */
+        w = sign | ((exp + 112u) << 23) | (frac << 13);
+    } else if (frac == 0) {             /* zero */
+        w = sign;
+    } else {                            /* subnormal: value = frac * 2^-24 */
+        int shift = 0;
+        while (!(frac & 0x400u)) {
+            frac <<= 1;
+            ++shift;
+        }
+        frac &= 0x3ffu;
+        w = sign | ((uint32_t)(113 - shift) << 23) | (frac << 13);
+    }
+    memcpy(&f, &w, sizeof f);
+    return f;
+}
+
+float oracle_half_to_float(uint16_t h) { return half_to_float(h); }
+
 /* bf16 is the upper half of an IEEE-754 binary32: widening is exact. */
 static float widen(const void *base, uint64_t i, int dtype)
 {
+    if (dtype == ORACLE_F16)
+        return half_to_float(((const uint16_t *)base)[i]);
     if (dtype == ORACLE_BF16) {
         uint16_t h = ((const uint16_t *)base)[i];
         uint32_t w = (uint32_t)h << 16;

@@ -243,6 +243,26 @@ def pin_bf16_widening(orc):
     assert a == b and a["flags"] != 0  # random bits include Inf and NaN patterns
 
 
+def pin_f16_widening(orc):
+    """binary16 inputs: every one of the 65536 bit patterns widens as numpy's float16 does,
+    and a check on halves equals the check on the same values as binary32."""
+    all_bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    want = all_bits.view(np.float16).astype(np.float32)
+    for b in range(0, 65536, 1):
+        got = orc.half_to_float(b)
+        w = want[b]
+        assert (np.isnan(got) and np.isnan(w)) or got.tobytes() == w.tobytes(), hex(b)
+    rng = np.random.default_rng(8)
+    bits_r = rng.integers(0, 1 << 16, 20000).astype(np.uint16)
+    bits_c = bits_r.copy()
+    move = rng.random(20000) < 0.5
+    bits_c[move] = (bits_c[move].astype(np.int32) + rng.integers(-3, 4, move.sum())).clip(0, 65535).astype(np.uint16)
+    a = orc.check_one(bits_r, bits_c, orc.F16, 1e-2, 1e-2)
+    b = orc.check_one(bits_r.view(np.float16).astype(np.float32),
+                      bits_c.view(np.float16).astype(np.float32), orc.F32, 1e-2, 1e-2)
+    assert a == b and a["flags"] != 0
+
+
 def _rank_select(row, k):
     """k-th smallest by counting, O(T^2): no sort involved."""
     T = len(row)
@@ -337,6 +357,6 @@ def pin_select_elite(orc):
 
 ALL_PINS = [
     pin_truth_table, pin_flag_classes, pin_worked_check_examples, pin_worked_fitness_examples,
-    pin_numpy_isclose, pin_sums_and_maxima, pin_invariants, pin_bf16_widening,
+    pin_numpy_isclose, pin_sums_and_maxima, pin_invariants, pin_bf16_widening, pin_f16_widening,
     pin_median_and_speedup, pin_unusable_timing_rows, pin_select_elite,
 ]

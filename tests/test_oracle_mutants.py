@@ -31,6 +31,9 @@ MUTANTS = [
     ("inf_diff_ignores_equality", "&& !c_nan && !r_nan && c != r)", "&& !c_nan && !r_nan)"),
     ("cand_ref_flags_swapped", "if (c_inf) a->flags |= ORACLE_F_CAND_INF;", "if (c_inf) a->flags |= ORACLE_F_REF_INF;"),
     ("bf16_shift", "(uint32_t)h << 16", "(uint32_t)h << 15"),
+    ("f16_bias", "w = sign | ((exp + 112u) << 23) | (frac << 13);", "w = sign | ((exp + 111u) << 23) | (frac << 13);"),
+    ("f16_subnormal_exponent", "w = sign | ((uint32_t)(113 - shift) << 23) | (frac << 13);", "w = sign | ((uint32_t)(112 - shift) << 23) | (frac << 13);"),
+    ("f16_nan_payload_dropped", "w = sign | 0x7f800000u | (frac << 13);", "w = sign | 0x7f800000u;"),
     ("median_upper_middle", "const float s = scratch[T / 2 - 1] + scratch[T / 2];", "const float s = scratch[T / 2] + scratch[T / 2];"),
     ("median_no_half", "*median = 0.5f * s;", "*median = s;"),
     ("odd_median_off_by_one", "*median = scratch[T / 2];", "*median = scratch[(T - 1) / 2 + (T > 1)];"),
