@@ -6,7 +6,7 @@ batched (or segmented) tolerance check of every candidate against its reference,
 then the median-timing / speedup / fitness reduction.  Inputs are resident in HBM
 before the timed region starts.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c4|c5|cases]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c3h|c4|c5|cases]
                     [--no-cpu-baseline] [--copy-calibration]
 
 --copy-calibration runs only a plain device-to-device copy of known size (used to
@@ -60,6 +60,9 @@ def build_workload(name: str):
         return synth.ragged_f32("cuda", P_s=32, T=100)
     if name == "c5":
         return synth.heavy_tail_f32("cuda", log2n=30, P=8, T=1000)
+    if name == "c3h":
+        import torch
+        return synth.softmax_bf16("cuda", B=32, R=128, C=4096, P=64, T=100, dtype=torch.float16)
     if name == "cases":
         return synth.multi_case_f32("cuda", K=5, side=4096, P=16, T=100)
     raise SystemExit("unknown workload %r" % name)
@@ -78,7 +81,7 @@ def cpu_baseline(w, budget_elems: int):
     rows = []
     for seg in w.segments:
         m = seg.n if frac >= 1.0 else max(1, int(seg.n * frac))
-        dt = oracle.BF16 if seg.dtype_name == "bf16" else oracle.F32
+        dt = {"bf16": oracle.BF16, "f16": oracle.F16}.get(seg.dtype_name, oracle.F32)
         ref = synth.to_oracle_array(seg.ref[:m])
         for c in seg.cands:
             ch = synth.to_oracle_array(c[:m])
@@ -151,7 +154,7 @@ def main() -> int:
     w = build_workload(args.workload)
     torch.cuda.synchronize()
     segs = w.segments
-    dcode = lambda s: evo.EVO_BF16 if s.dtype_name == "bf16" else evo.EVO_F32  # noqa: E731
+    dcode = lambda s: {"bf16": evo.EVO_BF16, "f16": evo.EVO_F16}.get(s.dtype_name, evo.EVO_F32)  # noqa: E731
     chk = evo.Checker(dcode(segs[0]), segs[0].n, w.atol, w.rtol)
     P = w.P
     stats = chk.new_stats(P)
@@ -217,7 +220,7 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16->f32" if segs[0].dtype_name == "bf16" else "f32",
+        "dtype": {"bf16": "bf16->f32", "f16": "f16->f32"}.get(segs[0].dtype_name, "f32"),
         "data": "synthetic",
         "config": {"workload": w.name, "P": P, "cand_elems": w.cand_elems,
                    "algorithmic_bytes": alg_bytes, "T": int(w.timings.shape[1]),

@@ -24,8 +24,8 @@
  *     writes caller memory beyond what each call documents.
  *   - Tensors are contiguous and are read as flat arrays; their shape plays no
  *     part in a tolerance check.  EVO_BF16 elements are the upper 16 bits of an
- *     IEEE-754 binary32, little endian; they are widened exactly and every
- *     operation is done in binary32.
+ *     IEEE-754 binary32 and EVO_F16 elements are IEEE-754 binary16, both little
+ *     endian; they are widened exactly and every operation is done in binary32.
  *   - Every call that takes a stream only enqueues work on it and returns; results
  *     are defined once the caller has synchronised that stream.  `stream` is a
  *     hipStream_t passed as void* (NULL = the null stream).
@@ -52,7 +52,7 @@ extern "C" {
 
 typedef struct evo_check evo_check_t; /* opaque, owned by the library */
 
-typedef enum { EVO_F32 = 0, EVO_BF16 = 1 } evo_dtype;
+typedef enum { EVO_F32 = 0, EVO_BF16 = 1, EVO_F16 = 2 } evo_dtype;
 
 typedef enum {
     EVO_OK         = 0,

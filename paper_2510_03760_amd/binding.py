@@ -20,6 +20,7 @@ lib_path = os.path.join(_HERE, "libevo.so")
 
 EVO_F32 = 0
 EVO_BF16 = 1
+EVO_F16 = 2
 
 
 class EvoError(RuntimeError):

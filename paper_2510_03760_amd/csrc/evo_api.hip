@@ -61,9 +61,9 @@ bool is_live(evo_check *c) {
     return c != nullptr && g_live.count(c) != 0;
 }
 
-uint32_t elem_size(uint32_t dtype) { return dtype == EVO_BF16 ? 2u : 4u; }
+uint32_t elem_size(uint32_t dtype) { return dtype == EVO_F32 ? 4u : 2u; }
 
-bool dtype_ok(uint32_t dtype) { return dtype == EVO_F32 || dtype == EVO_BF16; }
+bool dtype_ok(uint32_t dtype) { return dtype == EVO_F32 || dtype == EVO_BF16 || dtype == EVO_F16; }
 
 int dev(hipError_t e) { return e == hipSuccess ? EVO_OK : (e == hipErrorOutOfMemory ? EVO_ERR_NOMEM : EVO_ERR_DEVICE); }
 
@@ -262,7 +262,11 @@ int run_check(evo_check *c, const std::vector<HostSeg> &segs, hipStream_t stream
     } catch (const std::bad_alloc &) {
         return EVO_ERR_NOMEM;
     }
-    for (const HostSeg &h : segs) total_ptrs += h.P;
+    uint32_t dtype_set = 0;
+    for (const HostSeg &h : segs) {
+        total_ptrs += h.P;
+        dtype_set |= 1u << h.dtype;
+    }
 
     const size_t S = segs.size();
     // first-level rows (one set per job) and second-level rows (at most one set per job);
@@ -288,7 +292,7 @@ int run_check(evo_check *c, const std::vector<HostSeg> &segs, hipStream_t stream
             for (uint32_t p = 0; p < segs[s].P; ++p)
                 tab.ptrs[descs[s].ptr0 + p] = reinterpret_cast<uint64_t>(segs[s].cand_ptrs[p]);
         }
-        return dev(evo::launch_check_inline(tab, (uint32_t)S, total_jobs, c->atol, c->rtol,
+        return dev(evo::launch_check_inline(dtype_set, tab, (uint32_t)S, total_jobs, c->atol, c->rtol,
                                             c->d_partials, c->d_tickets, stats, stream));
     }
 
@@ -310,7 +314,7 @@ int run_check(evo_check *c, const std::vector<HostSeg> &segs, hipStream_t stream
     slot->in_flight = true;
 
     return dev(evo::launch_check(
-        static_cast<const SegDesc *>(c->d_table),
+        dtype_set, static_cast<const SegDesc *>(c->d_table),
         reinterpret_cast<const uint64_t *>(static_cast<char *>(c->d_table) + desc_bytes), (uint32_t)S,
         total_jobs, c->atol, c->rtol, c->d_partials, c->d_tickets, stats, stream));
 }

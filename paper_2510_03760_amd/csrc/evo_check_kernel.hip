@@ -50,6 +50,12 @@ template <> struct Tile<EVO_BF16> {
     static constexpr int kE = kVec * kNV;
     using elem_t = uint16_t;
 };
+template <> struct Tile<EVO_F16> : Tile<EVO_BF16> {};
+
+// IEEE binary16 -> binary32 (v_cvt_f32_f16: exact, subnormals included).
+__device__ __forceinline__ float half_bits_to_f32(uint16_t h) {
+    return (float)__builtin_bit_cast(_Float16, h);
+}
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 128-bit load
 
@@ -67,12 +73,19 @@ __device__ __forceinline__ void widen(const u32x4 &raw, float *out) {
         out[1] = as_f32(raw.y);
         out[2] = as_f32(raw.z);
         out[3] = as_f32(raw.w);
-    } else {
+    } else if constexpr (DT == EVO_BF16) {
         const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             out[2 * k] = as_f32(w[k] << 16);
             out[2 * k + 1] = as_f32(w[k] & 0xffff0000u);
+        }
+    } else {
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            out[2 * k] = half_bits_to_f32((uint16_t)(w[k] & 0xffffu));
+            out[2 * k + 1] = half_bits_to_f32((uint16_t)(w[k] >> 16));
         }
     }
 }
@@ -81,8 +94,10 @@ template <uint32_t DT>
 __device__ __forceinline__ float load_elem(const void *base, uint64_t idx) {
     if constexpr (DT == EVO_F32) {
         return static_cast<const float *>(base)[idx];
-    } else {
+    } else if constexpr (DT == EVO_BF16) {
         return as_f32((uint32_t) static_cast<const uint16_t *>(base)[idx] << 16);
+    } else {
+        return half_bits_to_f32(static_cast<const uint16_t *>(base)[idx]);
     }
 }
 
@@ -406,7 +421,7 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_p
 
 // One job: a chunk of tiles of one segment for up to kWaves candidate groups.
 template <uint32_t DT>
-__device__ void run_job(const SegDesc &sd, const uint64_t *ptr_table, uint32_t job_local,
+__device__ __forceinline__ void run_job(const SegDesc &sd, const uint64_t *ptr_table, uint32_t job_local,
                         uint32_t job_global, float atol, float rtol, Partial *partials,
                         ExactAcc (*exact_acc)[kG],
                         Partial (*wave_part)[kG], uint16_t (*redo)[kMaxTilesPerWave]) {
@@ -567,7 +582,7 @@ __device__ __forceinline__ void load_row(const Partial *row, uint64_t (&w)[6]) {
 
 // Level 1: rows of chunks [first, first + count) of group block `gblock` -> one row per
 // candidate slot in rows1[bundle].  Thread t: slot row t % 64, quarter t / 64 of the bundle.
-__device__ void fold_bundle(const SegDesc &sd, uint32_t gblock, uint32_t first, uint32_t count,
+__device__ __forceinline__ void fold_bundle(const SegDesc &sd, uint32_t gblock, uint32_t first, uint32_t count,
                             const Partial *rows0, Partial *row1, Partial *fold) {
     static_assert(kRowsPerJob <= 64 && kThreads == 256 && kFold == 16, "thread layout");
     const uint32_t slot_row = threadIdx.x % 64u;
@@ -619,7 +634,7 @@ __device__ __forceinline__ void write_stats(evo_stats *dst, const Partial &a, ui
     *dst = s;
 }
 
-__device__ void finalize_segment(const SegDesc &sd, const Partial *rows1, uint32_t units,
+__device__ __forceinline__ void finalize_segment(const SegDesc &sd, const Partial *rows1, uint32_t units,
                                  evo_stats *stats, Partial *case_rows, Partial *fold) {
     uint32_t pc = 1;
     while (pc < sd.P && pc < (uint32_t)kThreads) pc <<= 1;   // candidates per pass (power of 2)
@@ -671,7 +686,7 @@ __device__ void finalize_segment(const SegDesc &sd, const Partial *rows1, uint32
 
 // Level 3 (case groups only): candidate p over all cases of the group, cases added in
 // case order.
-__device__ void write_case_group(const SegDesc *descs, const SegDesc &sd, const Partial *case_rows,
+__device__ __forceinline__ void write_case_group(const SegDesc *descs, const SegDesc &sd, const Partial *case_rows,
                                  evo_stats *stats) {
     for (uint32_t p = threadIdx.x; p < sd.P; p += kThreads) {
         Partial a{};
@@ -687,6 +702,10 @@ __device__ void write_case_group(const SegDesc *descs, const SegDesc &sd, const 
     }
 }
 
+// DTS = set of element types (bit 1 << evo_dtype) this instantiation can meet.  A launch
+// whose segments all have one element type gets a kernel that holds only that type's
+// code, so that its register allocation is not the worst case over all types.
+template <uint32_t DTS>
 __device__ __forceinline__ void check_body(const SegDesc *descs, const uint64_t *ptr_table,
                                            uint32_t S, float atol, float rtol, Partial *partials,
                                            uint32_t *tickets, evo_stats *stats) {
@@ -704,10 +723,18 @@ __device__ __forceinline__ void check_body(const SegDesc *descs, const uint64_t 
     __shared__ ExactAcc exact_acc[kWaves][kG];
     __shared__ Partial wave_part[kWaves][kG];
     __shared__ uint16_t redo[kWaves][kMaxTilesPerWave];
-    if (sd.dtype == EVO_BF16)
-        run_job<EVO_BF16>(sd, ptr_table, job_local, job, atol, rtol, partials, exact_acc, wave_part, redo);
-    else
-        run_job<EVO_F32>(sd, ptr_table, job_local, job, atol, rtol, partials, exact_acc, wave_part, redo);
+    if constexpr ((DTS & (1u << EVO_BF16)) != 0) {
+        if (sd.dtype == EVO_BF16 || DTS == (1u << EVO_BF16))
+            run_job<EVO_BF16>(sd, ptr_table, job_local, job, atol, rtol, partials, exact_acc, wave_part, redo);
+    }
+    if constexpr ((DTS & (1u << EVO_F16)) != 0) {
+        if (sd.dtype == EVO_F16 || DTS == (1u << EVO_F16))
+            run_job<EVO_F16>(sd, ptr_table, job_local, job, atol, rtol, partials, exact_acc, wave_part, redo);
+    }
+    if constexpr ((DTS & (1u << EVO_F32)) != 0) {
+        if (sd.dtype == EVO_F32 || DTS == (1u << EVO_F32))
+            run_job<EVO_F32>(sd, ptr_table, job_local, job, atol, rtol, partials, exact_acc, wave_part, redo);
+    }
 
     // This job's rows are published (run_job fences after writing them).  Two tickets:
     // the bundle of kFold chunks this job belongs to, then the segment (see fold_bundle).
@@ -765,40 +792,60 @@ __device__ __forceinline__ void check_body(const SegDesc *descs, const uint64_t 
         __hip_atomic_store(&case_tickets[sd.case0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+template <uint32_t DTS>
 __global__ void __launch_bounds__(kThreads, EVO_WAVES_PER_EU)
 evo_check_kernel(const SegDesc *__restrict__ descs, const uint64_t *__restrict__ ptr_table,
                  uint32_t S, float atol, float rtol, Partial *__restrict__ partials,
                  uint32_t *__restrict__ tickets, evo_stats *__restrict__ stats) {
-    check_body(descs, ptr_table, S, atol, rtol, partials, tickets, stats);
+    check_body<DTS>(descs, ptr_table, S, atol, rtol, partials, tickets, stats);
 }
 
 // Same kernel with the table inside the kernel argument block.  The block is read in
 // place through the kernel-argument segment pointer (the table is the first argument,
 // at offset 0); naming the by-value parameter would make the compiler copy all of it
 // into per-lane scratch memory.
+template <uint32_t DTS>
 __global__ void __launch_bounds__(kThreads, EVO_WAVES_PER_EU)
 evo_check_kernel_inline(const InlineTable /*read via the segment pointer*/, uint32_t S, float atol,
                         float rtol, Partial *__restrict__ partials,
                         uint32_t *__restrict__ tickets, evo_stats *__restrict__ stats) {
     const InlineTable *tab = (const InlineTable *)__builtin_amdgcn_kernarg_segment_ptr();
-    check_body(tab->descs, tab->ptrs, S, atol, rtol, partials, tickets, stats);
+    check_body<DTS>(tab->descs, tab->ptrs, S, atol, rtol, partials, tickets, stats);
 }
+
+constexpr uint32_t kAllTypes = (1u << EVO_F32) | (1u << EVO_BF16) | (1u << EVO_F16);
 
 }  // namespace
 
-hipError_t launch_check(const SegDesc *d_descs, const uint64_t *d_ptrs, uint32_t S,
-                        uint32_t total_jobs, float atol, float rtol, Partial *partials,
+hipError_t launch_check(uint32_t dtype_set, const SegDesc *d_descs, const uint64_t *d_ptrs,
+                        uint32_t S, uint32_t total_jobs, float atol, float rtol, Partial *partials,
                         uint32_t *tickets, evo_stats *stats, hipStream_t stream) {
-    hipLaunchKernelGGL(evo_check_kernel, dim3(total_jobs), dim3(kThreads), 0, stream, d_descs,
-                       d_ptrs, S, atol, rtol, partials, tickets, stats);
+#define EVO_LAUNCH(DTS_)                                                                         \
+    hipLaunchKernelGGL(evo_check_kernel<DTS_>, dim3(total_jobs), dim3(kThreads), 0, stream, d_descs, \
+                       d_ptrs, S, atol, rtol, partials, tickets, stats)
+    switch (dtype_set) {
+        case 1u << EVO_F32: EVO_LAUNCH(1u << EVO_F32); break;
+        case 1u << EVO_BF16: EVO_LAUNCH(1u << EVO_BF16); break;
+        case 1u << EVO_F16: EVO_LAUNCH(1u << EVO_F16); break;
+        default: EVO_LAUNCH(kAllTypes); break;
+    }
+#undef EVO_LAUNCH
     return hipGetLastError();
 }
 
-hipError_t launch_check_inline(const InlineTable &tab, uint32_t S, uint32_t total_jobs,
-                               float atol, float rtol, Partial *partials, uint32_t *tickets,
-                               evo_stats *stats, hipStream_t stream) {
-    hipLaunchKernelGGL(evo_check_kernel_inline, dim3(total_jobs), dim3(kThreads), 0, stream, tab,
-                       S, atol, rtol, partials, tickets, stats);
+hipError_t launch_check_inline(uint32_t dtype_set, const InlineTable &tab, uint32_t S,
+                               uint32_t total_jobs, float atol, float rtol, Partial *partials,
+                               uint32_t *tickets, evo_stats *stats, hipStream_t stream) {
+#define EVO_LAUNCH(DTS_)                                                                        \
+    hipLaunchKernelGGL(evo_check_kernel_inline<DTS_>, dim3(total_jobs), dim3(kThreads), 0, stream, \
+                       tab, S, atol, rtol, partials, tickets, stats)
+    switch (dtype_set) {
+        case 1u << EVO_F32: EVO_LAUNCH(1u << EVO_F32); break;
+        case 1u << EVO_BF16: EVO_LAUNCH(1u << EVO_BF16); break;
+        case 1u << EVO_F16: EVO_LAUNCH(1u << EVO_F16); break;
+        default: EVO_LAUNCH(kAllTypes); break;
+    }
+#undef EVO_LAUNCH
     return hipGetLastError();
 }
 

@@ -50,7 +50,7 @@ constexpr uint32_t kMaxTilesPerWave = 2048; // per job: bounds the LDS redo list
 
 // Elements one wavefront consumes per tile and per tensor (16 bytes per lane and vector).
 __host__ __device__ constexpr uint32_t tile_elems(uint32_t dtype) {
-    return dtype == EVO_BF16 ? EVO_NV_BF16 * 64 * 8 : EVO_NV_F32 * 64 * 4;
+    return dtype == EVO_F32 ? EVO_NV_F32 * 64 * 4 : EVO_NV_BF16 * 64 * 8;   // 16-bit types alike
 }
 
 // A population of P candidates is cut into groups whose sizes are powers of two:
@@ -148,13 +148,14 @@ static_assert(sizeof(InlineTable) <= 3600, "kernel argument block must stay belo
 // Scratch layout of one launch (J = workgroups, S = segments, C = candidate pointers):
 //   partials: J*kRowsPerJob first-level rows | J*kRowsPerJob second-level rows | C case rows
 //   tickets:  J bundle tickets | S segment tickets | S case-group tickets
-hipError_t launch_check(const SegDesc *d_descs, const uint64_t *d_ptrs, uint32_t S,
-                        uint32_t total_jobs, float atol, float rtol, Partial *partials,
+// dtype_set: OR of (1 << evo_dtype) over the segments of the launch.
+hipError_t launch_check(uint32_t dtype_set, const SegDesc *d_descs, const uint64_t *d_ptrs,
+                        uint32_t S, uint32_t total_jobs, float atol, float rtol, Partial *partials,
                         uint32_t *tickets, evo_stats *stats, hipStream_t stream);
 
-hipError_t launch_check_inline(const InlineTable &tab, uint32_t S, uint32_t total_jobs,
-                               float atol, float rtol, Partial *partials, uint32_t *tickets,
-                               evo_stats *stats, hipStream_t stream);
+hipError_t launch_check_inline(uint32_t dtype_set, const InlineTable &tab, uint32_t S,
+                               uint32_t total_jobs, float atol, float rtol, Partial *partials,
+                               uint32_t *tickets, evo_stats *stats, hipStream_t stream);
 
 hipError_t launch_fitness(const float *timings, const float *baseline, uint32_t P, uint32_t T,
                           evo_stats *stats, evo_pop_summary *summary, float *base_median,

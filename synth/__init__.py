@@ -39,7 +39,7 @@ class Segment:
 
     @property
     def dtype_name(self) -> str:
-        return "bf16" if self.ref.dtype == torch.bfloat16 else "f32"
+        return {torch.bfloat16: "bf16", torch.float16: "f16"}.get(self.ref.dtype, "f32")
 
     @property
     def n(self) -> int:
@@ -159,18 +159,19 @@ def dense_f32(device="cpu", side: int = 8192, P: int = 16, T: int = 100,
 
 
 def softmax_bf16(device="cpu", B: int = 32, R: int = 128, C: int = 4096, P: int = 64,
-                 T: int = 100) -> Workload:
+                 T: int = 100, dtype=torch.bfloat16) -> Workload:
     """Config 3: bf16 [B, R, C] with softmax rows (fp64 softmax of N(0, sd 3) logits,
     rounded to bf16); each candidate element is moved by +-1 or +-2 bf16 ulp with
     probability one half (clamped to [0, 1]); candidates 7, 15, 23, ... also have the
-    R rows of one seeded batch slab rotated by one row."""
+    R rows of one seeded batch slab rotated by one row.  With dtype=torch.float16 the same
+    recipe in binary16 (the half-precision variant of the workload)."""
     cfg = 3
     logits = 3.0 * torch.randn(B, R, C, generator=_gen(device, cfg, 0), device=device,
                                dtype=torch.float64)
-    ref = torch.softmax(logits, dim=-1).to(torch.bfloat16).contiguous()
+    ref = torch.softmax(logits, dim=-1).to(dtype).contiguous()
     del logits
     ref_bits = ref.view(torch.int16).to(torch.int32)
-    one_bits = 0x3F80  # bf16 1.0
+    one_bits = 0x3F80 if dtype == torch.bfloat16 else 0x3C00  # 1.0
     cands, corrupted, slabs = [], [], []
     for p in range(P):
         g = _gen(device, cfg, 1 + p)
@@ -179,7 +180,7 @@ def softmax_bf16(device="cpu", B: int = 32, R: int = 128, C: int = 4096, P: int 
         sign = torch.randint(0, 2, (B, R, C), generator=g, device=device, dtype=torch.int32) * 2 - 1
         bits = ref_bits + torch.where(move, delta * sign, torch.zeros_like(delta))
         bits = bits.clamp_(0, one_bits).to(torch.int16)
-        c = bits.view(torch.bfloat16)
+        c = bits.view(dtype)
         bad = (p % 8) == 7
         slab = -1
         if bad:
@@ -193,7 +194,8 @@ def softmax_bf16(device="cpu", B: int = 32, R: int = 128, C: int = 4096, P: int 
         del move, delta, sign, bits
     t, b = _timings(device, cfg, P, T, "lognormal")
     seg = Segment(ref.view(-1), cands, (B, R, C), corrupted, {"rotated_slab": slabs})
-    return Workload("C3-bf16-%dx%dx%d-P%d" % (B, R, C, P), [seg], 1e-2, 1e-2, t, b)
+    tag = "C3-bf16" if dtype == torch.bfloat16 else "C3h-f16"
+    return Workload("%s-%dx%dx%d-P%d" % (tag, B, R, C, P), [seg], 1e-2, 1e-2, t, b)
 
 
 RAGGED_SHAPES: Tuple[Tuple[int, ...], ...] = (
@@ -329,6 +331,6 @@ def to_oracle_array(x: torch.Tensor):
     """Host numpy view the CPU oracle accepts (float32, or uint16 bits for bf16)."""
     import numpy as np
     x = x.detach().cpu().contiguous()
-    if x.dtype == torch.bfloat16:
+    if x.dtype in (torch.bfloat16, torch.float16):
         return x.view(torch.int16).numpy().view(np.uint16)
     return x.numpy()

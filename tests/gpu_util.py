@@ -21,11 +21,11 @@ SUM_FIELDS = ("sum_abs_err", "sum_rel_err")
 
 
 def dtype_code(seg):
-    return evo.EVO_BF16 if seg.dtype_name == "bf16" else evo.EVO_F32
+    return {"bf16": evo.EVO_BF16, "f16": evo.EVO_F16}.get(seg.dtype_name, evo.EVO_F32)
 
 
 def oracle_dtype(seg):
-    return oracle.BF16 if seg.dtype_name == "bf16" else oracle.F32
+    return {"bf16": oracle.BF16, "f16": oracle.F16}.get(seg.dtype_name, oracle.F32)
 
 
 def oracle_rows(seg, atol, rtol, threads=16, chunk=1 << 24):

@@ -60,6 +60,8 @@ def _create(evo, *args):
 def test_create_validates(evo):
     assert evo.lib.evo_check_create(None, 0, 10, 0.0, 0.0) == -1
     assert _create(evo, 7, 10, 0.0, 0.0) == (-2, None)
+    rc, h16 = _create(evo, 2, 10, 0.0, 0.0)
+    assert rc == 0 and evo.lib.evo_check_destroy(h16) == 0
     assert _create(evo, 0, 0, 0.0, 0.0) == (-3, None)
     for atol, rtol in ((-1e-3, 0.0), (0.0, -1.0), (float("nan"), 0.0), (0.0, float("nan")),
                        (float("inf"), 0.0), (0.0, float("inf"))):

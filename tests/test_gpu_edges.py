@@ -44,9 +44,10 @@ def _mixed(n, P, seed, dtype=torch.float32, special=True):
             v = torch.tensor(vals, device="cuda")[torch.randint(0, len(vals), (k,), generator=g,
                                                                  device="cuda")]
             t[idx] = v
-    if dtype == torch.bfloat16:
-        ref = ref.to(torch.bfloat16)
-        cands = [c.to(torch.bfloat16) for c in cands]
+    if dtype in (torch.bfloat16, torch.float16):
+        # (3e38 etc. become Inf in binary16: more special sites, which is fine)
+        ref = ref.to(dtype)
+        cands = [c.to(dtype) for c in cands]
     seg = synth.Segment(ref.contiguous(), [c.contiguous() for c in cands], (n,), [True] * P)
     T = 8
     t = 1 + torch.rand(P, T, generator=g, device="cuda")
@@ -58,7 +59,8 @@ SIZES = [1, 3, 4, 5, 63, 64, 65, 255, 256, 257, 511, 512, 513, 1023, 1024, 1025,
          4095, 4097, 65535, 65537, (1 << 20) + 1]
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16],
+                         ids=["f32", "bf16", "f16"])
 def test_ragged_sizes_special_values(gu, dtype):
     for i, n in enumerate(SIZES):
         _say("mixed n=%d %s" % (n, dtype))
@@ -77,6 +79,10 @@ def test_population_sizes(gu, P):
     w = _mixed(3000, P, 2000 + P, torch.bfloat16, special=False)
     chk, stats, want = gu.check_parity(w, label="P-bf16")
     chk.close()
+    if P in (1, 5, 16, 33):
+        w = _mixed(3000, P, 3000 + P, torch.float16, special=True)
+        chk, stats, want = gu.check_parity(w, label="P-f16")
+        chk.close()
 
 
 def test_reciprocal_shortcut_is_exact_on_this_device(gu):
@@ -150,6 +156,28 @@ def test_unaligned_tensors(gu):
             chk.close()
 
 
+def test_f16_every_bit_pattern(gu):
+    """All 65536 binary16 patterns on both sides (subnormals, Inf, every NaN payload)."""
+    _say("f16 all patterns")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(16)
+    allbits = torch.arange(65536, device="cuda", dtype=torch.int32)
+    ref = allbits.repeat(8).to(torch.int16).view(torch.float16)
+    n = ref.numel()
+    cands = []
+    for p in range(4):
+        delta = torch.randint(-2, 3, (n,), generator=g, device="cuda", dtype=torch.int32)
+        c = ((allbits.repeat(8) + delta) & 0xFFFF).to(torch.int16).view(torch.float16)
+        cands.append(c.contiguous())
+    cands.append(ref.clone())
+    seg = synth.Segment(ref.contiguous(), cands, (n,), [True] * 5)
+    w = synth.Workload("f16-all", [seg], 1e-2, 1e-2, torch.ones(5, 4, device="cuda"),
+                       torch.ones(4, device="cuda"))
+    chk, stats, want = gu.check_parity(w, label="f16-all")
+    assert want[4]["n_mismatch"] == 8 * 2046   # the NaN patterns: 2 * (2^10 - 1) per copy
+    chk.close()
+
+
 def test_tolerance_extremes(gu):
     _say("tolerances")
     base = _mixed(10000, 4, 77, torch.float32)
@@ -164,7 +192,7 @@ def test_segmented_mixed_dtypes_and_row_layout(gu):
     _say("segmented mixed")
     import paper_2510_03760_amd as evo
     from paper_2510_03760_amd.binding import stats_to_numpy
-    ws = [_mixed(70000, 20, 1, torch.float32), _mixed(513, 3, 2, torch.bfloat16),
+    ws = [_mixed(70000, 20, 1, torch.float32), _mixed(513, 3, 2, torch.float16),
           _mixed(1, 1, 3, torch.float32), _mixed(250000, 40, 4, torch.bfloat16, special=False),
           _mixed(4096, 16, 5, torch.float32, special=False)]
     order = [3, 0, 4, 1, 2]           # row ranges in a different order than the segments

@@ -48,6 +48,15 @@ def test_config3_reduced_bf16(gu):
     chk.close()
 
 
+def test_config3_reduced_f16(gu):
+    _say("C3 reduced, binary16")
+    w = synth.softmax_bf16("cuda", B=4, R=32, C=1000, P=64, T=100, dtype=torch.float16)
+    chk, stats, want = gu.check_parity(w)
+    assert sum(r["valid"] for r in want) == 56
+    gu.fitness_parity(chk, stats, w.timings, w.baseline, label="C3h")
+    chk.close()
+
+
 def test_config4_reduced_ragged(gu):
     _say("C4 reduced")
     shapes = ((4, 16, 28, 28), (512, 512), (128, 1, 1), (2 ** 16,), (8, 3, 56, 56), (128, 128),
