@@ -273,6 +273,44 @@ def test_check_cases_equals_one_accumulator_over_all_cases(gu):
         chk.close()
 
 
+def test_large_tables_go_through_the_staged_path(gu):
+    """More segments / candidate pointers than fit into the kernel-argument block: the
+    descriptors are staged through pinned memory and a device table.  Also more segments
+    than resident workgroup slots."""
+    _say("staged table: 700 segments")
+    import paper_2510_03760_amd as evo
+    from paper_2510_03760_amd.binding import stats_to_numpy
+    g = torch.Generator(device="cuda")
+    g.manual_seed(99)
+    S = 700
+    sizes = torch.randint(1, 3000, (S,), generator=g, device="cuda").tolist()
+    segs, want_rows, row0 = [], [], 0
+    keep = []
+    for si, n in enumerate(sizes):
+        dt = (torch.float32, torch.bfloat16, torch.float16)[si % 3]
+        w = _mixed(n, 2, 5000 + si, dt, special=(si % 5 == 0))
+        keep.append(w)
+        seg = w.segments[0]
+        segs.append({"ref": seg.ref, "cand_ptrs": seg.cands, "n_elems": seg.n,
+                     "dtype": gu.dtype_code(seg), "stats_row0": row0})
+        want_rows += gu.oracle_rows(seg, 1e-2, 1e-2, threads=1)
+        row0 += 2
+    chk = evo.Checker(evo.EVO_F32, 1, 1e-2, 1e-2)
+    stats = chk.new_stats(row0)
+    for rep in range(3):      # the staging slots rotate
+        stats.fill_(0x11)
+        chk.check_segmented(segs, stats, row0)
+        torch.cuda.synchronize()
+        got = stats_to_numpy(stats)
+        for r, (gr, o) in enumerate(zip(got, want_rows)):
+            gu.assert_rows_equal(gr, o, "staged rep %d row %d" % (rep, r))
+    chk.close()
+    _say("staged table: 1000 candidates")
+    w = _mixed(2000, 1000, 4242, torch.float32, special=False)
+    chk, stats, want = gu.check_parity(w, label="P1000")
+    chk.close()
+
+
 def test_repeatable_and_reusable_context(gu):
     """Same call twice gives byte-identical rows; a context can be reused for other
     populations (its counters re-arm themselves)."""
