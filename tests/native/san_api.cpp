@@ -1,0 +1,280 @@
+// Host-sanitizer driver for the host side of the C ABI (include/evo.h).
+//
+// Built by tests/test_host_sanitizers.py with hipcc, the host pass under
+// -fsanitize=address,undefined, and run on the CPU.  The translation unit of the
+// library's host code is included textually so that its internal partitioner can be
+// driven directly; the four kernel launchers are replaced by stubs that launch
+// nothing, so no kernel runs even where a GPU is present.
+//
+// Covered: every argument check of every entry point, handle lifetime (double
+// destroy, foreign pointers), behaviour when HIP has no device (a clean
+// EVO_ERR_DEVICE, nothing leaked), and the partitioner on a few thousand seeded
+// ragged populations, checked against the invariants the kernel's indexing relies
+// on (the list of those is in check_partition below).
+#include "../../paper_2510_03760_amd/csrc/evo_api.hip"
+
+#include <cstdio>
+#include <cstdlib>
+
+namespace evo {
+static int g_launches = 0;
+hipError_t launch_check(uint32_t, const SegDesc *, const uint64_t *, uint32_t, uint32_t, float, float,
+                        Partial *, uint32_t *, evo_stats *, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_check_inline(uint32_t, const InlineTable &, uint32_t, uint32_t, float, float,
+                               Partial *, uint32_t *, evo_stats *, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_fitness(const float *, const float *, uint32_t, uint32_t, evo_stats *,
+                          evo_pop_summary *, float *, uint32_t *, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_select(const evo_stats *, uint32_t, uint32_t, uint32_t *, uint32_t *, hipStream_t) {
+    ++g_launches;
+    return hipSuccess;
+}
+}  // namespace evo
+
+static int g_fail = 0;
+#define EXPECT(cond)                                                        \
+    do {                                                                    \
+        if (!(cond)) {                                                      \
+            std::printf("FAIL %s:%d: %s\n", __FILE__, __LINE__, #cond);     \
+            ++g_fail;                                                       \
+        }                                                                   \
+    } while (0)
+
+static uint64_t g_rng = 0x2510037600000001ull;
+static uint64_t rng() {
+    g_rng = g_rng * 6364136223846793005ull + 1442695040888963407ull;
+    return g_rng >> 17;
+}
+
+// Invariants of partition():
+//  1. jobs of consecutive segments are consecutive, total_jobs is their sum;
+//  2. n_jobs = ceil(n_groups / gpw) * n_chunks, gpw in {1, 2, 4}, gpw <= pow2_ceil(n_groups);
+//  3. the tile slots of a segment's workgroups cover all its tiles;
+//  4. no wavefront walks more than kMaxTilesPerWave tiles in one job (the size of the
+//     kernel's per-wavefront redo list);
+//  5. the launch fits the target when there is room for it (at most one job per segment
+//     is forced, and the cap on tiles per wavefront can force more).
+static void check_partition(const std::vector<HostSeg> &segs, uint32_t target) {
+    std::vector<SegDesc> d;
+    uint32_t total = 0;
+    partition(segs, target, d, total);
+    EXPECT(d.size() == segs.size());
+    uint64_t job = 0;
+    bool capped = false;
+    for (size_t s = 0; s < segs.size(); ++s) {
+        const uint64_t te = evo::tile_elems(segs[s].dtype);
+        const uint64_t tiles = (segs[s].n + te - 1) / te;
+        EXPECT(d[s].job0 == job);
+        EXPECT(d[s].n == segs[s].n && d[s].P == segs[s].P && d[s].dtype == segs[s].dtype);
+        EXPECT(d[s].stats_row0 == segs[s].row0);
+        EXPECT(d[s].n_groups == evo::group_count(segs[s].P));
+        EXPECT(d[s].gpw == 1 || d[s].gpw == 2 || d[s].gpw == 4);
+        EXPECT(d[s].gpw <= pow2_ceil(d[s].n_groups));
+        const uint32_t gblocks = (d[s].n_groups + d[s].gpw - 1) / d[s].gpw;
+        EXPECT(d[s].n_chunks >= 1);
+        EXPECT(d[s].n_jobs == gblocks * d[s].n_chunks);
+        const uint64_t slots = (uint64_t)d[s].n_chunks * (evo::kWaves / d[s].gpw);
+        const uint64_t steps = (tiles + slots - 1) / slots;   // tiles one wavefront walks
+        EXPECT(steps >= 1 && steps <= evo::kMaxTilesPerWave);
+        // the cap on tiles per wavefront decided this segment's chunk count
+        const uint64_t cap_slots = (uint64_t)evo::kMaxTilesPerWave * (evo::kWaves / d[s].gpw);
+        if (d[s].n_chunks > 1 && d[s].n_chunks == (tiles + cap_slots - 1) / cap_slots) capped = true;
+        EXPECT(segs[s].n_cases > 1 ? d[s].case0 == segs[s].case0 : d[s].case0 == s);
+        EXPECT(d[s].n_cases == segs[s].n_cases);
+        job += d[s].n_jobs;
+    }
+    EXPECT(job == total);
+    uint64_t forced = 0;   // group blocks: each needs a workgroup of its own
+    for (const SegDesc &x : d) forced += (x.n_groups + x.gpw - 1) / x.gpw;
+    if (!capped && forced <= target / 2) EXPECT(total <= target);
+}
+
+static void partition_cases() {
+    const uint32_t targets[] = {1, 8, 64, 512, 608};
+    for (int it = 0; it < 3000; ++it) {
+        const uint32_t S = 1 + (uint32_t)(rng() % (it % 10 == 0 ? 700 : 9));
+        std::vector<HostSeg> segs(S);
+        uint32_t row0 = 0;
+        for (HostSeg &h : segs) {
+            const int lg = (int)(rng() % (S > 16 ? 22 : 34));
+            h.n = 1 + rng() % (1ull << lg);
+            const uint32_t pk = (uint32_t)(rng() % 8);
+            h.P = pk == 0 ? 1 + (uint32_t)(rng() % kMaxP) : 1 + (uint32_t)(rng() % 70);
+            h.dtype = (uint32_t)(rng() % 3);
+            h.ref = nullptr;
+            h.cand_ptrs = nullptr;
+            h.row0 = row0;
+            row0 += h.P;
+            if (!partition_fits(std::vector<HostSeg>(1, h))) h.n = 1 + h.n % 4096;
+        }
+        if (!partition_fits(segs)) continue;
+        check_partition(segs, targets[it % 5]);
+    }
+    // the shapes the benchmark runs: one dense tensor, one 2^30 one
+    HostSeg h{};
+    h.n = 1ull << 26; h.P = 16; h.dtype = EVO_F32; h.n_cases = 1;
+    check_partition(std::vector<HostSeg>(1, h), 512);
+    h.n = 1ull << 30; h.P = 8;
+    check_partition(std::vector<HostSeg>(1, h), 512);
+    h.n = 1ull << 40; h.P = kMaxP;          // too large: refused before partitioning
+    EXPECT(!partition_fits(std::vector<HostSeg>(1, h)));
+}
+
+static void group_cases() {
+    for (uint32_t P = 1; P <= 300; ++P) {
+        const uint32_t G = evo::group_count(P);
+        uint32_t next = 0;
+        for (uint32_t g = 0; g < G; ++g) {
+            const evo::Group gr = evo::group_of(P, g);
+            EXPECT(gr.cand0 == next);
+            EXPECT(gr.nc >= 1 && gr.nc <= (uint32_t)evo::kG && (gr.nc & (gr.nc - 1)) == 0);
+            for (uint32_t i = 0; i < gr.nc; ++i) {
+                uint32_t gg = ~0u, gi = ~0u;
+                evo::locate(P, gr.cand0 + i, &gg, &gi);
+                EXPECT(gg == g && gi == i);
+            }
+            next += gr.nc;
+        }
+        EXPECT(next == P);
+        EXPECT(evo::group_of(P, G).nc == 0);
+    }
+}
+
+static void validation_cases() {
+    evo_check_t *c = nullptr;
+    EXPECT(evo_check_create(nullptr, EVO_F32, 16, 0.f, 0.f) == EVO_ERR_NULL);
+    EXPECT(evo_check_create(&c, (evo_dtype)3, 16, 0.f, 0.f) == EVO_ERR_DTYPE && c == nullptr);
+    EXPECT(evo_check_create(&c, EVO_F32, 0, 0.f, 0.f) == EVO_ERR_SIZE);
+    EXPECT(evo_check_create(&c, EVO_F32, 16, -1.f, 0.f) == EVO_ERR_TOL);
+    EXPECT(evo_check_create(&c, EVO_F32, 16, 0.f, __builtin_nanf("")) == EVO_ERR_TOL);
+    EXPECT(evo_check_create(&c, EVO_F32, 16, __builtin_huge_valf(), 0.f) == EVO_ERR_TOL);
+    EXPECT(evo_check_create(&c, EVO_F32, 1000, 1e-2f, 1e-2f) == EVO_OK && c != nullptr);
+
+    // fake "device" addresses: validated, never dereferenced by host code
+    alignas(16) static char arena[4096];
+    const void *ref = arena;
+    const void *cands[3] = {arena + 16, arena + 32, arena + 48};
+    evo_stats *stats = reinterpret_cast<evo_stats *>(arena + 1024);
+    int foreign = 0;
+
+    EXPECT(evo_check_batch(nullptr, ref, cands, 3, nullptr, stats) == EVO_ERR_HANDLE);
+    EXPECT(evo_check_batch(reinterpret_cast<evo_check_t *>(&foreign), ref, cands, 3, nullptr, stats) ==
+           EVO_ERR_HANDLE);
+    EXPECT(evo_check_batch(c, nullptr, cands, 3, nullptr, stats) == EVO_ERR_NULL);
+    EXPECT(evo_check_batch(c, ref, nullptr, 3, nullptr, stats) == EVO_ERR_NULL);
+    EXPECT(evo_check_batch(c, ref, cands, 3, nullptr, nullptr) == EVO_ERR_NULL);
+    EXPECT(evo_check_batch(c, ref, cands, 0, nullptr, stats) == EVO_ERR_SIZE);
+    EXPECT(evo_check_batch(c, ref, cands, 65536, nullptr, stats) == EVO_ERR_SIZE);
+    EXPECT(evo_check_batch(c, arena + 2, cands, 3, nullptr, stats) == EVO_ERR_ALIGN);
+    {
+        const void *bad[3] = {arena + 16, nullptr, arena + 48};
+        EXPECT(evo_check_batch(c, ref, bad, 3, nullptr, stats) == EVO_ERR_NULL);
+        bad[1] = arena + 33;
+        EXPECT(evo_check_batch(c, ref, bad, 3, nullptr, stats) == EVO_ERR_ALIGN);
+    }
+
+    evo_segment seg[2] = {{ref, cands, 100, 3, EVO_F32, 0, 0}, {ref, cands, 7, 2, EVO_BF16, 3, 0}};
+    EXPECT(evo_check_segmented(nullptr, seg, 2, nullptr, stats, 5) == EVO_ERR_HANDLE);
+    EXPECT(evo_check_segmented(c, nullptr, 2, nullptr, stats, 5) == EVO_ERR_NULL);
+    EXPECT(evo_check_segmented(c, seg, 2, nullptr, nullptr, 5) == EVO_ERR_NULL);
+    EXPECT(evo_check_segmented(c, seg, 0, nullptr, stats, 5) == EVO_ERR_SIZE);
+    EXPECT(evo_check_segmented(c, seg, 2, nullptr, stats, 0) == EVO_ERR_SIZE);
+    EXPECT(evo_check_segmented(c, seg, 2, nullptr, stats, 4) == EVO_ERR_SIZE);   // rows past n_rows
+    seg[1].stats_row0 = 2;                                                        // overlap
+    EXPECT(evo_check_segmented(c, seg, 2, nullptr, stats, 5) == EVO_ERR_SIZE);
+    seg[1].stats_row0 = 3;
+    seg[1].dtype = 9;
+    EXPECT(evo_check_segmented(c, seg, 2, nullptr, stats, 5) == EVO_ERR_DTYPE);
+    seg[1].dtype = EVO_F16;
+    seg[1].n_elems = 0;
+    EXPECT(evo_check_segmented(c, seg, 2, nullptr, stats, 5) == EVO_ERR_SIZE);
+    seg[1].n_elems = 7;
+    seg[1].P_s = 0;
+    EXPECT(evo_check_segmented(c, seg, 2, nullptr, stats, 5) == EVO_ERR_SIZE);
+    seg[1].P_s = 2;
+    seg[1].stats_row0 = 0xffffffffu;   // lo + P_s must not wrap
+    EXPECT(evo_check_segmented(c, seg, 2, nullptr, stats, 5) == EVO_ERR_SIZE);
+    seg[1].stats_row0 = 3;
+
+    evo_segment cs[2] = {{ref, cands, 100, 3, EVO_F32, 0, 0}, {ref, cands, 50, 3, EVO_F16, 0, 0}};
+    EXPECT(evo_check_cases(nullptr, cs, 2, nullptr, stats) == EVO_ERR_HANDLE);
+    EXPECT(evo_check_cases(c, nullptr, 2, nullptr, stats) == EVO_ERR_NULL);
+    EXPECT(evo_check_cases(c, cs, 2, nullptr, nullptr) == EVO_ERR_NULL);
+    EXPECT(evo_check_cases(c, cs, 0, nullptr, stats) == EVO_ERR_SIZE);
+    cs[1].P_s = 2;
+    EXPECT(evo_check_cases(c, cs, 2, nullptr, stats) == EVO_ERR_SIZE);
+    cs[1].P_s = 3;
+    cs[1].stats_row0 = 1;
+    EXPECT(evo_check_cases(c, cs, 2, nullptr, stats) == EVO_ERR_SIZE);
+    cs[1].stats_row0 = 0;
+
+    const float *tim = reinterpret_cast<const float *>(arena + 2048);
+    const float *base = reinterpret_cast<const float *>(arena + 3072);
+    evo_pop_summary *pop = reinterpret_cast<evo_pop_summary *>(arena + 3584);
+    EXPECT(evo_fitness(nullptr, tim, base, 3, 5, nullptr, stats, pop) == EVO_ERR_HANDLE);
+    EXPECT(evo_fitness(c, nullptr, base, 3, 5, nullptr, stats, pop) == EVO_ERR_NULL);
+    EXPECT(evo_fitness(c, tim, nullptr, 3, 5, nullptr, stats, pop) == EVO_ERR_NULL);
+    EXPECT(evo_fitness(c, tim, base, 3, 5, nullptr, nullptr, pop) == EVO_ERR_NULL);
+    EXPECT(evo_fitness(c, tim, base, 0, 5, nullptr, stats, pop) == EVO_ERR_SIZE);
+    EXPECT(evo_fitness(c, tim, base, 3, 0, nullptr, stats, pop) == EVO_ERR_SIZE);
+    EXPECT(evo_fitness(c, tim, base, 3, EVO_FITNESS_MAX_T + 1, nullptr, stats, pop) == EVO_ERR_SIZE);
+    EXPECT(evo_fitness(c, tim, base, (1u << 20) + 1, 5, nullptr, stats, pop) == EVO_ERR_SIZE);
+    EXPECT(evo_fitness(c, reinterpret_cast<const float *>(arena + 2050), base, 3, 5, nullptr, stats,
+                       pop) == EVO_ERR_ALIGN);
+    EXPECT(evo_fitness(c, tim, base, 3, 5, nullptr, reinterpret_cast<evo_stats *>(arena + 1028), pop) ==
+           EVO_ERR_ALIGN);
+
+    uint32_t *elite = reinterpret_cast<uint32_t *>(arena + 3600);
+    EXPECT(evo_select_elite(nullptr, stats, 3, 2, nullptr, elite, nullptr) == EVO_ERR_HANDLE);
+    EXPECT(evo_select_elite(c, nullptr, 3, 2, nullptr, elite, nullptr) == EVO_ERR_NULL);
+    EXPECT(evo_select_elite(c, stats, 3, 2, nullptr, nullptr, nullptr) == EVO_ERR_NULL);
+    EXPECT(evo_select_elite(c, stats, 0, 1, nullptr, elite, nullptr) == EVO_ERR_SIZE);
+    EXPECT(evo_select_elite(c, stats, 3, 0, nullptr, elite, nullptr) == EVO_ERR_SIZE);
+    EXPECT(evo_select_elite(c, stats, 3, 4, nullptr, elite, nullptr) == EVO_ERR_SIZE);
+    EXPECT(evo_select_elite(c, stats, 65536, 4, nullptr, elite, nullptr) == EVO_ERR_SIZE);
+    EXPECT(evo_select_elite(c, stats, 3, 2, nullptr, reinterpret_cast<uint32_t *>(arena + 3602),
+                            nullptr) == EVO_ERR_ALIGN);
+
+    EXPECT(evo::g_launches == 0);   // nothing above got past validation
+
+    // Valid arguments.  Without a device HIP refuses and the call reports it; with one,
+    // scratch is allocated and the (stubbed) launcher is reached.  Either way nothing
+    // may leak or be touched out of bounds.
+    const int rc1 = evo_check_batch(c, ref, cands, 3, nullptr, stats);
+    EXPECT(rc1 == EVO_OK || rc1 == EVO_ERR_DEVICE);
+    const int rc2 = evo_check_segmented(c, seg, 2, nullptr, stats, 5);
+    EXPECT(rc2 == rc1);
+    const int rc3 = evo_check_cases(c, cs, 2, nullptr, stats);
+    EXPECT(rc3 == rc1);
+    if (rc1 == EVO_OK) {
+        // more groups and pointers than the argument block holds: the staged-table path
+        std::vector<const void *> many(400, arena + 64);
+        std::vector<evo_segment> big(12);
+        uint32_t row = 0;
+        for (evo_segment &s : big) {
+            s = evo_segment{ref, many.data(), 33, 400, EVO_F32, row, 0};
+            row += 400;
+        }
+        EXPECT(evo_check_segmented(c, big.data(), 12, nullptr, stats, row) == EVO_OK);
+        EXPECT(evo_check_segmented(c, big.data(), 12, nullptr, stats, row) == EVO_OK);
+    }
+    const int rc4 = evo_fitness(c, tim, base, 3, 5, nullptr, stats, pop);
+    EXPECT(rc4 == rc1);
+    const int rc5 = evo_select_elite(c, stats, 3, 2, nullptr, elite, nullptr);
+    EXPECT(rc5 == rc1);
+    std::printf("san_api: device calls %s\n", rc1 == EVO_OK ? "reached the launchers" : "refused (no device)");
+
+    EXPECT(evo_check_destroy(c) == EVO_OK || rc1 != EVO_OK);
+    EXPECT(evo_check_destroy(c) == EVO_ERR_HANDLE);        // already destroyed
+    EXPECT(evo_check_destroy(nullptr) == EVO_ERR_HANDLE);
+    EXPECT(evo_check_batch(c, ref, cands, 3, nullptr, stats) == EVO_ERR_HANDLE);
+
+    for (int code = 1; code >= -10; --code) EXPECT(evo_strerror(code) != nullptr && evo_strerror(code)[0]);
+}
+
+int main() {
+    group_cases();
+    partition_cases();
+    validation_cases();
+    std::puts(g_fail ? "san_api: FAILED" : "san_api: ok");
+    return g_fail ? 1 : 0;
+}
