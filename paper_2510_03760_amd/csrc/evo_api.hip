@@ -293,7 +293,7 @@ int run_check(evo_check *c, const std::vector<HostSeg> &segs, hipStream_t stream
                 tab.ptrs[descs[s].ptr0 + p] = reinterpret_cast<uint64_t>(segs[s].cand_ptrs[p]);
         }
         return dev(evo::launch_check_inline(dtype_set, tab, (uint32_t)S, total_jobs, c->atol, c->rtol,
-                                            c->d_partials, c->d_tickets, stats, stream));
+                                            c->n_cus, c->d_partials, c->d_tickets, stats, stream));
     }
 
     // blob = descriptors, then all candidate pointers, staged through pinned memory
@@ -316,7 +316,7 @@ int run_check(evo_check *c, const std::vector<HostSeg> &segs, hipStream_t stream
     return dev(evo::launch_check(
         dtype_set, static_cast<const SegDesc *>(c->d_table),
         reinterpret_cast<const uint64_t *>(static_cast<char *>(c->d_table) + desc_bytes), (uint32_t)S,
-        total_jobs, c->atol, c->rtol, c->d_partials, c->d_tickets, stats, stream));
+        total_jobs, c->atol, c->rtol, c->n_cus, c->d_partials, c->d_tickets, stats, stream));
 }
 
 }  // namespace

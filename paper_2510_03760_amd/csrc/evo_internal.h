@@ -149,13 +149,16 @@ static_assert(sizeof(InlineTable) <= 3600, "kernel argument block must stay belo
 //   partials: J*kRowsPerJob first-level rows | J*kRowsPerJob second-level rows | C case rows
 //   tickets:  J bundle tickets | S segment tickets | S case-group tickets
 // dtype_set: OR of (1 << evo_dtype) over the segments of the launch.
+// n_first: compute units of the device (workgroups numbered below it get a compute unit
+// of their own when the launch starts).
 hipError_t launch_check(uint32_t dtype_set, const SegDesc *d_descs, const uint64_t *d_ptrs,
-                        uint32_t S, uint32_t total_jobs, float atol, float rtol, Partial *partials,
-                        uint32_t *tickets, evo_stats *stats, hipStream_t stream);
+                        uint32_t S, uint32_t total_jobs, float atol, float rtol, uint32_t n_first,
+                        Partial *partials, uint32_t *tickets, evo_stats *stats, hipStream_t stream);
 
 hipError_t launch_check_inline(uint32_t dtype_set, const InlineTable &tab, uint32_t S,
-                               uint32_t total_jobs, float atol, float rtol, Partial *partials,
-                               uint32_t *tickets, evo_stats *stats, hipStream_t stream);
+                               uint32_t total_jobs, float atol, float rtol, uint32_t n_first,
+                               Partial *partials, uint32_t *tickets, evo_stats *stats,
+                               hipStream_t stream);
 
 hipError_t launch_fitness(const float *timings, const float *baseline, uint32_t P, uint32_t T,
                           evo_stats *stats, evo_pop_summary *summary, float *base_median,

@@ -19,8 +19,8 @@
 namespace evo {
 static int g_launches = 0;
 hipError_t launch_check(uint32_t, const SegDesc *, const uint64_t *, uint32_t, uint32_t, float, float,
-                        Partial *, uint32_t *, evo_stats *, hipStream_t) { ++g_launches; return hipSuccess; }
-hipError_t launch_check_inline(uint32_t, const InlineTable &, uint32_t, uint32_t, float, float,
+                        uint32_t, Partial *, uint32_t *, evo_stats *, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_check_inline(uint32_t, const InlineTable &, uint32_t, uint32_t, float, float, uint32_t,
                                Partial *, uint32_t *, evo_stats *, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_fitness(const float *, const float *, uint32_t, uint32_t, evo_stats *,
                           evo_pop_summary *, float *, uint32_t *, hipStream_t) { ++g_launches; return hipSuccess; }
