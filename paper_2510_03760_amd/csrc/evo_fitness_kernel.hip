@@ -120,14 +120,13 @@ evo_fitness_kernel(const float *__restrict__ timings, const float *__restrict__ 
         } else {
             *base_median = median;
         }
-        __threadfence();   // publish before the ticket
+        // the release of the ticket publishes the two stores above
         const uint32_t prev = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL,
                                                      __HIP_MEMORY_SCOPE_AGENT);
         is_last = (prev == P) ? 1u : 0u;
     }
     __syncthreads();
-    if (!is_last) return;
-    __threadfence();
+    if (!is_last) return;   // thread 0 acquired with the last ticket; the barrier hands that on
 
     // The last of the P+1 workgroups: speedups, fitness, population figures.
     const float bm = __hip_atomic_load(base_median, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
