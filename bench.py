@@ -7,10 +7,14 @@ then the median-timing / speedup / fitness reduction.  Inputs are resident in HB
 before the timed region starts.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c3h|c4|c5|cases]
-                    [--no-cpu-baseline] [--copy-calibration]
+                    [--no-cpu-baseline] [--no-read-ceiling] [--copy-calibration]
 
 --copy-calibration runs only a plain device-to-device copy of known size (used to
 scale the rocprofv3 FETCH_SIZE / WRITE_SIZE counters) and prints its own JSON line.
+
+Before the workload is built, the stand-alone probe paper_2510_03760_amd/read_ceiling
+(a trivial read-only kernel over 8 GiB, run as a child process) measures what this
+machine streams at best; the JSON line carries it beside the vendor peak.
 """
 from __future__ import annotations
 
@@ -45,6 +49,23 @@ def measured_traffic(workload_name: str):
             return None
         return entry["traffic_bytes"]
     except (OSError, KeyError, ValueError):
+        return None
+
+
+def read_ceiling():
+    """Best read-only streaming rate of this GPU in GB/s from the stand-alone probe, or
+    None when the probe is not built or fails."""
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2510_03760_amd", "read_ceiling")
+    if not os.path.exists(exe):
+        return None
+    try:
+        res = subprocess.run([exe, "8"], stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True,
+                             timeout=120)
+        if res.returncode != 0:
+            return None
+        return json.loads(res.stdout.strip().splitlines()[-1])
+    except (OSError, ValueError, subprocess.TimeoutExpired, IndexError):
         return None
 
 
@@ -116,6 +137,7 @@ def main() -> int:
     ap.add_argument("--cpu-budget-elems", type=float, default=2.0e9,
                     help="candidate-elements the CPU oracle is timed on (about 160 M/s/core)")
     ap.add_argument("--copy-calibration", action="store_true")
+    ap.add_argument("--no-read-ceiling", action="store_true")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -123,6 +145,9 @@ def main() -> int:
               "supported (candidates shard trivially across GPUs, see DESIGN.md)" % args.gpus,
               file=sys.stderr)
         return 2
+
+    # child process, finished before this process touches the GPU
+    ceiling = None if (args.no_read_ceiling or args.copy_calibration) else read_ceiling()
 
     import torch
     if not torch.cuda.is_available():
@@ -235,6 +260,11 @@ def main() -> int:
                               "median": 1e3 * fit_ms[len(fit_ms) // 2]},
         "hbm_gbps_whole_step": alg_bytes / (wall / args.steps) / 1e9,
     }
+    if ceiling is not None:
+        best = max(ceiling["nontemporal_GBps"], ceiling["plain_GBps"])
+        out["read_ceiling"] = {"GBps": best, "plain_loads_GBps": ceiling["plain_GBps"],
+                               "frac_of_ceiling": achieved / best,
+                               "how": "read-only sweep of 8 GiB, paper_2510_03760_amd/read_ceiling"}
 
     # Outside the timed step: elite selection (population management) on the same rows.
     k_elite = min(4, P)

@@ -50,6 +50,21 @@ def build_rcp_check() -> str:
     return RCP_CHECK_PATH
 
 
+READ_CEILING_PATH = os.path.join(_PKG, "read_ceiling")
+
+
+def build_read_ceiling() -> str:
+    """Compiles the stand-alone read-only streaming probe (csrc/read_ceiling.hip)."""
+    tmp = READ_CEILING_PATH + ".tmp.%d" % os.getpid()
+    flags = [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC", "-fvisibility=hidden")]
+    cmd = [hipcc(), *flags, "-o", tmp, os.path.join(CSRC, "read_ceiling.hip")]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout)
+    os.replace(tmp, READ_CEILING_PATH)
+    return READ_CEILING_PATH
+
+
 def is_stale() -> bool:
     if not os.path.exists(LIB_PATH):
         return True
@@ -77,6 +92,7 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     os.replace(tmp, LIB_PATH)
     if not extra_flags:
         build_rcp_check()
+        build_read_ceiling()
     return LIB_PATH
 
 
