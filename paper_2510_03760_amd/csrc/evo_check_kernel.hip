@@ -179,40 +179,54 @@ __device__ __forceinline__ void exact_tile(const void *ref, const void *cand, ui
     float max_abs = 0.0f, max_rel = 0.0f;
     double sum_abs = 0.0, sum_rel = 0.0;
     uint32_t n_mismatch = 0, n_excluded = 0, flags = 0;
+    // four elements per lane at a time: their loads share one memory round trip (the loop
+    // stays rolled: unrolling it all raises the register pressure of the whole kernel)
+    constexpr int kChunk = 4;
+    static_assert(kE % kChunk == 0, "tile elements per lane");
 #pragma unroll 1
-    for (int k = 0; k < kE; ++k) {
-        const uint64_t idx = tile_base + (uint64_t)(k * kLanes + lane);
-        const bool inb = idx < n;
-        float r = 0.0f, c = 0.0f;
-        if (inb) {
-            r = load_elem<DT>(ref, idx);
-            c = load_elem<DT>(cand, idx);
+    for (int k0 = 0; k0 < kE; k0 += kChunk) {
+        float rv[kChunk], cv[kChunk];
+#pragma unroll
+        for (int k = 0; k < kChunk; ++k) {
+            const uint64_t idx = tile_base + (uint64_t)((k0 + k) * kLanes + lane);
+            rv[k] = 0.0f;
+            cv[k] = 0.0f;
+            if (idx < n) {
+                rv[k] = load_elem<DT>(ref, idx);
+                cv[k] = load_elem<DT>(cand, idx);
+            }
         }
-        const float ar = __builtin_fabsf(r);
-        const float ac = __builtin_fabsf(c);
-        const float scaled = rtol * ar;
-        const float tol = atol + scaled;
-        const bool r_nan = r != r, c_nan = c != c;
-        const bool r_inf = ar == kInf, c_inf = ac == kInf;
-        const bool both = !r_nan && !c_nan && !r_inf && !c_inf;
-        const float d = __builtin_fabsf(c - r);
-        const bool match = (c == r) || (both && d <= tol);
-        n_mismatch += popc64(ballot(inb && !match));
-        n_excluded += popc64(ballot(inb && !both));
-        if (ballot(c_nan)) flags |= EVO_F_CAND_NAN;
-        if (ballot(c_inf)) flags |= EVO_F_CAND_INF;
-        if (ballot(r_nan)) flags |= EVO_F_REF_NAN;
-        if (ballot(r_inf)) flags |= EVO_F_REF_INF;
-        if (ballot(c_nan != r_nan)) flags |= EVO_F_NAN_SITE_DIFF;
-        if (ballot((c_inf || r_inf) && !c_nan && !r_nan && c != r)) flags |= EVO_F_INF_DIFF;
-        if (inb && both) {
-            float inv = 0.0f;
-            if (ar >= kFltMin) inv = 1.0f / ar;
-            const float q = d * inv;
-            max_abs = d > max_abs ? d : max_abs;
-            max_rel = q > max_rel ? q : max_rel;
-            sum_abs += (double)d;
-            sum_rel += (double)q;
+#pragma unroll
+        for (int k = 0; k < kChunk; ++k) {
+            const uint64_t idx = tile_base + (uint64_t)((k0 + k) * kLanes + lane);
+            const bool inb = idx < n;
+            const float r = rv[k], c = cv[k];
+            const float ar = __builtin_fabsf(r);
+            const float ac = __builtin_fabsf(c);
+            const float scaled = rtol * ar;
+            const float tol = atol + scaled;
+            const bool r_nan = r != r, c_nan = c != c;
+            const bool r_inf = ar == kInf, c_inf = ac == kInf;
+            const bool both = !r_nan && !c_nan && !r_inf && !c_inf;
+            const float d = __builtin_fabsf(c - r);
+            const bool match = (c == r) || (both && d <= tol);
+            n_mismatch += popc64(ballot(inb && !match));
+            n_excluded += popc64(ballot(inb && !both));
+            if (ballot(c_nan)) flags |= EVO_F_CAND_NAN;
+            if (ballot(c_inf)) flags |= EVO_F_CAND_INF;
+            if (ballot(r_nan)) flags |= EVO_F_REF_NAN;
+            if (ballot(r_inf)) flags |= EVO_F_REF_INF;
+            if (ballot(c_nan != r_nan)) flags |= EVO_F_NAN_SITE_DIFF;
+            if (ballot((c_inf || r_inf) && !c_nan && !r_nan && c != r)) flags |= EVO_F_INF_DIFF;
+            if (inb && both) {
+                float inv = 0.0f;
+                if (ar >= kFltMin) inv = 1.0f / ar;
+                const float q = d * inv;
+                max_abs = d > max_abs ? d : max_abs;
+                max_rel = q > max_rel ? q : max_rel;
+                sum_abs += (double)d;
+                sum_rel += (double)q;
+            }
         }
     }
     uint32_t ma_bits = __builtin_bit_cast(uint32_t, max_abs), mr_bits = __builtin_bit_cast(uint32_t, max_rel);
