@@ -22,6 +22,12 @@ _LIB = os.path.join(_HERE, "libevo_oracle.so")
 F32 = 0
 BF16 = 1
 F16 = 2
+F64 = 3
+I32 = 4
+I64 = 5
+
+REDUCE_MEDIAN = 0
+REDUCE_MEAN = 1
 
 F_CAND_NAN = 1 << 0
 F_CAND_INF = 1 << 1
@@ -83,6 +89,9 @@ def _load(path: str = None):
         lib.oracle_check_chunk.restype = None
         lib.oracle_fitness.argtypes = [ctypes.c_void_p] * 2 + [ctypes.c_uint32] * 2 + [ctypes.c_void_p] * 7
         lib.oracle_fitness.restype = ctypes.c_int
+        lib.oracle_fitness_ex.argtypes = ([ctypes.c_void_p] * 2 + [ctypes.c_uint32] * 2 + [ctypes.c_void_p]
+                                          + [ctypes.c_int] + [ctypes.c_void_p] * 6)
+        lib.oracle_fitness_ex.restype = ctypes.c_int
         lib.oracle_select_elite.argtypes = [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint32,
                                             ctypes.c_void_p]
         lib.oracle_select_elite.restype = ctypes.c_uint32
@@ -95,11 +104,12 @@ def _load(path: str = None):
 
 
 def _as_elems(x, dtype: int) -> np.ndarray:
-    """Flat contiguous view: float32 for F32, uint16 bit patterns for BF16 and F16."""
+    """Flat contiguous view: float32 / float64 / int32 / int64 for those types, uint16 bit
+    patterns for BF16 and F16."""
     a = np.ascontiguousarray(x).reshape(-1)
     if dtype == F16 and a.dtype == np.float16:
         a = a.view(np.uint16)
-    want = np.float32 if dtype == F32 else np.uint16
+    want = {F32: np.float32, F64: np.float64, I32: np.int32, I64: np.int64}.get(dtype, np.uint16)
     if a.dtype != want:
         raise TypeError("oracle expects %s elements, got %s" % (np.dtype(want), a.dtype))
     return a
@@ -159,8 +169,9 @@ def check_batch(ref, cands, dtype: int, atol: float, rtol: float, threads: int =
         return list(ex.map(lambda c: check_one(ref, c, dtype, atol, rtol, lib_path), cands))
 
 
-def fitness(timings, baseline, valid, lib_path: str = None) -> dict:
-    """Median/mean time, speedup, fitness per candidate and the population summary."""
+def fitness(timings, baseline, valid, lib_path: str = None, reducer: int = REDUCE_MEDIAN) -> dict:
+    """Median/mean time, speedup, fitness per candidate and the population summary.
+    ``reducer`` picks what the speedup is the ratio of: medians (default) or means."""
     lib = _load(lib_path)
     t = np.ascontiguousarray(timings, dtype=np.float32)
     if t.ndim != 2:
@@ -178,8 +189,8 @@ def fitness(timings, baseline, valid, lib_path: str = None) -> dict:
     fit = np.empty(P, np.float32)
     base = ctypes.c_float()
     pop = _Pop()
-    rc = lib.oracle_fitness(
-        t.ctypes.data, b.ctypes.data, P, T, v.ctypes.data, med.ctypes.data,
+    rc = lib.oracle_fitness_ex(
+        t.ctypes.data, b.ctypes.data, P, T, v.ctypes.data, int(reducer), med.ctypes.data,
         mean.ctypes.data, spd.ctypes.data, fit.ctypes.data,
         ctypes.addressof(base), ctypes.addressof(pop))
     if rc != 0:
@@ -210,7 +221,8 @@ class Variant:
     """The same interface bound to another build of the C file (used by the tests
     that check the pins catch planted mistakes)."""
 
-    F32, BF16, F16 = F32, BF16, F16
+    F32, BF16, F16, F64, I32, I64 = F32, BF16, F16, F64, I32, I64
+    REDUCE_MEDIAN, REDUCE_MEAN = REDUCE_MEDIAN, REDUCE_MEAN
     F_CAND_NAN, F_CAND_INF, F_REF_NAN, F_REF_INF = F_CAND_NAN, F_CAND_INF, F_REF_NAN, F_REF_INF
     F_NAN_SITE_DIFF, F_INF_DIFF = F_NAN_SITE_DIFF, F_INF_DIFF
 
@@ -226,8 +238,8 @@ class Variant:
     def check_batch(self, ref, cands, dtype, atol, rtol, threads=1):
         return check_batch(ref, cands, dtype, atol, rtol, threads, self.lib_path)
 
-    def fitness(self, timings, baseline, valid):
-        return fitness(timings, baseline, valid, self.lib_path)
+    def fitness(self, timings, baseline, valid, reducer=REDUCE_MEDIAN):
+        return fitness(timings, baseline, valid, self.lib_path, reducer)
 
     def select_elite(self, fitness_values, k):
         return select_elite(fitness_values, k, self.lib_path)

@@ -28,7 +28,10 @@
  * Parity status: every function here is pinned by tests that do not use this file
  * to produce their expected values (hand-written truth table and worked examples
  * under tests/golden/, numpy.isclose / numpy.median / math.fsum, an independent
- * element-at-a-time Python brute force, closed forms on the synthetic configs).
+ * element-at-a-time Python brute force, closed forms on the synthetic configs;
+ * binary64 tensors: the same table and class fixtures, numpy.isclose in binary64,
+ * agreement with the binary32 path where both are exact; integer tensors: Python
+ * integers; mean-based speedup: closed forms on exactly summable samples).
  *
  * Build:  gcc -O2 -std=c11 -ffp-contract=off -fPIC -shared
  * Every fp32 operation below is rounded on its own (no fused multiply-add, no
@@ -39,7 +42,14 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
+enum {
+    ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2,
+    ORACLE_F64 = 3, /* IEEE-754 binary64, checked in binary64          */
+    ORACLE_I32 = 4, /* two's complement, checked for exact equality    */
+    ORACLE_I64 = 5
+};
+
+enum { ORACLE_REDUCE_MEDIAN = 0, ORACLE_REDUCE_MEAN = 1 };
 
 enum {
     ORACLE_F_CAND_NAN      = 1u << 0, /* some candidate element is NaN          */
@@ -124,6 +134,102 @@ static float widen(const void *base, uint64_t i, int dtype)
 }
 
 /*
+ * binary64 tensors: the same rule and statistics with every operation in binary64
+ * (the binary32 tolerances are widened exactly).  Reading: a tensor is checked in its
+ * own precision.  The two maxima are reported in binary32, each element's value
+ * rounded to nearest (rounding is monotone, so this is the rounded maximum; values
+ * beyond the binary32 range become +Inf).  Relative error is 0 where |r| is below the
+ * smallest normal binary64.
+ */
+static void check_chunk_f64(oracle_check_acc *a, const double *ref, const double *cand,
+                            uint64_t n, float atol, float rtol)
+{
+    const double atol_d = (double)atol, rtol_d = (double)rtol;
+    for (uint64_t i = 0; i < n; ++i) {
+        const double rd = ref[i], cd = cand[i];
+        const double ard = fabs(rd);
+        const double scaled_d = rtol_d * ard;
+        const double tol_d = atol_d + scaled_d;
+        const int rd_nan = isnan(rd), cd_nan = isnan(cd);
+        const int rd_inf = isinf(rd), cd_inf = isinf(cd);
+        const int rd_fin = !rd_nan && !rd_inf;
+        const int cd_fin = !cd_nan && !cd_inf;
+        int match;
+
+        if (cd == rd)
+            match = 1;
+        else if (rd_fin && cd_fin)
+            match = (fabs(cd - rd) <= tol_d);
+        else
+            match = 0;
+        if (!match)
+            a->n_mismatch += 1;
+
+        if (cd_nan) a->flags |= ORACLE_F_CAND_NAN;
+        if (cd_inf) a->flags |= ORACLE_F_CAND_INF;
+        if (rd_nan) a->flags |= ORACLE_F_REF_NAN;
+        if (rd_inf) a->flags |= ORACLE_F_REF_INF;
+        if (cd_nan != rd_nan) a->flags |= ORACLE_F_NAN_SITE_DIFF;
+        if ((cd_inf || rd_inf) && !cd_nan && !rd_nan && cd != rd)
+            a->flags |= ORACLE_F_INF_DIFF;
+
+        if (rd_fin && cd_fin) {
+            const double dd = fabs(cd - rd); /* may overflow to +Inf: kept */
+            double inv_d = 0.0, qd;
+            float d32, q32;
+            if (ard >= 2.2250738585072014e-308) /* DBL_MIN, smallest normal */
+                inv_d = 1.0 / ard;
+            qd = dd * inv_d;
+            if (isnan(qd))
+                a->flags |= ORACLE_F_INTERNAL;
+            d32 = (float)dd;
+            q32 = (float)qd;
+            a->n_finite += 1;
+            if (d32 > a->max_abs_err) a->max_abs_err = d32;
+            if (q32 > a->max_rel_err) a->max_rel_err = q32;
+            a->sum_abs_err += dd;
+            a->sum_rel_err += qd;
+        }
+    }
+    a->n_seen += n;
+    a->valid = (a->n_mismatch == 0) ? 1u : 0u;
+}
+
+/*
+ * Integer tensors (index-valued outputs, e.g. of arg-reductions in the
+ * "Normalization & Reduction" class of the kernel classification table): exact
+ * equality, no tolerance.  d = |c - r| as an exact unsigned integer; its maximum is
+ * reported rounded to binary32 (nearest even), its sum in binary64 (each term rounded
+ * to binary64, added in index order).  Every element counts as finite; the relative
+ * statistics and the flags stay 0.
+ */
+static void check_chunk_int(oracle_check_acc *a, const void *ref, const void *cand,
+                            uint64_t n, int dtype)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        int64_t r, c;
+        uint64_t diff;
+        float diff32;
+        if (dtype == ORACLE_I32) {
+            r = ((const int32_t *)ref)[i];
+            c = ((const int32_t *)cand)[i];
+        } else {
+            r = ((const int64_t *)ref)[i];
+            c = ((const int64_t *)cand)[i];
+        }
+        if (c != r)
+            a->n_mismatch += 1;
+        diff = (c > r) ? (uint64_t)c - (uint64_t)r : (uint64_t)r - (uint64_t)c;
+        diff32 = (float)diff;
+        a->n_finite += 1;
+        if (diff32 > a->max_abs_err) a->max_abs_err = diff32;
+        a->sum_abs_err += (double)diff;
+    }
+    a->n_seen += n;
+    a->valid = (a->n_mismatch == 0) ? 1u : 0u;
+}
+
+/*
  * Functional-correctness constraint of Sec. 3.1 / functional testing of Sec. 4.3,
  * for one candidate over n elements, element by element in index order.
  *
@@ -141,6 +247,14 @@ static float widen(const void *base, uint64_t i, int dtype)
 void oracle_check_chunk(oracle_check_acc *a, const void *ref, const void *cand,
                         uint64_t n, int dtype, float atol, float rtol)
 {
+    if (dtype == ORACLE_F64) {
+        check_chunk_f64(a, (const double *)ref, (const double *)cand, n, atol, rtol);
+        return;
+    }
+    if (dtype == ORACLE_I32 || dtype == ORACLE_I64) {
+        check_chunk_int(a, ref, cand, n, dtype);
+        return;
+    }
     for (uint64_t i = 0; i < n; ++i) {
         const float r = widen(ref, i, dtype);
         const float c = widen(cand, i, dtype);
@@ -243,16 +357,17 @@ static void row_reduce(const float *row, uint32_t T, float *scratch,
 /*
  * Objective of Sec. 3.1 with the metric of Sec. 5.1: per candidate, the time of
  * T runs is reduced to its median (and mean), speedup = baseline median /
- * candidate median (fp32 division), fitness = speedup for a candidate that met
+ * candidate median (fp32 division; with reducer == ORACLE_REDUCE_MEAN, baseline mean /
+ * candidate mean instead), fitness = speedup for a candidate that met
  * the constraint and 0 for one that did not.  Population: index of the largest
  * fitness (lowest index on ties, P when every fitness is 0), that fitness
  * floored at 1.0, the number of valid candidates and its ratio to P.
  * Returns 0, or -1 when scratch memory cannot be had.
  */
-int oracle_fitness(const float *timings, const float *baseline, uint32_t P,
-                   uint32_t T, const uint32_t *valid, float *median_ms,
-                   float *mean_ms, float *speedup, float *fitness,
-                   float *base_median_out, oracle_pop *pop)
+int oracle_fitness_ex(const float *timings, const float *baseline, uint32_t P,
+                      uint32_t T, const uint32_t *valid, int reducer, float *median_ms,
+                      float *mean_ms, float *speedup, float *fitness,
+                      float *base_median_out, oracle_pop *pop)
 {
     float *scratch = (float *)malloc((size_t)(T ? T : 1) * sizeof(float));
     float base_median, base_mean;
@@ -269,6 +384,8 @@ int oracle_fitness(const float *timings, const float *baseline, uint32_t P,
         row_reduce(timings + (size_t)p * T, T, scratch, &median_ms[p], &mean_ms[p]);
         if (isnan(median_ms[p]) || isnan(base_median))
             speedup[p] = 0.0f;
+        else if (reducer == ORACLE_REDUCE_MEAN) /* the "average over 100 runs" of Sec. 4.3 */
+            speedup[p] = base_mean / mean_ms[p];
         else
             speedup[p] = base_median / median_ms[p];
         fitness[p] = valid[p] ? speedup[p] : 0.0f;
@@ -287,6 +404,16 @@ int oracle_fitness(const float *timings, const float *baseline, uint32_t P,
         pop->valid_rate = (float)n_valid / (float)P;
     }
     return 0;
+}
+
+/* The default: timings reduced by their median (appendix on threats to validity). */
+int oracle_fitness(const float *timings, const float *baseline, uint32_t P,
+                   uint32_t T, const uint32_t *valid, float *median_ms,
+                   float *mean_ms, float *speedup, float *fitness,
+                   float *base_median_out, oracle_pop *pop)
+{
+    return oracle_fitness_ex(timings, baseline, P, T, valid, ORACLE_REDUCE_MEDIAN, median_ms,
+                             mean_ms, speedup, fitness, base_median_out, pop);
 }
 
 /*

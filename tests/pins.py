@@ -77,10 +77,10 @@ def pin_flag_classes(orc):
                 for name in flags.split(","):
                     want |= bit[name]
             cv = 2.5 if ccls == "fin" else val[ccls]
-            got = orc.check_one(np.array([val[rcls]], np.float32), np.array([cv], np.float32),
-                                orc.F32, 1.0, 1.0)
-            assert got["flags"] == want, (rcls, ccls, got)
-            assert got["n_finite"] == int(in_stats), (rcls, ccls, got)
+            for code, npdt in ((orc.F32, np.float32), (orc.F64, np.float64)):   # same classes in binary64
+                got = orc.check_one(np.array([val[rcls]], npdt), np.array([cv], npdt), code, 1.0, 1.0)
+                assert got["flags"] == want, (rcls, ccls, npdt, got)
+                assert got["n_finite"] == int(in_stats), (rcls, ccls, npdt, got)
             seen += 1
     assert seen == 16
 
@@ -355,8 +355,208 @@ def pin_select_elite(orc):
         assert got["elite"].tolist() == order + [P] * (k - len(order)), (P, k)
 
 
+_D = np.float64
+SPECIAL64 = {   # the binary64 analogues of SPECIAL, under the same names
+    "+0": _D(0.0), "-0": _D(-0.0), "1": _D(1.0), "1+ulp": np.nextafter(_D(1), _D(2)),
+    "-1": _D(-1.0), "FLT_MIN": _D(2.2250738585072014e-308), "DENORM_MIN": _D(5e-324),
+    "FLT_MAX": _D(1.7976931348623157e308), "+Inf": _D(np.inf), "-Inf": _D(-np.inf),
+    "NaN": _D(np.nan),
+}
+
+
+def pin_f64_truth_table(orc):
+    """The hand-written match matrix holds for the binary64 analogues of its values too
+    (the worked tolerances of the fixture carry over: 0.25 + fl(0.25*(1+2^-52)) rounds
+    to 0.5, and 0.25*DBL_MAX is far below DBL_MAX - 1)."""
+    rows = []
+    with open(os.path.join(GOLDEN, "match_truth_table.txt")) as fh:
+        for line in fh:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                rows.append(line.split())
+    names = rows[0][1:]
+    for row in rows[1:]:
+        for cname, cell in zip(names, row[1:]):
+            r = np.array([SPECIAL64[row[0]]], np.float64)
+            c = np.array([SPECIAL64[cname]], np.float64)
+            got = orc.check_one(r, c, orc.F64, 0.25, 0.25)
+            assert got["n_mismatch"] == (0 if cell == "M" else 1), (row[0], cname, got)
+
+
+def _mixed_pair64(rng, n):
+    r = rng.standard_normal(n) * 3.0
+    c = r * (1 + 0.02 * rng.standard_normal(n))
+    far = rng.random(n) < 0.1
+    c[far] = rng.uniform(-10, 10, far.sum())
+    for arr in (r, c):
+        k = max(1, n // 50)
+        arr[rng.integers(0, n, k)] = np.inf
+        arr[rng.integers(0, n, k)] = -np.inf
+        arr[rng.integers(0, n, k)] = np.nan
+        arr[rng.integers(0, n, k)] = 0.0
+        arr[rng.integers(0, n, k)] = 1e-310            # subnormal
+        arr[rng.integers(0, n, k)] = 1e-40             # below the binary32 range, normal here
+    same = rng.random(n) < 0.2
+    c[same] = r[same]
+    return r, c
+
+
+def pin_f64_numpy_isclose_sums_maxima(orc):
+    """binary64 tensors: mismatches against numpy.isclose in binary64 (tolerances are the
+    binary32 values, widened), sums against math.fsum, maxima against a scan with Python
+    floats, rounded to binary32 at the end."""
+    rng = np.random.default_rng(4321)
+    for n, atol, rtol in ((1, 1e-2, 1e-2), (4099, 1e-2, 1e-2), (4099, 0.0, 3e-2), (2000, 5e-2, 0.0),
+                          (1000, 0.0, 0.0), (3000, 1e-9, 1e-9)):
+        r, c = _mixed_pair64(rng, n)
+        a64, r64 = float(np.float32(atol)), float(np.float32(rtol))
+        with np.errstate(all="ignore"):
+            close = np.isclose(c, r, rtol=r64, atol=a64, equal_nan=False)
+        got = orc.check_one(r, c, orc.F64, atol, rtol)
+        assert got["n_mismatch"] == int((~close).sum()), (n, atol, rtol, got)
+        both = np.isfinite(r) & np.isfinite(c)
+        assert got["n_finite"] == int(both.sum()) and got["n_elems"] == n
+        ds, qs = [], []
+        for ri, ci in zip(r.tolist(), c.tolist()):
+            if not (math.isfinite(ri) and math.isfinite(ci)):
+                continue
+            d = abs(ci - ri)
+            q = d * (1.0 / abs(ri)) if abs(ri) >= 2.2250738585072014e-308 else 0.0
+            ds.append(d)
+            qs.append(q)
+        if ds:
+            with np.errstate(over="ignore"):     # beyond the binary32 range: +Inf, as intended
+                assert _same_f32(got["max_abs_err"], np.float32(max(ds))), (n, got)
+                assert _same_f32(got["max_rel_err"], np.float32(max(qs))), (n, got)
+            for key, terms in (("sum_abs_err", ds), ("sum_rel_err", qs)):
+                exact = math.fsum(terms)
+                assert abs(got[key] - exact) <= 1e-12 * exact, (key, got[key], exact)
+    # the relative error is d * (1/|r|), two roundings -- not d / |r| (one element: the sum
+    # is the term itself, in binary64)
+    pairs = [(float(a), float(d)) for a in range(3, 60) for d in range(1, 60)
+             if d * (1.0 / a) != d / a]
+    assert len(pairs) > 20
+    for a, d in pairs[:20]:
+        got = orc.check_one(np.array([a]), np.array([a + d]), orc.F64, 0.0, 0.0)
+        assert got["sum_rel_err"] == d * (1.0 / a) and got["sum_abs_err"] == d
+    # a difference binary32 cannot tell apart decides here
+    r = np.array([1.0], np.float64)
+    c = np.array([1.0 + 2.0 ** -40], np.float64)
+    assert orc.check_one(r, c, orc.F64, 0.0, 0.0)["n_mismatch"] == 1
+    assert orc.check_one(r, c, orc.F64, 0.0, 1e-6)["n_mismatch"] == 0
+    # a maximum beyond the binary32 range is reported as +Inf, the sum stays finite
+    got = orc.check_one(np.array([0.0, 1.0]), np.array([1e300, 1.0]), orc.F64, 0.0, 0.0)
+    assert np.isposinf(got["max_abs_err"]) and got["sum_abs_err"] == 1e300 and got["n_finite"] == 2
+    # relative error is dropped below DBL_MIN, kept at DBL_MIN
+    got = orc.check_one(np.array([2.0e-308]), np.array([0.0]), orc.F64, 1.0, 0.0)
+    assert got["max_rel_err"] == 0 and got["sum_rel_err"] == 0
+    got = orc.check_one(np.array([2.2250738585072014e-308]), np.array([0.0]), orc.F64, 1.0, 0.0)
+    assert got["max_rel_err"] == 1.0
+    # chunked feeding equals one pass
+    rr, cc = _mixed_pair64(rng, 3001)
+    whole = orc.check_one(rr, cc, orc.F64, 1e-2, 1e-2)
+    acc = orc.CheckAccumulator(orc.F64, 1e-2, 1e-2)
+    for lo, hi in ((0, 7), (7, 7), (7, 2000), (2000, 3001)):
+        acc.feed(rr[lo:hi], cc[lo:hi])
+    assert acc.result() == whole
+
+
+def pin_f64_agrees_with_f32_where_both_are_exact(orc):
+    """On a dyadic grid (multiples of 2^-6 in [-8, 8], tolerances 2^-2) every operation of the
+    match rule and of the absolute statistics is exact in both precisions, so checking the
+    same values as binary64 and as binary32 tensors must give the same numbers."""
+    rng = np.random.default_rng(64)
+    r = rng.integers(-512, 513, 5000) / 64.0
+    c = r + rng.integers(-200, 201, 5000) / 64.0
+    g64 = orc.check_one(r, c, orc.F64, 0.25, 0.25)
+    g32 = orc.check_one(r.astype(np.float32), c.astype(np.float32), orc.F32, 0.25, 0.25)
+    for key in ("n_mismatch", "n_finite", "sum_abs_err", "flags", "valid"):
+        assert g64[key] == g32[key], key
+    assert _same_f32(g64["max_abs_err"], g32["max_abs_err"])
+    want = int((np.abs(c - r) > 0.25 + 0.25 * np.abs(r)).sum())
+    assert g64["n_mismatch"] == want and want > 0
+
+
+def pin_integer_equality(orc):
+    """Integer tensors: exact equality; |c - r| as an exact integer (Python ints), its
+    maximum rounded to binary32 by numpy, its sum exact while it fits 2^53."""
+    rng = np.random.default_rng(5)
+    for code, npdt, lo, hi in ((orc.I32, np.int32, -2 ** 31, 2 ** 31 - 1), (orc.I64, np.int64, -2 ** 63, 2 ** 63 - 1)):
+        for n in (1, 63, 4099):
+            r = rng.integers(-1000, 1000, n).astype(npdt)
+            c = r.copy()
+            sites = rng.random(n) < 0.3
+            c[sites] += rng.integers(-5, 6, int(sites.sum())).astype(npdt)   # some of these are +0
+            got = orc.check_one(r, c, code, 123.0, 456.0)                      # tolerances play no part
+            diffs = [abs(int(ci) - int(ri)) for ri, ci in zip(r, c)]
+            assert got["n_mismatch"] == sum(1 for d in diffs if d) == int(np.count_nonzero(c != r))
+            assert got["n_finite"] == n and got["n_elems"] == n and got["flags"] == 0
+            assert got["valid"] == (1 if not any(diffs) else 0)
+            assert _same_f32(got["max_abs_err"], np.float32(max(diffs)))
+            assert got["sum_abs_err"] == float(sum(diffs))
+            assert got["max_rel_err"] == 0 and got["sum_rel_err"] == 0
+        # extremes: the magnitude needs one bit more than the type has
+        r = np.array([lo, hi, lo, 0, -1], npdt)
+        c = np.array([hi, lo, lo, hi, hi], npdt)
+        got = orc.check_one(r, c, code, 0.0, 0.0)
+        diffs = [abs(int(ci) - int(ri)) for ri, ci in zip(r, c)]
+        assert diffs[0] == hi - lo
+        assert got["n_mismatch"] == 4
+        assert _same_f32(got["max_abs_err"], np.float32(float(max(diffs))))   # 2^32 and 2^64
+        assert abs(got["sum_abs_err"] - float(sum(diffs))) <= 4 * 2.0 ** -53 * float(sum(diffs))
+        # values that differ only beyond 24 or 53 bits are still different
+        r = np.array([2 ** 30], npdt)
+        c = np.array([2 ** 30 + 1], npdt)
+        assert orc.check_one(r, c, code, 1e30, 1e30)["n_mismatch"] == 1
+        # identical, empty, chunked
+        r = rng.integers(lo // 2, hi // 2, 1000).astype(npdt)
+        got = orc.check_one(r, r.copy(), code, 0.0, 0.0)
+        assert got["valid"] == 1 and got["max_abs_err"] == 0 and got["sum_abs_err"] == 0
+        e = orc.check_one(np.zeros(0, npdt), np.zeros(0, npdt), code, 0.0, 0.0)
+        assert e["valid"] == 1 and e["n_finite"] == 0
+        c = r.copy()
+        c[::7] -= 3
+        whole = orc.check_one(r, c, code, 0.0, 0.0)
+        acc = orc.CheckAccumulator(code, 0.0, 0.0)
+        for a, b in ((0, 1), (1, 500), (500, 1000)):
+            acc.feed(r[a:b], c[a:b])
+        assert acc.result() == whole and whole["n_mismatch"] == len(range(0, 1000, 7))
+    # 2^40 + 1 needs int64: as int32 data it cannot even be written, as int64 it is one mismatch
+    got = orc.check_one(np.array([2 ** 40], np.int64), np.array([2 ** 40 + 1], np.int64), orc.I64, 0.0, 0.0)
+    assert got["n_mismatch"] == 1 and got["max_abs_err"] == 1.0
+
+
+def pin_mean_reducer(orc):
+    """Speedup as a ratio of means (the "average" reading of Sec. 4.3) on samples whose sums
+    are exact in any order, so the expected values are closed forms."""
+    t = np.array([[1, 2, 9], [2, 2, 2], [4, 4, 4], [1, 1, np.nan]], np.float32)
+    b = np.array([2, 4, 6], np.float32)
+    valid = np.array([1, 1, 0, 1], np.uint32)
+    got = orc.fitness(t, b, valid, reducer=orc.REDUCE_MEAN)
+    assert got["mean_ms"][:3].tolist() == [4.0, 2.0, 4.0] and got["median_ms"][:3].tolist() == [2.0, 2.0, 4.0]
+    assert got["speedup"].tolist() == [1.0, 2.0, 1.0, 0.0]          # 4/4, 4/2, 4/4, unusable row
+    assert got["fitness"].tolist() == [1.0, 2.0, 0.0, 0.0]
+    assert got["best_idx"] == 1 and got["best_speedup"] == 2.0 and got["n_valid"] == 3
+    med = orc.fitness(t, b, valid)                                   # default: ratio of medians
+    assert med["speedup"].tolist() == [2.0, 2.0, 1.0, 0.0]
+    assert orc.fitness(t, b, valid, reducer=orc.REDUCE_MEDIAN)["speedup"].tolist() == med["speedup"].tolist()
+    # random dyadic samples: every partial sum is exact, so the mean is fl32(sum / T) exactly
+    rng = np.random.default_rng(17)
+    T = 100
+    t = (rng.integers(1, 4096, (5, T)) / 1024.0).astype(np.float32)
+    b = (rng.integers(1, 4096, T) / 1024.0).astype(np.float32)
+    got = orc.fitness(t, b, np.ones(5, np.uint32), reducer=orc.REDUCE_MEAN)
+    bm = np.float32(float(b.astype(np.float64).sum()) / T)
+    for p in range(5):
+        m = np.float32(float(t[p].astype(np.float64).sum()) / T)
+        assert _same_f32(got["mean_ms"][p], m)
+        assert _same_f32(got["speedup"][p], bm / m)
+
+
 ALL_PINS = [
     pin_truth_table, pin_flag_classes, pin_worked_check_examples, pin_worked_fitness_examples,
     pin_numpy_isclose, pin_sums_and_maxima, pin_invariants, pin_bf16_widening, pin_f16_widening,
     pin_median_and_speedup, pin_unusable_timing_rows, pin_select_elite,
+    pin_f64_truth_table, pin_f64_numpy_isclose_sums_maxima, pin_f64_agrees_with_f32_where_both_are_exact,
+    pin_integer_equality, pin_mean_reducer,
 ]

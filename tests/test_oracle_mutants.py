@@ -48,6 +48,27 @@ MUTANTS = [
     ("elite_takes_infeasible", "            if (!(fitness[i] > 0.0f))\n                continue;", "            if (0)\n                continue;"),
     ("elite_worst_first", "if (best == P || fitness[i] > fitness[best])", "if (best == P || fitness[i] < fitness[best])"),
     ("valid_rate_over_T", "(float)n_valid / (float)P", "(float)n_valid / (float)T"),
+    ("f64_tolerance_scaled_by_candidate", "const double scaled_d = rtol_d * ard;", "const double scaled_d = rtol_d * fabs(cd);"),
+    ("f64_strict_less_than", "match = (fabs(cd - rd) <= tol_d);", "match = (fabs(cd - rd) < tol_d);"),
+    ("f64_difference_in_binary32", "match = (fabs(cd - rd) <= tol_d);", "match = (fabs((double)((float)cd - (float)rd)) <= tol_d);"),
+    ("f64_no_equality_shortcut", "if (cd == rd)", "if (0)"),
+    ("f64_no_finiteness_guard", "else if (rd_fin && cd_fin)", "else if (1)"),
+    ("f64_dbl_min_exclusive", "if (ard >= 2.2250738585072014e-308)", "if (ard > 2.2250738585072014e-308)"),
+    ("f64_binary32_threshold", "if (ard >= 2.2250738585072014e-308)", "if (ard >= 1.17549435e-38)"),
+    ("f64_sum_of_rounded_terms", "a->sum_abs_err += dd;", "a->sum_abs_err += (double)d32;"),
+    ("f64_division_instead_of_reciprocal", "qd = dd * inv_d;", "qd = (inv_d != 0.0) ? dd / ard : 0.0;"),
+    ("f64_rel_max_tracks_abs", "if (q32 > a->max_rel_err) a->max_rel_err = q32;", "if (d32 > a->max_rel_err) a->max_rel_err = d32;"),
+    ("f64_nan_site_one_sided", "if (cd_nan != rd_nan)", "if (cd_nan && !rd_nan)"),
+    ("int_mismatch_one_sided", "        if (c != r)\n            a->n_mismatch += 1;", "        if (c > r)\n            a->n_mismatch += 1;"),
+    ("int_off_by_one_tolerated", "        if (c != r)\n            a->n_mismatch += 1;", "        if (c > r + 1 || r > c + 1)\n            a->n_mismatch += 1;"),
+    ("int_difference_not_a_magnitude", "diff = (c > r) ? (uint64_t)c - (uint64_t)r : (uint64_t)r - (uint64_t)c;", "diff = (uint64_t)c - (uint64_t)r;"),
+    ("int_difference_in_32_bits", "diff = (c > r) ? (uint64_t)c - (uint64_t)r : (uint64_t)r - (uint64_t)c;", "diff = (uint32_t)((c > r) ? (uint64_t)c - (uint64_t)r : (uint64_t)r - (uint64_t)c);"),
+    ("int_reference_read_unsigned", "r = ((const int32_t *)ref)[i];", "r = ((const uint32_t *)ref)[i];"),
+    ("int_sum_in_binary32", "a->sum_abs_err += (double)diff;", "a->sum_abs_err += (double)diff32;"),
+    ("int_not_counted_finite", "        diff32 = (float)diff;\n        a->n_finite += 1;", "        diff32 = (float)diff;"),
+    ("mean_reducer_keeps_median_baseline", "speedup[p] = base_mean / mean_ms[p];", "speedup[p] = base_median / mean_ms[p];"),
+    ("mean_reducer_ignored", "else if (reducer == ORACLE_REDUCE_MEAN)", "else if (0)"),
+    ("mean_reducer_always", "else if (reducer == ORACLE_REDUCE_MEAN)", "else if (1)"),
 ]
 
 
