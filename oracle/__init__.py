@@ -11,6 +11,7 @@ from __future__ import annotations
 import ctypes
 import os
 import subprocess
+import threading
 from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
@@ -73,11 +74,19 @@ class _Pop(ctypes.Structure):
 
 
 _libs = {}
+_load_lock = threading.Lock()
 
 
 def _load(path: str = None):
     """ctypes handle of the oracle library (default: built from evo_oracle.c here)."""
     key = path or _LIB
+    if key in _libs:
+        return _libs[key]
+    with _load_lock:   # one thread compiles and binds; check_batch may get here from several
+        return _load_locked(path, key)
+
+
+def _load_locked(path, key):
     if key not in _libs:
         lib = ctypes.CDLL(path or build())
         lib.oracle_check_init.argtypes = [ctypes.POINTER(_Acc)]
