@@ -6,7 +6,7 @@ batched (or segmented) tolerance check of every candidate against its reference,
 then the median-timing / speedup / fitness reduction.  Inputs are resident in HBM
 before the timed region starts.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c3h|c4|c5|cases]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c3h|c4|c5|cases|f64|i32|i64]
                     [--no-cpu-baseline] [--no-read-ceiling] [--copy-calibration]
 
 --copy-calibration runs only a plain device-to-device copy of known size (used to
@@ -84,6 +84,11 @@ def build_workload(name: str):
     if name == "c3h":
         import torch
         return synth.softmax_bf16("cuda", B=32, R=128, C=4096, P=64, T=100, dtype=torch.float16)
+    if name in ("f64", "i32", "i64"):
+        import torch
+        dt = {"f64": torch.float64, "i32": torch.int32, "i64": torch.int64}[name]
+        # the bytes of the default workload: 2^26 four-byte or 2^25 eight-byte elements
+        return synth.dense_typed("cuda", dt, n=(1 << 26) if name == "i32" else (1 << 25), P=16, T=100)
     if name == "cases":
         return synth.multi_case_f32("cuda", K=5, side=4096, P=16, T=100)
     raise SystemExit("unknown workload %r" % name)
@@ -102,7 +107,8 @@ def cpu_baseline(w, budget_elems: int):
     rows = []
     for seg in w.segments:
         m = seg.n if frac >= 1.0 else max(1, int(seg.n * frac))
-        dt = {"bf16": oracle.BF16, "f16": oracle.F16}.get(seg.dtype_name, oracle.F32)
+        dt = {"bf16": oracle.BF16, "f16": oracle.F16, "f64": oracle.F64, "i32": oracle.I32,
+              "i64": oracle.I64}.get(seg.dtype_name, oracle.F32)
         ref = synth.to_oracle_array(seg.ref[:m])
         for c in seg.cands:
             ch = synth.to_oracle_array(c[:m])
@@ -132,7 +138,8 @@ def cpu_baseline(w, budget_elems: int):
     t_par = 0.0
     for seg in w.segments:
         m = seg.n if frac >= 1.0 else max(1, int(seg.n * frac))
-        dt = {"bf16": oracle.BF16, "f16": oracle.F16}.get(seg.dtype_name, oracle.F32)
+        dt = {"bf16": oracle.BF16, "f16": oracle.F16, "f64": oracle.F64, "i32": oracle.I32,
+              "i64": oracle.I64}.get(seg.dtype_name, oracle.F32)
         ref = synth.to_oracle_array(seg.ref[:m])
         cands = [synth.to_oracle_array(c[:m]) for c in seg.cands]
         t0 = time.perf_counter()
@@ -198,7 +205,8 @@ def main() -> int:
     w = build_workload(args.workload)
     torch.cuda.synchronize()
     segs = w.segments
-    dcode = lambda s: {"bf16": evo.EVO_BF16, "f16": evo.EVO_F16}.get(s.dtype_name, evo.EVO_F32)  # noqa: E731
+    dcode = lambda s: {"bf16": evo.EVO_BF16, "f16": evo.EVO_F16, "f64": evo.EVO_F64,  # noqa: E731
+                       "i32": evo.EVO_I32, "i64": evo.EVO_I64}.get(s.dtype_name, evo.EVO_F32)
     chk = evo.Checker(dcode(segs[0]), segs[0].n, w.atol, w.rtol)
     P = w.P
     stats = chk.new_stats(P)
@@ -264,7 +272,8 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": {"bf16": "bf16->f32", "f16": "f16->f32"}.get(segs[0].dtype_name, "f32"),
+        "dtype": {"bf16": "bf16->f32", "f16": "f16->f32", "f64": "f64", "i32": "i32",
+                  "i64": "i64"}.get(segs[0].dtype_name, "f32"),
         "data": "synthetic",
         "config": {"workload": w.name, "P": P, "cand_elems": w.cand_elems,
                    "algorithmic_bytes": alg_bytes, "T": int(w.timings.shape[1]),

@@ -26,6 +26,7 @@
  *     part in a tolerance check.  EVO_BF16 elements are the upper 16 bits of an
  *     IEEE-754 binary32 and EVO_F16 elements are IEEE-754 binary16, both little
  *     endian; they are widened exactly and every operation is done in binary32.
+ *     The other element types are listed with evo_dtype and evo_stats.
  *   - Every call that takes a stream only enqueues work on it and returns; results
  *     are defined once the caller has synchronised that stream.  `stream` is a
  *     hipStream_t passed as void* (NULL = the null stream).
@@ -52,7 +53,15 @@ extern "C" {
 
 typedef struct evo_check evo_check_t; /* opaque, owned by the library */
 
-typedef enum { EVO_F32 = 0, EVO_BF16 = 1, EVO_F16 = 2 } evo_dtype;
+typedef enum {
+    EVO_F32  = 0, /* IEEE-754 binary32                                             */
+    EVO_BF16 = 1, /* upper 16 bits of a binary32, checked in binary32               */
+    EVO_F16  = 2, /* IEEE-754 binary16, checked in binary32                         */
+    EVO_F64  = 3, /* IEEE-754 binary64, checked in binary64                         */
+    EVO_I32  = 4, /* two's complement integers (index-valued outputs, e.g. of the   */
+    EVO_I64  = 5  /* arg-reductions among the reduction operations of the kernel    */
+                  /* classification table): exact equality, tolerances play no part */
+} evo_dtype;
 
 typedef enum {
     EVO_OK         = 0,
@@ -87,6 +96,14 @@ enum {
  * Statistics run over elements where both sides are finite: d = |c - r| (kept when
  * it overflows to +Inf), q = d * (1/|r|) with the reciprocal rounded first and
  * q = 0 where |r| < FLT_MIN.
+ *
+ * EVO_F64: the same rule and statistics with every operation in binary64 (atol and rtol
+ * widened exactly; q = 0 where |r| < DBL_MIN); the two maxima are reported rounded to
+ * binary32 (to nearest; +Inf beyond its range).
+ * EVO_I32 / EVO_I64: match <=> c == r.  d = |c - r| is an exact unsigned integer; every
+ * element counts as finite; max_abs_err is the largest d rounded to binary32 (to nearest
+ * even), sum_abs_err the sum of the d (each rounded to binary64); max_rel_err, sum_rel_err
+ * and flags are 0.
  */
 typedef struct evo_stats {
     uint64_t n_mismatch;  /* elements failing the rule (exact)                     */
@@ -205,6 +222,20 @@ EVO_API int evo_check_cases(evo_check_t *c, const evo_segment *cases, uint32_t K
 EVO_API int evo_fitness(evo_check_t *c, const float *timings, const float *baseline,
                 uint32_t P, uint32_t T, void *stream, evo_stats *stats,
                 evo_pop_summary *summary);
+
+/*
+ * evo_fitness with the reduction of the T samples that feeds the speedup chosen by the
+ * caller.  Sec. 4.3 and the reproducibility guidelines average the runs, the appendix on
+ * threats to validity takes their median: EVO_REDUCE_MEDIAN (what evo_fitness does) gives
+ * speedup = median(baseline) / median(candidate), EVO_REDUCE_MEAN gives
+ * mean(baseline) / mean(candidate) with the means as defined above.  median_ms and mean_ms
+ * are written either way; everything else is as in evo_fitness.
+ * Errors: as evo_fitness, plus EVO_ERR_SIZE for an unknown reducer.
+ */
+typedef enum { EVO_REDUCE_MEDIAN = 0, EVO_REDUCE_MEAN = 1 } evo_reducer;
+EVO_API int evo_fitness_ex(evo_check_t *c, const float *timings, const float *baseline,
+                           uint32_t P, uint32_t T, int reducer /* evo_reducer */, void *stream,
+                           evo_stats *stats, evo_pop_summary *summary);
 
 /*
  * Population management of Sec. 3.2.2 (elite preservation): the indices of the k

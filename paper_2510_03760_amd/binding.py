@@ -21,6 +21,12 @@ lib_path = os.path.join(_HERE, "libevo.so")
 EVO_F32 = 0
 EVO_BF16 = 1
 EVO_F16 = 2
+EVO_F64 = 3
+EVO_I32 = 4
+EVO_I64 = 5
+
+EVO_REDUCE_MEDIAN = 0
+EVO_REDUCE_MEAN = 1
 
 
 class EvoError(RuntimeError):
@@ -81,12 +87,13 @@ def _load() -> ctypes.CDLL:
     h.evo_check_segmented.argtypes = [vp, ctypes.POINTER(EvoSegment), u32, vp, vp, u32]
     h.evo_check_cases.argtypes = [vp, ctypes.POINTER(EvoSegment), u32, vp, vp]
     h.evo_fitness.argtypes = [vp, vp, vp, u32, u32, vp, vp, vp]
+    h.evo_fitness_ex.argtypes = [vp, vp, vp, u32, u32, ctypes.c_int, vp, vp, vp]
     h.evo_select_elite.argtypes = [vp, vp, u32, u32, vp, vp, vp]
     h.evo_check_destroy.argtypes = [vp]
     h.evo_strerror.argtypes = [ctypes.c_int]
     h.evo_strerror.restype = ctypes.c_char_p
     for name in ("evo_check_create", "evo_check_batch", "evo_check_segmented", "evo_check_cases",
-                 "evo_fitness", "evo_select_elite",
+                 "evo_fitness", "evo_fitness_ex", "evo_select_elite",
                  "evo_check_destroy"):
         getattr(h, name).restype = ctypes.c_int
     return h
@@ -178,6 +185,14 @@ def evo_fitness(ctx: int, timings, baseline, P: int, T: int, stream, stats, summ
         raise EvoError(rc, "evo_fitness")
 
 
+def evo_fitness_ex(ctx: int, timings, baseline, P: int, T: int, reducer: int, stream, stats,
+                   summary=None) -> None:
+    rc = lib.evo_fitness_ex(ctx, _ptr(timings), _ptr(baseline), int(P), int(T), int(reducer),
+                            _stream(stream), _ptr(stats), _ptr(summary))
+    if rc != 0:
+        raise EvoError(rc, "evo_fitness_ex")
+
+
 def evo_select_elite(ctx: int, stats, P: int, k: int, stream, elite, n_elite=None) -> None:
     rc = lib.evo_select_elite(ctx, _ptr(stats), int(P), int(k), _stream(stream), _ptr(elite),
                               _ptr(n_elite))
@@ -238,10 +253,14 @@ class Checker:
                         stream if stream is not None else torch.cuda.current_stream(), stats)
 
     def fitness(self, timings: torch.Tensor, baseline: torch.Tensor, stats: torch.Tensor,
-                summary: Optional[torch.Tensor] = None, stream=None) -> None:
+                summary: Optional[torch.Tensor] = None, stream=None,
+                reducer: Optional[int] = None) -> None:
         P, T = timings.shape
-        evo_fitness(self.ctx, timings, baseline, P, T,
-                    stream if stream is not None else torch.cuda.current_stream(), stats, summary)
+        st = stream if stream is not None else torch.cuda.current_stream()
+        if reducer is None:
+            evo_fitness(self.ctx, timings, baseline, P, T, st, stats, summary)
+        else:
+            evo_fitness_ex(self.ctx, timings, baseline, P, T, reducer, st, stats, summary)
 
 
     def select_elite(self, stats: torch.Tensor, P: int, k: int, elite: torch.Tensor,

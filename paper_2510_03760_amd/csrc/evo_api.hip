@@ -61,9 +61,9 @@ bool is_live(evo_check *c) {
     return c != nullptr && g_live.count(c) != 0;
 }
 
-uint32_t elem_size(uint32_t dtype) { return dtype == EVO_F32 ? 4u : 2u; }
+uint32_t elem_size(uint32_t dtype) { return evo::elem_bytes(dtype); }
 
-bool dtype_ok(uint32_t dtype) { return dtype == EVO_F32 || dtype == EVO_BF16 || dtype == EVO_F16; }
+bool dtype_ok(uint32_t dtype) { return dtype <= EVO_I64; }
 
 int dev(hipError_t e) { return e == hipSuccess ? EVO_OK : (e == hipErrorOutOfMemory ? EVO_ERR_NOMEM : EVO_ERR_DEVICE); }
 
@@ -411,8 +411,15 @@ int evo_check_cases(evo_check_t *c, const evo_segment *cases, uint32_t K, void *
 
 int evo_fitness(evo_check_t *c, const float *timings, const float *baseline, uint32_t P,
                 uint32_t T, void *stream, evo_stats *stats, evo_pop_summary *summary) {
+    return evo_fitness_ex(c, timings, baseline, P, T, EVO_REDUCE_MEDIAN, stream, stats, summary);
+}
+
+int evo_fitness_ex(evo_check_t *c, const float *timings, const float *baseline, uint32_t P,
+                   uint32_t T, int reducer, void *stream, evo_stats *stats,
+                   evo_pop_summary *summary) {
     if (!is_live(c)) return EVO_ERR_HANDLE;
     if (!timings || !baseline || !stats) return EVO_ERR_NULL;
+    if (reducer != EVO_REDUCE_MEDIAN && reducer != EVO_REDUCE_MEAN) return EVO_ERR_SIZE;
     if (P == 0 || T == 0 || T > EVO_FITNESS_MAX_T || P > (1u << 20)) return EVO_ERR_SIZE;
     if ((reinterpret_cast<uintptr_t>(timings) & 3u) || (reinterpret_cast<uintptr_t>(baseline) & 3u) ||
         (reinterpret_cast<uintptr_t>(stats) & 7u) || (reinterpret_cast<uintptr_t>(summary) & 3u))
@@ -421,8 +428,8 @@ int evo_fitness(evo_check_t *c, const float *timings, const float *baseline, uin
     if (rc != EVO_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if ((rc = ensure_fitness_scratch(c, st)) != EVO_OK) return rc;
-    return dev(evo::launch_fitness(timings, baseline, P, T, stats, summary, c->d_base_median,
-                                   c->d_fit_ticket, st));
+    return dev(evo::launch_fitness(timings, baseline, P, T, (uint32_t)reducer, stats, summary,
+                                   c->d_base_median, c->d_fit_ticket, st));
 }
 
 int evo_select_elite(evo_check_t *c, const evo_stats *stats, uint32_t P, uint32_t k, void *stream,

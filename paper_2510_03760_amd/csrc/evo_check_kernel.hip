@@ -26,6 +26,8 @@
 // sums differ only in summation order (fp32 over 8 non-negative terms in a tree,
 // then fp64), which stays far inside the 1e-6 relative budget of evo_stats.
 
+#include <type_traits>
+
 #include "evo_internal.h"
 #include "evo_rcp.h"
 
@@ -34,6 +36,8 @@ namespace {
 
 constexpr float kInf = __builtin_huge_valf();
 constexpr float kFltMin = 1.17549435e-38f;
+constexpr double kInfD = __builtin_huge_val();
+constexpr double kDblMin = 2.2250738585072014e-308;
 constexpr int kDepth = EVO_DEPTH;
 constexpr uint32_t kRotate = EVO_ROTATE;   // slot rotation per step (odd)
 
@@ -51,6 +55,17 @@ template <> struct Tile<EVO_BF16> {
     using elem_t = uint16_t;
 };
 template <> struct Tile<EVO_F16> : Tile<EVO_BF16> {};
+template <> struct Tile<EVO_I32> : Tile<EVO_F32> {};
+template <> struct Tile<EVO_F64> {
+    static constexpr int kVec = 2;
+    static constexpr int kNV = EVO_NV_F32;
+    static constexpr int kE = kVec * kNV;
+    using elem_t = double;
+};
+template <> struct Tile<EVO_I64> : Tile<EVO_F64> {};
+
+template <uint32_t DT> constexpr bool kIsInt = DT == EVO_I32 || DT == EVO_I64;
+template <uint32_t DT> constexpr bool kIsWide = DT == EVO_F64 || kIsInt<DT>;   // see fast_tiles_wide
 
 // IEEE binary16 -> binary32 (v_cvt_f32_f16: exact, subnormals included).
 __device__ __forceinline__ float half_bits_to_f32(uint16_t h) {
@@ -168,13 +183,38 @@ __device__ __forceinline__ double last_lane_f64(double v) {
     STEP(kRowBcast15, 0xa);              \
     STEP(kRowBcast31, 0xc)
 
+// Wavefront totals of one exact-path tile into the wavefront's LDS record of the candidate.
+__device__ __forceinline__ void exact_commit(ExactAcc *out, int lane, float max_abs, float max_rel,
+                                             double sum_abs, double sum_rel, uint32_t n_mismatch,
+                                             uint32_t n_excluded, uint32_t flags) {
+    uint32_t ma_bits = __builtin_bit_cast(uint32_t, max_abs), mr_bits = __builtin_bit_cast(uint32_t, max_rel);
+#define EVO_STEP(CTRL_, MASK_)                            \
+    reduce_step<CTRL_, MASK_>(ma_bits, sum_abs);          \
+    reduce_step<CTRL_, MASK_>(mr_bits, sum_rel)
+    EVO_WAVE_REDUCE(EVO_STEP);
+#undef EVO_STEP
+    max_abs = last_lane_f32(ma_bits);
+    max_rel = last_lane_f32(mr_bits);
+    sum_abs = last_lane_f64(sum_abs);
+    sum_rel = last_lane_f64(sum_rel);
+    if (lane == 0) {
+        out->sum_abs += sum_abs;
+        out->sum_rel += sum_rel;
+        out->max_abs = __builtin_fmaxf(out->max_abs, max_abs);
+        out->max_rel = __builtin_fmaxf(out->max_rel, max_rel);
+        out->n_mismatch += n_mismatch;
+        out->n_excluded += n_excluded;
+        out->flags |= flags;
+    }
+}
+
 // Exact path: the rule of evo.h one element per lane at a time.  Handles elements
 // beyond n (ignored), any alignment and every special value.  Results are reduced
 // over the wavefront and added to the wavefront's LDS record of the candidate.
 template <uint32_t DT>
-__device__ __forceinline__ void exact_tile(const void *ref, const void *cand, uint64_t n,
-                                           uint64_t tile_base, int lane, float atol,
-                                           float rtol, ExactAcc *out) {
+__device__ __forceinline__ void exact_tile_narrow(const void *ref, const void *cand, uint64_t n,
+                                                  uint64_t tile_base, int lane, float atol,
+                                                  float rtol, ExactAcc *out) {
     constexpr int kE = Tile<DT>::kE;
     float max_abs = 0.0f, max_rel = 0.0f;
     double sum_abs = 0.0, sum_rel = 0.0;
@@ -229,24 +269,114 @@ __device__ __forceinline__ void exact_tile(const void *ref, const void *cand, ui
             }
         }
     }
-    uint32_t ma_bits = __builtin_bit_cast(uint32_t, max_abs), mr_bits = __builtin_bit_cast(uint32_t, max_rel);
-#define EVO_STEP(CTRL_, MASK_)                            \
-    reduce_step<CTRL_, MASK_>(ma_bits, sum_abs);          \
-    reduce_step<CTRL_, MASK_>(mr_bits, sum_rel)
-    EVO_WAVE_REDUCE(EVO_STEP);
-#undef EVO_STEP
-    max_abs = last_lane_f32(ma_bits);
-    max_rel = last_lane_f32(mr_bits);
-    sum_abs = last_lane_f64(sum_abs);
-    sum_rel = last_lane_f64(sum_rel);
-    if (lane == 0) {
-        out->sum_abs += sum_abs;
-        out->sum_rel += sum_rel;
-        out->max_abs = __builtin_fmaxf(out->max_abs, max_abs);
-        out->max_rel = __builtin_fmaxf(out->max_rel, max_rel);
-        out->n_mismatch += n_mismatch;
-        out->n_excluded += n_excluded;
-        out->flags |= flags;
+    exact_commit(out, lane, max_abs, max_rel, sum_abs, sum_rel, n_mismatch, n_excluded, flags);
+}
+
+// Exact path, binary64 tensors: the same rule with every operation in binary64; the
+// maxima are rounded to binary32 when they leave the lane (rounding is monotone).
+__device__ __forceinline__ void exact_tile_f64(const void *ref, const void *cand, uint64_t n,
+                                               uint64_t tile_base, int lane, float atol,
+                                               float rtol, ExactAcc *out) {
+    constexpr int kE = Tile<EVO_F64>::kE;
+    const double atol_d = (double)atol, rtol_d = (double)rtol;
+    double max_abs = 0.0, max_rel = 0.0, sum_abs = 0.0, sum_rel = 0.0;
+    uint32_t n_mismatch = 0, n_excluded = 0, flags = 0;
+    double rv[kE], cv[kE];
+#pragma unroll
+    for (int k = 0; k < kE; ++k) {
+        const uint64_t idx = tile_base + (uint64_t)(k * kLanes + lane);
+        rv[k] = 0.0;
+        cv[k] = 0.0;
+        if (idx < n) {
+            rv[k] = static_cast<const double *>(ref)[idx];
+            cv[k] = static_cast<const double *>(cand)[idx];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kE; ++k) {
+        const uint64_t idx = tile_base + (uint64_t)(k * kLanes + lane);
+        const bool inb = idx < n;
+        const double r = rv[k], c = cv[k];
+        const double ar = __builtin_fabs(r);
+        const double ac = __builtin_fabs(c);
+        const double scaled = rtol_d * ar;
+        const double tol = atol_d + scaled;
+        const bool r_nan = r != r, c_nan = c != c;
+        const bool r_inf = ar == kInfD, c_inf = ac == kInfD;
+        const bool both = !r_nan && !c_nan && !r_inf && !c_inf;
+        const double d = __builtin_fabs(c - r);
+        const bool match = (c == r) || (both && d <= tol);
+        n_mismatch += popc64(ballot(inb && !match));
+        n_excluded += popc64(ballot(inb && !both));
+        if (ballot(c_nan)) flags |= EVO_F_CAND_NAN;
+        if (ballot(c_inf)) flags |= EVO_F_CAND_INF;
+        if (ballot(r_nan)) flags |= EVO_F_REF_NAN;
+        if (ballot(r_inf)) flags |= EVO_F_REF_INF;
+        if (ballot(c_nan != r_nan)) flags |= EVO_F_NAN_SITE_DIFF;
+        if (ballot((c_inf || r_inf) && !c_nan && !r_nan && c != r)) flags |= EVO_F_INF_DIFF;
+        if (inb && both) {
+            double inv = 0.0;
+            if (ar >= kDblMin) inv = 1.0 / ar;
+            const double q = d * inv;
+            max_abs = d > max_abs ? d : max_abs;
+            max_rel = q > max_rel ? q : max_rel;
+            sum_abs += d;
+            sum_rel += q;
+        }
+    }
+    exact_commit(out, lane, (float)max_abs, (float)max_rel, sum_abs, sum_rel, n_mismatch, n_excluded,
+                 flags);
+}
+
+// |c - r| of two signed integers as an exact unsigned integer.
+__device__ __forceinline__ uint32_t abs_diff(int32_t c, int32_t r) {
+    return c > r ? (uint32_t)c - (uint32_t)r : (uint32_t)r - (uint32_t)c;
+}
+__device__ __forceinline__ uint64_t abs_diff(int64_t c, int64_t r) {
+    return c > r ? (uint64_t)c - (uint64_t)r : (uint64_t)r - (uint64_t)c;
+}
+
+// Exact path, integer tensors: equality; |c - r| exact, its maximum rounded to binary32
+// when it leaves the lane, its sum in binary64.
+template <uint32_t DT>
+__device__ __forceinline__ void exact_tile_int(const void *ref, const void *cand, uint64_t n,
+                                               uint64_t tile_base, int lane, ExactAcc *out) {
+    using elem_t = typename std::conditional<DT == EVO_I32, int32_t, int64_t>::type;
+    constexpr int kE = Tile<DT>::kE;
+    uint64_t max_d = 0;
+    double sum_abs = 0.0;
+    uint32_t n_mismatch = 0;
+    elem_t rv[kE], cv[kE];
+#pragma unroll
+    for (int k = 0; k < kE; ++k) {
+        const uint64_t idx = tile_base + (uint64_t)(k * kLanes + lane);
+        rv[k] = 0;
+        cv[k] = 0;
+        if (idx < n) {
+            rv[k] = static_cast<const elem_t *>(ref)[idx];
+            cv[k] = static_cast<const elem_t *>(cand)[idx];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kE; ++k) {
+        const uint64_t d = abs_diff(cv[k], rv[k]);   // 0 beyond n
+        n_mismatch += popc64(ballot(d != 0));
+        max_d = d > max_d ? d : max_d;
+        sum_abs += (double)d;
+    }
+    exact_commit(out, lane, (float)max_d, 0.0f, sum_abs, 0.0, n_mismatch, 0u, 0u);
+}
+
+template <uint32_t DT>
+__device__ __forceinline__ void exact_tile(const void *ref, const void *cand, uint64_t n,
+                                           uint64_t tile_base, int lane, float atol,
+                                           float rtol, ExactAcc *out) {
+    if constexpr (kIsInt<DT>) {
+        exact_tile_int<DT>(ref, cand, n, tile_base, lane, out);
+    } else if constexpr (DT == EVO_F64) {
+        exact_tile_f64(ref, cand, n, tile_base, lane, atol, rtol, out);
+    } else {
+        exact_tile_narrow<DT>(ref, cand, n, tile_base, lane, atol, rtol, out);
     }
 }
 
@@ -502,6 +632,242 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_p
     return any_redo;
 }
 
+// Pairwise sum of N binary64 values (of their magnitudes when ABS), N a power of two.
+template <int N, bool ABS>
+__device__ __forceinline__ double tree_sum_f64(const double *v) {
+    if constexpr (N == 1) {
+        return ABS ? __builtin_fabs(v[0]) : v[0];
+    } else {
+        return tree_sum_f64<N / 2, ABS>(v) + tree_sum_f64<N / 2, ABS>(v + N / 2);
+    }
+}
+
+__device__ __forceinline__ uint64_t u64_of(uint32_t lo, uint32_t hi) { return ((uint64_t)hi << 32) | lo; }
+
+// Fast path for the 64-bit and integer element types (EVO_F64, EVO_I32, EVO_I64): the
+// load pipeline of fast_tiles with the arithmetic of those types.  Kept apart from
+// fast_tiles so that the register allocation of the binary32 loop is not touched.
+//   EVO_F64  as fast_tiles with every operation in binary64 (correctly rounded division
+//            for the reciprocal); a tile's maxima are rounded to binary32 when they are
+//            folded into the running ones.
+//   integers |c - r| as an exact unsigned integer; running maximum as an integer (kept in
+//            the two 32-bit words of the accumulator's maxima), sum of the exactly
+//            converted differences in binary64; nothing is ever left to the exact path.
+template <uint32_t DT, int NC, bool REF_STREAM>
+__device__ __forceinline__ uint32_t fast_tiles_wide(const char *rptr, uint64_t cand_ptr_of_lane,
+                                                    const TileWalk walk, uint64_t t_fend,
+                                                    float atol, float rtol, int lane,
+                                                    bool second_round, uint16_t *redo,
+                                                    Partial *wpart) {
+    using TL = Tile<DT>;
+    constexpr bool kInt = kIsInt<DT>;
+    constexpr int kE = TL::kE;
+    constexpr int kNV = TL::kNV;
+    constexpr uint64_t kTileBytes = (uint64_t)tile_elems(DT) * elem_bytes(DT);
+    constexpr int D = NC < kDepth ? NC : kDepth;
+    const uint32_t lane_off = (uint32_t)lane * 16u;
+    const double atol_d = (double)atol, rtol_d = (double)rtol;
+
+    Acc acc[NC];
+    uint32_t n_mismatch[NC];
+    const char *cptr[NC];
+#pragma unroll
+    for (int g = 0; g < NC; ++g) {
+        acc[g] = Acc{0.0f, 0.0f, 0.0, 0.0};   // integers: the two maxima hold one 64-bit integer, 0
+        n_mismatch[g] = 0;
+        cptr[g] = lane_ptr(cand_ptr_of_lane, g);
+    }
+    uint32_t any_redo = 0;
+
+    const uint32_t k_end = walk.steps_below(t_fend);
+    if (k_end > 0) {
+        u32x4 ref_raw[kNV];
+        u32x4 buf[D][kNV];
+        {
+            const uint64_t off = walk.at(0) * kTileBytes;
+#pragma unroll
+            for (int j = 0; j < kNV; ++j) ref_raw[j] = load16<REF_STREAM>(rptr + off + j * 1024, lane_off);
+#pragma unroll
+            for (int g = 0; g < D; ++g)
+#pragma unroll
+                for (int j = 0; j < kNV; ++j) buf[g][j] = load16<true>(cptr[g] + off + j * 1024, lane_off);
+        }
+        uint64_t t = walk.at(0);
+        for (uint32_t slot = 0; slot < k_end; ++slot) {
+            if (second_round) {   // issue priority, as in fast_tiles
+                if (slot & 2u) __builtin_amdgcn_s_setprio(1);
+                else __builtin_amdgcn_s_setprio(0);
+            }
+            const uint64_t off = t * kTileBytes;
+            const uint64_t t_next = (slot + 1 < k_end) ? walk.at(slot + 1) : t;
+            const uint64_t off_next = t_next * kTileBytes;
+
+            // this tile's reference elements, then the request for the next tile's
+            u32x4 rw[kNV];
+#pragma unroll
+            for (int j = 0; j < kNV; ++j) rw[j] = ref_raw[j];
+#pragma unroll
+            for (int j = 0; j < kNV; ++j) ref_raw[j] = load16<REF_STREAM>(rptr + off_next + j * 1024, lane_off);
+            double r[kInt ? 1 : kE], inv[kInt ? 1 : kE];
+            if constexpr (!kInt) {
+#pragma unroll
+                for (int j = 0; j < kNV; ++j) {
+                    r[2 * j] = __builtin_bit_cast(double, u64_of(rw[j].x, rw[j].y));
+                    r[2 * j + 1] = __builtin_bit_cast(double, u64_of(rw[j].z, rw[j].w));
+                }
+#pragma unroll
+                for (int e = 0; e < kE; ++e) {
+                    const double ar = __builtin_fabs(r[e]);
+                    inv[e] = ar >= kDblMin ? 1.0 / ar : 0.0;
+                }
+            }
+
+            uint32_t redo_mask = 0;
+#pragma unroll
+            for (int g = 0; g < NC; ++g) {
+                u32x4 cw[kNV];
+#pragma unroll
+                for (int j = 0; j < kNV; ++j) cw[j] = buf[g % D][j];
+                // refill the slot: candidate g+D of this tile, or g+D-NC of the next
+#pragma unroll
+                for (int j = 0; j < kNV; ++j)
+                    buf[g % D][j] = load16<true>(cptr[(g + D) % NC] + (g + D < NC ? off : off_next) + j * 1024,
+                                           lane_off);
+                if constexpr (DT == EVO_F64) {
+                    double d[kE], q[kE];
+#pragma unroll
+                    for (int j = 0; j < kNV; ++j) {
+                        d[2 * j] = __builtin_bit_cast(double, u64_of(cw[j].x, cw[j].y)) - r[2 * j];
+                        d[2 * j + 1] = __builtin_bit_cast(double, u64_of(cw[j].z, cw[j].w)) - r[2 * j + 1];
+                    }
+#pragma unroll
+                    for (int e = 0; e < kE; ++e) q[e] = __builtin_fabs(d[e]) * inv[e];
+                    const double sa = tree_sum_f64<kE, true>(d);
+                    const double sr = tree_sum_f64<kE, false>(q);
+                    const double chk = sa + sr;
+                    double t_abs = __builtin_fabs(d[0]), t_rel = q[0];
+#pragma unroll
+                    for (int e = 1; e < kE; ++e) {
+                        t_abs = __builtin_fmax(t_abs, __builtin_fabs(d[e]));
+                        t_rel = __builtin_fmax(t_rel, q[e]);
+                    }
+                    uint32_t mism = 0;
+                    if (ballot(!(t_abs <= atol_d)) != 0) {   // see fast_tiles
+#pragma unroll
+                        for (int e = 0; e < kE; ++e) {
+                            const double scaled = rtol_d * __builtin_fabs(r[e]);
+                            const double tol = atol_d + scaled;
+                            mism += popc64(ballot(!(__builtin_fabs(d[e]) <= tol)));
+                        }
+                    }
+                    if (ballot(!(chk < kInfD)) == 0) {
+                        const float ta = (float)t_abs, tr = (float)t_rel;   // +Inf beyond binary32
+                        acc[g].max_abs = max3(acc[g].max_abs, ta, ta);
+                        acc[g].max_rel = max3(acc[g].max_rel, tr, tr);
+                        acc[g].sum_abs += sa;
+                        acc[g].sum_rel += sr;
+                        n_mismatch[g] += mism;
+                    } else {
+                        redo_mask |= 1u << g;
+                    }
+                } else if constexpr (DT == EVO_I32) {
+                    const uint32_t rr[kE] = {rw[0].x, rw[0].y, rw[0].z, rw[0].w, rw[1].x, rw[1].y, rw[1].z, rw[1].w};
+                    const uint32_t cc[kE] = {cw[0].x, cw[0].y, cw[0].z, cw[0].w, cw[1].x, cw[1].y, cw[1].z, cw[1].w};
+                    static_assert(kNV == 2, "element lists above");
+                    uint32_t du[kE];
+                    uint32_t t_max = 0;
+                    double sa = 0.0;
+#pragma unroll
+                    for (int e = 0; e < kE; ++e) {
+                        du[e] = abs_diff((int32_t)cc[e], (int32_t)rr[e]);
+                        t_max = du[e] > t_max ? du[e] : t_max;
+                        sa += (double)du[e];
+                    }
+                    uint32_t mism = 0;
+                    if (ballot(t_max != 0) != 0) {
+#pragma unroll
+                        for (int e = 0; e < kE; ++e) mism += popc64(ballot(du[e] != 0));
+                    }
+                    const uint32_t run = __builtin_bit_cast(uint32_t, acc[g].max_abs);
+                    acc[g].max_abs = __builtin_bit_cast(float, t_max > run ? t_max : run);
+                    acc[g].sum_abs += sa;
+                    n_mismatch[g] += mism;
+                } else {
+                    static_assert(kNV == 2 && kE == 4, "element lists below");
+                    const uint64_t rr[kE] = {u64_of(rw[0].x, rw[0].y), u64_of(rw[0].z, rw[0].w),
+                                             u64_of(rw[1].x, rw[1].y), u64_of(rw[1].z, rw[1].w)};
+                    const uint64_t cc[kE] = {u64_of(cw[0].x, cw[0].y), u64_of(cw[0].z, cw[0].w),
+                                             u64_of(cw[1].x, cw[1].y), u64_of(cw[1].z, cw[1].w)};
+                    uint64_t du[kE];
+                    uint64_t t_max = 0;
+                    double sa = 0.0;
+#pragma unroll
+                    for (int e = 0; e < kE; ++e) {
+                        du[e] = abs_diff((int64_t)cc[e], (int64_t)rr[e]);
+                        t_max = du[e] > t_max ? du[e] : t_max;
+                        sa += (double)du[e];
+                    }
+                    uint32_t mism = 0;
+                    if (ballot(t_max != 0) != 0) {
+#pragma unroll
+                        for (int e = 0; e < kE; ++e) mism += popc64(ballot(du[e] != 0));
+                    }
+                    const uint64_t run = u64_of(__builtin_bit_cast(uint32_t, acc[g].max_abs),
+                                                __builtin_bit_cast(uint32_t, acc[g].max_rel));
+                    const uint64_t top = t_max > run ? t_max : run;
+                    acc[g].max_abs = __builtin_bit_cast(float, (uint32_t)top);
+                    acc[g].max_rel = __builtin_bit_cast(float, (uint32_t)(top >> 32));
+                    acc[g].sum_abs += sa;
+                    n_mismatch[g] += mism;
+                    // 64-bit integer temporaries are many: keep the candidates' instruction
+                    // streams apart, or their overlap pushes the kernel into register spills
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            if (lane == 0) redo[slot] = (uint16_t)redo_mask;
+            any_redo |= redo_mask;
+            t = t_next;
+        }
+    }
+    __builtin_amdgcn_s_setprio(0);
+
+    // Lanes -> wavefront, as in fast_tiles.  Integer maxima become binary32 values first
+    // (rounded to nearest even: monotone, so the order of rounding and maximum is free).
+    uint32_t ma_bits[NC], mr_bits[NC];
+#pragma unroll
+    for (int g = 0; g < NC; ++g) {
+        ma_bits[g] = __builtin_bit_cast(uint32_t, acc[g].max_abs);
+        mr_bits[g] = __builtin_bit_cast(uint32_t, acc[g].max_rel);
+        if constexpr (DT == EVO_I32) {
+            ma_bits[g] = __builtin_bit_cast(uint32_t, (float)ma_bits[g]);
+        } else if constexpr (DT == EVO_I64) {
+            ma_bits[g] = __builtin_bit_cast(uint32_t, (float)u64_of(ma_bits[g], mr_bits[g]));
+            mr_bits[g] = 0;
+        }
+    }
+#define EVO_STEP(CTRL_, MASK_)                                          \
+    _Pragma("unroll") for (int g = 0; g < NC; ++g) {                    \
+        reduce_step<CTRL_, MASK_>(ma_bits[g], acc[g].sum_abs);          \
+        reduce_step<CTRL_, MASK_>(mr_bits[g], acc[g].sum_rel);          \
+    }
+    EVO_WAVE_REDUCE(EVO_STEP);
+#undef EVO_STEP
+#pragma unroll
+    for (int g = 0; g < NC; ++g) {
+        Partial p;
+        p.n_mismatch = n_mismatch[g];
+        p.n_excluded = 0;
+        p.sum_abs = last_lane_f64(acc[g].sum_abs);
+        p.sum_rel = last_lane_f64(acc[g].sum_rel);
+        p.max_abs = last_lane_f32(ma_bits[g]);
+        p.max_rel = last_lane_f32(mr_bits[g]);
+        p.flags = 0;
+        p.pad = 0;
+        if (lane == 0) wpart[g] = p;
+    }
+    return any_redo;
+}
+
 // One job: a chunk of tiles of one segment for up to kWaves candidate groups.
 template <uint32_t DT>
 __device__ __forceinline__ void run_job(const SegDesc &sd, const uint64_t *ptr_table, uint32_t job_local,
@@ -550,11 +916,19 @@ __device__ __forceinline__ void run_job(const SegDesc &sd, const uint64_t *ptr_t
         Partial *wp = wave_part[wave];
         // the reference tile is shared by the workgroup's wavefronts iff gpw > 1
 #define EVO_FAST(NC_)                                                                          \
-    any_redo = (gpw == 1)                                                                      \
-        ? fast_tiles<DT, NC_, true>(rptr, cand_ptr_of_lane, walk, n_full, atol, rtol, lane,      \
-                                    second_round, rd, wp)                                       \
-        : fast_tiles<DT, NC_, false>(rptr, cand_ptr_of_lane, walk, n_full, atol, rtol, lane,     \
-                                     second_round, rd, wp)
+    if constexpr (kIsWide<DT>) {                                                               \
+        any_redo = (gpw == 1)                                                                  \
+            ? fast_tiles_wide<DT, NC_, true>(rptr, cand_ptr_of_lane, walk, n_full, atol, rtol, lane, \
+                                             second_round, rd, wp)                              \
+            : fast_tiles_wide<DT, NC_, false>(rptr, cand_ptr_of_lane, walk, n_full, atol, rtol, lane, \
+                                              second_round, rd, wp);                            \
+    } else {                                                                                   \
+        any_redo = (gpw == 1)                                                                  \
+            ? fast_tiles<DT, NC_, true>(rptr, cand_ptr_of_lane, walk, n_full, atol, rtol, lane,  \
+                                        second_round, rd, wp)                                   \
+            : fast_tiles<DT, NC_, false>(rptr, cand_ptr_of_lane, walk, n_full, atol, rtol, lane, \
+                                         second_round, rd, wp);                                 \
+    }
         switch (nc) {
 #if EVO_KG > 8
             case 16: EVO_FAST(16); break;
@@ -830,6 +1204,21 @@ __device__ __forceinline__ void check_body(const SegDesc *descs, const uint64_t 
             run_job<EVO_F32>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
                              wave_part, redo);
     }
+    if constexpr ((DTS & (1u << EVO_F64)) != 0) {
+        if (sd.dtype == EVO_F64 || DTS == (1u << EVO_F64))
+            run_job<EVO_F64>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
+                             wave_part, redo);
+    }
+    if constexpr ((DTS & (1u << EVO_I32)) != 0) {
+        if (sd.dtype == EVO_I32 || DTS == (1u << EVO_I32))
+            run_job<EVO_I32>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
+                             wave_part, redo);
+    }
+    if constexpr ((DTS & (1u << EVO_I64)) != 0) {
+        if (sd.dtype == EVO_I64 || DTS == (1u << EVO_I64))
+            run_job<EVO_I64>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
+                             wave_part, redo);
+    }
 
     // Two tickets: the bundle of kFold chunks this job belongs to, then the segment (see
     // fold_bundle).  Second-level rows and tickets follow the first-level ones in the same
@@ -914,7 +1303,8 @@ evo_check_kernel_inline(const InlineTable /*read via the segment pointer*/, uint
     check_body<DTS>(tab->descs, tab->ptrs, S, atol, rtol, n_first, partials, tickets, stats);
 }
 
-constexpr uint32_t kAllTypes = (1u << EVO_F32) | (1u << EVO_BF16) | (1u << EVO_F16);
+constexpr uint32_t kAllTypes = (1u << EVO_F32) | (1u << EVO_BF16) | (1u << EVO_F16) |
+                               (1u << EVO_F64) | (1u << EVO_I32) | (1u << EVO_I64);
 
 }  // namespace
 
@@ -928,6 +1318,9 @@ hipError_t launch_check(uint32_t dtype_set, const SegDesc *d_descs, const uint64
         case 1u << EVO_F32: EVO_LAUNCH(1u << EVO_F32); break;
         case 1u << EVO_BF16: EVO_LAUNCH(1u << EVO_BF16); break;
         case 1u << EVO_F16: EVO_LAUNCH(1u << EVO_F16); break;
+        case 1u << EVO_F64: EVO_LAUNCH(1u << EVO_F64); break;
+        case 1u << EVO_I32: EVO_LAUNCH(1u << EVO_I32); break;
+        case 1u << EVO_I64: EVO_LAUNCH(1u << EVO_I64); break;
         default: EVO_LAUNCH(kAllTypes); break;
     }
 #undef EVO_LAUNCH
@@ -945,6 +1338,9 @@ hipError_t launch_check_inline(uint32_t dtype_set, const InlineTable &tab, uint3
         case 1u << EVO_F32: EVO_LAUNCH(1u << EVO_F32); break;
         case 1u << EVO_BF16: EVO_LAUNCH(1u << EVO_BF16); break;
         case 1u << EVO_F16: EVO_LAUNCH(1u << EVO_F16); break;
+        case 1u << EVO_F64: EVO_LAUNCH(1u << EVO_F64); break;
+        case 1u << EVO_I32: EVO_LAUNCH(1u << EVO_I32); break;
+        case 1u << EVO_I64: EVO_LAUNCH(1u << EVO_I64); break;
         default: EVO_LAUNCH(kAllTypes); break;
     }
 #undef EVO_LAUNCH

@@ -40,7 +40,7 @@ __device__ __forceinline__ bool better(float fa, uint32_t ia, float fb, uint32_t
 
 __global__ void __launch_bounds__(kThreads)
 evo_fitness_kernel(const float *__restrict__ timings, const float *__restrict__ baseline,
-                   uint32_t P, uint32_t T, evo_stats *__restrict__ stats,
+                   uint32_t P, uint32_t T, uint32_t reducer, evo_stats *__restrict__ stats,
                    evo_pop_summary *__restrict__ summary, float *__restrict__ base_median,
                    uint32_t *__restrict__ ticket) {
     __shared__ float sorted[EVO_FITNESS_MAX_T];
@@ -118,7 +118,8 @@ evo_fitness_kernel(const float *__restrict__ timings, const float *__restrict__ 
             stats[row].median_ms = median;
             stats[row].mean_ms = mean;
         } else {
-            *base_median = median;
+            base_median[0] = median;
+            base_median[1] = mean;
         }
         // the release of the ticket publishes the two stores above
         const uint32_t prev = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL,
@@ -129,12 +130,16 @@ evo_fitness_kernel(const float *__restrict__ timings, const float *__restrict__ 
     if (!is_last) return;   // thread 0 acquired with the last ticket; the barrier hands that on
 
     // The last of the P+1 workgroups: speedups, fitness, population figures.
-    const float bm = __hip_atomic_load(base_median, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // Numerator and denominator of the speedup: medians, or means when the caller asked for
+    // the "average over the runs" of Sec. 4.3.  (A row is unusable for both or for neither.)
+    const bool by_mean = reducer == EVO_REDUCE_MEAN;
+    const float bm = __hip_atomic_load(base_median + (by_mean ? 1 : 0), __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
     const bool base_ok = bm == bm;
     Best mine{0.0f, P, 0u};
     for (uint32_t p = tid; p < P; p += kThreads) {
-        const float med = __hip_atomic_load(&stats[p].median_ms, __ATOMIC_RELAXED,
-                                            __HIP_MEMORY_SCOPE_AGENT);
+        const float med = __hip_atomic_load(by_mean ? &stats[p].mean_ms : &stats[p].median_ms,
+                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const uint32_t valid = stats[p].valid;
         float speedup = 0.0f;
         if (base_ok && med == med) speedup = bm / med;
@@ -179,10 +184,10 @@ evo_fitness_kernel(const float *__restrict__ timings, const float *__restrict__ 
 }  // namespace
 
 hipError_t launch_fitness(const float *timings, const float *baseline, uint32_t P, uint32_t T,
-                          evo_stats *stats, evo_pop_summary *summary, float *base_median,
-                          uint32_t *ticket, hipStream_t stream) {
+                          uint32_t reducer, evo_stats *stats, evo_pop_summary *summary,
+                          float *base_median, uint32_t *ticket, hipStream_t stream) {
     hipLaunchKernelGGL(evo_fitness_kernel, dim3(P + 1), dim3(kThreads), 0, stream, timings,
-                       baseline, P, T, stats, summary, base_median, ticket);
+                       baseline, P, T, reducer, stats, summary, base_median, ticket);
     return hipGetLastError();
 }
 

@@ -48,9 +48,15 @@ constexpr int kG = EVO_KG;
 constexpr int kRowsPerJob = kWaves * kG;   // partial rows one job can produce
 constexpr uint32_t kMaxTilesPerWave = 2048; // per job: bounds the LDS redo list
 
-// Elements one wavefront consumes per tile and per tensor (16 bytes per lane and vector).
+// Bytes of one element, and elements one wavefront consumes per tile and per tensor (a tile
+// is EVO_NV_* 16-byte vectors per lane: 2 KiB of every tensor with the default of 2).
+__host__ __device__ constexpr uint32_t elem_bytes(uint32_t dtype) {
+    return (dtype == EVO_BF16 || dtype == EVO_F16) ? 2u
+         : (dtype == EVO_F64 || dtype == EVO_I64) ? 8u : 4u;
+}
 __host__ __device__ constexpr uint32_t tile_elems(uint32_t dtype) {
-    return dtype == EVO_F32 ? EVO_NV_F32 * 64 * 4 : EVO_NV_BF16 * 64 * 8;   // 16-bit types alike
+    return ((dtype == EVO_BF16 || dtype == EVO_F16) ? EVO_NV_BF16 : EVO_NV_F32) * 64u * 16u /
+           elem_bytes(dtype);
 }
 
 // A population of P candidates is cut into groups whose sizes are powers of two:
@@ -160,9 +166,10 @@ hipError_t launch_check_inline(uint32_t dtype_set, const InlineTable &tab, uint3
                                Partial *partials, uint32_t *tickets, evo_stats *stats,
                                hipStream_t stream);
 
+// base_median: two floats of device scratch (the baseline's median and mean).
 hipError_t launch_fitness(const float *timings, const float *baseline, uint32_t P, uint32_t T,
-                          evo_stats *stats, evo_pop_summary *summary, float *base_median,
-                          uint32_t *ticket, hipStream_t stream);
+                          uint32_t reducer, evo_stats *stats, evo_pop_summary *summary,
+                          float *base_median, uint32_t *ticket, hipStream_t stream);
 
 hipError_t launch_select(const evo_stats *stats, uint32_t P, uint32_t k, uint32_t *elite,
                          uint32_t *n_elite, hipStream_t stream);

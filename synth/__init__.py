@@ -39,7 +39,8 @@ class Segment:
 
     @property
     def dtype_name(self) -> str:
-        return {torch.bfloat16: "bf16", torch.float16: "f16"}.get(self.ref.dtype, "f32")
+        return {torch.bfloat16: "bf16", torch.float16: "f16", torch.float64: "f64",
+                torch.int32: "i32", torch.int64: "i64"}.get(self.ref.dtype, "f32")
 
     @property
     def n(self) -> int:
@@ -156,6 +157,47 @@ def dense_f32(device="cpu", side: int = 8192, P: int = 16, T: int = 100,
     t, b = _timings(device, cfg, P, T, "lognormal")
     seg = Segment(ref, cands, (side, side), corrupted, {"replaced": replaced})
     return Workload("C2-f32-%dx%d-P%d" % (side, side, P), [seg], 1e-2, 1e-2, t, b)
+
+
+def dense_typed(device="cpu", dtype=torch.float64, n: int = 1 << 25, P: int = 16, T: int = 100,
+                corrupt_frac: float = 1e-3) -> Workload:
+    """The dense recipe of config 2 for the other element types (config number 7).
+    binary64: ref ~N(0,1), cand = ref*(1 + N(0, sd 1e-4)), every fourth candidate with a
+    Bernoulli(corrupt_frac) set of elements replaced by U(-10, 10).  Integers (the index
+    output of an arg-reduction over 4096 positions): ref ~U{0..4095}, candidates equal to
+    it, every fourth one with a Bernoulli(corrupt_frac) set of elements redrawn."""
+    cfg = 7
+    is_int = dtype in (torch.int32, torch.int64)
+    if is_int:
+        ref = torch.randint(0, 4096, (n,), generator=_gen(device, cfg, 0), device=device, dtype=dtype)
+    else:
+        ref = torch.randn(n, generator=_gen(device, cfg, 0), device=device, dtype=dtype)
+    cands, corrupted = [], []
+    for p in range(P):
+        if is_int:
+            c = ref.clone()
+        else:
+            z = torch.randn(n, generator=_gen(device, cfg, 1 + p), device=device, dtype=dtype)
+            c = ref * (1.0 + 1e-4 * z)
+            del z
+        bad = (p % 4) == 3
+        if bad:
+            gs = _gen(device, cfg, 1000 + p)
+            mask = torch.rand(n, generator=gs, device=device) < corrupt_frac
+            if not bool(mask.any()):
+                mask[int(torch.randint(0, n, (1,), generator=gs, device=device))] = True
+            if is_int:
+                u = torch.randint(0, 4096, (n,), generator=gs, device=device, dtype=dtype)
+            else:
+                u = torch.rand(n, generator=gs, device=device, dtype=dtype) * 20.0 - 10.0
+            c = torch.where(mask, u, c)
+            del mask, u
+        cands.append(c.contiguous())
+        corrupted.append(bad)
+    t, b = _timings(device, cfg, P, T, "lognormal")
+    name = {torch.float64: "f64", torch.int32: "i32", torch.int64: "i64"}[dtype]
+    seg = Segment(ref, cands, (n,), corrupted)
+    return Workload("C7-%s-2^%d-P%d" % (name, n.bit_length() - 1, P), [seg], 1e-2, 1e-2, t, b)
 
 
 def softmax_bf16(device="cpu", B: int = 32, R: int = 128, C: int = 4096, P: int = 64,
@@ -328,7 +370,8 @@ def multi_case_f32(device="cpu", K: int = 5, side: int = 4096, P: int = 16, T: i
 
 
 def to_oracle_array(x: torch.Tensor):
-    """Host numpy view the CPU oracle accepts (float32, or uint16 bits for bf16)."""
+    """Host numpy view the CPU oracle accepts (uint16 bits for the 16-bit types, the
+    tensor's own element type otherwise)."""
     import numpy as np
     x = x.detach().cpu().contiguous()
     if x.dtype in (torch.bfloat16, torch.float16):

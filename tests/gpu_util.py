@@ -21,11 +21,13 @@ SUM_FIELDS = ("sum_abs_err", "sum_rel_err")
 
 
 def dtype_code(seg):
-    return {"bf16": evo.EVO_BF16, "f16": evo.EVO_F16}.get(seg.dtype_name, evo.EVO_F32)
+    return {"bf16": evo.EVO_BF16, "f16": evo.EVO_F16, "f64": evo.EVO_F64, "i32": evo.EVO_I32,
+            "i64": evo.EVO_I64}.get(seg.dtype_name, evo.EVO_F32)
 
 
 def oracle_dtype(seg):
-    return {"bf16": oracle.BF16, "f16": oracle.F16}.get(seg.dtype_name, oracle.F32)
+    return {"bf16": oracle.BF16, "f16": oracle.F16, "f64": oracle.F64, "i32": oracle.I32,
+            "i64": oracle.I64}.get(seg.dtype_name, oracle.F32)
 
 
 def oracle_rows(seg, atol, rtol, threads=16, chunk=1 << 24):

@@ -22,7 +22,7 @@ hipError_t launch_check(uint32_t, const SegDesc *, const uint64_t *, uint32_t, u
                         uint32_t, Partial *, uint32_t *, evo_stats *, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_check_inline(uint32_t, const InlineTable &, uint32_t, uint32_t, float, float, uint32_t,
                                Partial *, uint32_t *, evo_stats *, hipStream_t) { ++g_launches; return hipSuccess; }
-hipError_t launch_fitness(const float *, const float *, uint32_t, uint32_t, evo_stats *,
+hipError_t launch_fitness(const float *, const float *, uint32_t, uint32_t, uint32_t, evo_stats *,
                           evo_pop_summary *, float *, uint32_t *, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_select(const evo_stats *, uint32_t, uint32_t, uint32_t *, uint32_t *, hipStream_t) {
     ++g_launches;
@@ -99,7 +99,7 @@ static void partition_cases() {
             h.n = 1 + rng() % (1ull << lg);
             const uint32_t pk = (uint32_t)(rng() % 8);
             h.P = pk == 0 ? 1 + (uint32_t)(rng() % kMaxP) : 1 + (uint32_t)(rng() % 70);
-            h.dtype = (uint32_t)(rng() % 3);
+            h.dtype = (uint32_t)(rng() % 6);
             h.ref = nullptr;
             h.cand_ptrs = nullptr;
             h.row0 = row0;
@@ -142,7 +142,7 @@ static void group_cases() {
 static void validation_cases() {
     evo_check_t *c = nullptr;
     EXPECT(evo_check_create(nullptr, EVO_F32, 16, 0.f, 0.f) == EVO_ERR_NULL);
-    EXPECT(evo_check_create(&c, (evo_dtype)3, 16, 0.f, 0.f) == EVO_ERR_DTYPE && c == nullptr);
+    EXPECT(evo_check_create(&c, (evo_dtype)6, 16, 0.f, 0.f) == EVO_ERR_DTYPE && c == nullptr);
     EXPECT(evo_check_create(&c, EVO_F32, 0, 0.f, 0.f) == EVO_ERR_SIZE);
     EXPECT(evo_check_create(&c, EVO_F32, 16, -1.f, 0.f) == EVO_ERR_TOL);
     EXPECT(evo_check_create(&c, EVO_F32, 16, 0.f, __builtin_nanf("")) == EVO_ERR_TOL);
@@ -222,6 +222,17 @@ static void validation_cases() {
                        pop) == EVO_ERR_ALIGN);
     EXPECT(evo_fitness(c, tim, base, 3, 5, nullptr, reinterpret_cast<evo_stats *>(arena + 1028), pop) ==
            EVO_ERR_ALIGN);
+    EXPECT(evo_fitness_ex(c, tim, base, 3, 5, 2, nullptr, stats, pop) == EVO_ERR_SIZE);
+    EXPECT(evo_fitness_ex(nullptr, tim, base, 3, 5, EVO_REDUCE_MEAN, nullptr, stats, pop) == EVO_ERR_HANDLE);
+    EXPECT(evo_fitness_ex(c, tim, nullptr, 3, 5, EVO_REDUCE_MEAN, nullptr, stats, pop) == EVO_ERR_NULL);
+    {   // 8-byte element types need 8-byte aligned tensors
+        evo_check_t *c64 = nullptr;
+        EXPECT(evo_check_create(&c64, EVO_F64, 100, 0.f, 0.f) == EVO_OK);
+        const void *c4[1] = {arena + 20};
+        EXPECT(evo_check_batch(c64, ref, c4, 1, nullptr, stats) == EVO_ERR_ALIGN);
+        EXPECT(evo_check_batch(c64, arena + 4, cands, 1, nullptr, stats) == EVO_ERR_ALIGN);
+        EXPECT(evo_check_destroy(c64) == EVO_OK);
+    }
 
     uint32_t *elite = reinterpret_cast<uint32_t *>(arena + 3600);
     EXPECT(evo_select_elite(nullptr, stats, 3, 2, nullptr, elite, nullptr) == EVO_ERR_HANDLE);

@@ -29,7 +29,7 @@ def declared_functions():
 def test_header_declares_the_documented_entry_points():
     assert declared_functions() == ["evo_check_batch", "evo_check_cases", "evo_check_create",
                                     "evo_check_destroy", "evo_check_segmented", "evo_fitness",
-                                    "evo_select_elite", "evo_strerror"]
+                                    "evo_fitness_ex", "evo_select_elite", "evo_strerror"]
 
 
 def test_library_exports_every_declared_symbol(evo):
@@ -60,8 +60,10 @@ def _create(evo, *args):
 def test_create_validates(evo):
     assert evo.lib.evo_check_create(None, 0, 10, 0.0, 0.0) == -1
     assert _create(evo, 7, 10, 0.0, 0.0) == (-2, None)
-    rc, h16 = _create(evo, 2, 10, 0.0, 0.0)
-    assert rc == 0 and evo.lib.evo_check_destroy(h16) == 0
+    for code in range(6):                    # f32, bf16, f16, f64, i32, i64
+        rc, hx = _create(evo, code, 10, 0.0, 0.0)
+        assert rc == 0 and evo.lib.evo_check_destroy(hx) == 0
+    assert _create(evo, 6, 10, 0.0, 0.0) == (-2, None)
     assert _create(evo, 0, 0, 0.0, 0.0) == (-3, None)
     for atol, rtol in ((-1e-3, 0.0), (0.0, -1.0), (float("nan"), 0.0), (0.0, float("nan")),
                        (float("inf"), 0.0), (0.0, float("inf"))):
@@ -123,7 +125,7 @@ def test_check_segmented_validates_before_any_launch(evo):
     assert call([seg(cand=None)]) == -1
     assert call([seg(n=0)]) == -3
     assert call([seg(P=0)]) == -3
-    assert call([seg(dtype=5)]) == -2
+    assert call([seg(dtype=6)]) == -2
     assert call([seg(ref=66)]) == -5
     assert call([seg(row0=7)]) == -3                                   # rows 7,8 exceed n_rows
     assert call([seg(row0=0), seg(row0=1)]) == -3                      # overlapping rows
@@ -167,6 +169,12 @@ def test_fitness_validates_before_any_launch(evo):
     assert call(h, 64, 64, 4, 4097, None, 512, None) == -3
     assert call(h, 66, 64, 4, 10, None, 512, None) == -5
     assert call(h, 64, 64, 4, 10, None, 516, None) == -5
+    ex = evo.lib.evo_fitness_ex
+    assert ex(h, 64, 64, 4, 10, 2, None, 512, None) == -3      # unknown reducer
+    assert ex(h, 64, 64, 4, 10, -1, None, 512, None) == -3
+    assert ex(h, None, 64, 4, 10, 1, None, 512, None) == -1
+    assert ex(h, 64, 64, 4, 4097, 1, None, 512, None) == -3
+    assert ex(None, 64, 64, 4, 10, 1, None, 512, None) == -8
     assert evo.lib.evo_check_destroy(h) == 0
 
 
