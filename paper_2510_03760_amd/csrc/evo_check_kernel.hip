@@ -774,54 +774,59 @@ __device__ __forceinline__ uint32_t fast_tiles_wide(const char *rptr, uint64_t c
                     const uint32_t rr[kE] = {rw[0].x, rw[0].y, rw[0].z, rw[0].w, rw[1].x, rw[1].y, rw[1].z, rw[1].w};
                     const uint32_t cc[kE] = {cw[0].x, cw[0].y, cw[0].z, cw[0].w, cw[1].x, cw[1].y, cw[1].z, cw[1].w};
                     static_assert(kNV == 2, "element lists above");
-                    uint32_t du[kE];
-                    uint32_t t_max = 0;
-                    double sa = 0.0;
+                    // Integer outputs are mostly equal to the reference: a tile without a
+                    // single differing bit changes nothing and costs one XOR per element.
+                    uint32_t any_bits = 0;
 #pragma unroll
-                    for (int e = 0; e < kE; ++e) {
-                        du[e] = abs_diff((int32_t)cc[e], (int32_t)rr[e]);
-                        t_max = du[e] > t_max ? du[e] : t_max;
-                        sa += (double)du[e];
-                    }
-                    uint32_t mism = 0;
-                    if (ballot(t_max != 0) != 0) {
+                    for (int e = 0; e < kE; ++e) any_bits |= cc[e] ^ rr[e];
+                    if (ballot(any_bits != 0) != 0) {
+                        uint32_t du[kE];
+                        uint32_t t_max = 0;
+                        double sa = 0.0;
+#pragma unroll
+                        for (int e = 0; e < kE; ++e) {
+                            du[e] = abs_diff((int32_t)cc[e], (int32_t)rr[e]);
+                            t_max = du[e] > t_max ? du[e] : t_max;
+                            sa += (double)du[e];
+                        }
+                        uint32_t mism = 0;
 #pragma unroll
                         for (int e = 0; e < kE; ++e) mism += popc64(ballot(du[e] != 0));
+                        const uint32_t run = __builtin_bit_cast(uint32_t, acc[g].max_abs);
+                        acc[g].max_abs = __builtin_bit_cast(float, t_max > run ? t_max : run);
+                        acc[g].sum_abs += sa;
+                        n_mismatch[g] += mism;
                     }
-                    const uint32_t run = __builtin_bit_cast(uint32_t, acc[g].max_abs);
-                    acc[g].max_abs = __builtin_bit_cast(float, t_max > run ? t_max : run);
-                    acc[g].sum_abs += sa;
-                    n_mismatch[g] += mism;
                 } else {
                     static_assert(kNV == 2 && kE == 4, "element lists below");
                     const uint64_t rr[kE] = {u64_of(rw[0].x, rw[0].y), u64_of(rw[0].z, rw[0].w),
                                              u64_of(rw[1].x, rw[1].y), u64_of(rw[1].z, rw[1].w)};
                     const uint64_t cc[kE] = {u64_of(cw[0].x, cw[0].y), u64_of(cw[0].z, cw[0].w),
                                              u64_of(cw[1].x, cw[1].y), u64_of(cw[1].z, cw[1].w)};
-                    uint64_t du[kE];
-                    uint64_t t_max = 0;
-                    double sa = 0.0;
+                    uint64_t any_bits = 0;   // as for 32-bit integers
 #pragma unroll
-                    for (int e = 0; e < kE; ++e) {
-                        du[e] = abs_diff((int64_t)cc[e], (int64_t)rr[e]);
-                        t_max = du[e] > t_max ? du[e] : t_max;
-                        sa += (double)du[e];
-                    }
-                    uint32_t mism = 0;
-                    if (ballot(t_max != 0) != 0) {
+                    for (int e = 0; e < kE; ++e) any_bits |= cc[e] ^ rr[e];
+                    if (ballot(any_bits != 0) != 0) {
+                        uint64_t du[kE];
+                        uint64_t t_max = 0;
+                        double sa = 0.0;
+#pragma unroll
+                        for (int e = 0; e < kE; ++e) {
+                            du[e] = abs_diff((int64_t)cc[e], (int64_t)rr[e]);
+                            t_max = du[e] > t_max ? du[e] : t_max;
+                            sa += (double)du[e];
+                        }
+                        uint32_t mism = 0;
 #pragma unroll
                         for (int e = 0; e < kE; ++e) mism += popc64(ballot(du[e] != 0));
+                        const uint64_t run = u64_of(__builtin_bit_cast(uint32_t, acc[g].max_abs),
+                                                    __builtin_bit_cast(uint32_t, acc[g].max_rel));
+                        const uint64_t top = t_max > run ? t_max : run;
+                        acc[g].max_abs = __builtin_bit_cast(float, (uint32_t)top);
+                        acc[g].max_rel = __builtin_bit_cast(float, (uint32_t)(top >> 32));
+                        acc[g].sum_abs += sa;
+                        n_mismatch[g] += mism;
                     }
-                    const uint64_t run = u64_of(__builtin_bit_cast(uint32_t, acc[g].max_abs),
-                                                __builtin_bit_cast(uint32_t, acc[g].max_rel));
-                    const uint64_t top = t_max > run ? t_max : run;
-                    acc[g].max_abs = __builtin_bit_cast(float, (uint32_t)top);
-                    acc[g].max_rel = __builtin_bit_cast(float, (uint32_t)(top >> 32));
-                    acc[g].sum_abs += sa;
-                    n_mismatch[g] += mism;
-                    // 64-bit integer temporaries are many: keep the candidates' instruction
-                    // streams apart, or their overlap pushes the kernel into register spills
-                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
             if (lane == 0) redo[slot] = (uint16_t)redo_mask;
