@@ -253,6 +253,38 @@ EVO_API int evo_select_elite(evo_check_t *c, const evo_stats *stats, uint32_t P,
                              void *stream, uint32_t *elite, uint32_t *n_elite);
 
 /*
+ * Timing stage of the evaluator (Sec. 4.3: the execution time of a candidate is collected
+ * over 100 runs; the appendix on threats to validity names run-to-run noise): produces the
+ * P x T table of milliseconds that evo_fitness consumes.  For every candidate p the library
+ * calls launch[p](user[p], stream) `warmup` times untimed and then T times, each timed run
+ * bracketed by two device events on `stream`; launch[p] must enqueue exactly one run of the
+ * candidate on that stream and return (it must not synchronise the device).
+ *   opts->flush_cache  non-zero: before every timed run a 512 MiB scratch buffer is
+ *                      overwritten (outside the timed bracket), so that the run does not
+ *                      find the previous run's data in the last-level cache
+ *   timings            device, P*T binary32 milliseconds, row major, written in stream order
+ *   clock_ratio        host, P entries, or NULL: a fixed chain of dependent FMAs is timed
+ *                      before the first and after the last timed run of candidate p; entry
+ *                      p is after/before (1.0 = the shader clock did not change; a caller
+ *                      may discard rows far from 1)
+ * Unlike the other calls this one BLOCKS: it returns when every run has completed and the
+ * table has been copied.  It allocates events, pinned memory and (with flush_cache) the
+ * scratch buffer on first use.
+ * Errors: EVO_ERR_HANDLE, EVO_ERR_NULL (launch, any launch[p], timings, opts),
+ * EVO_ERR_SIZE (P == 0, T == 0, T > EVO_FITNESS_MAX_T, P > 65535, warmup > 1000000),
+ * EVO_ERR_ALIGN (timings), EVO_ERR_NOMEM, EVO_ERR_DEVICE.
+ */
+typedef void (*evo_launch_fn)(void *user, void *stream);
+typedef struct evo_timing_opts {
+    uint32_t warmup;      /* untimed runs per candidate before the timed ones          */
+    uint32_t flush_cache; /* 0 / 1                                                     */
+    uint32_t reserved[2]; /* set to 0                                                  */
+} evo_timing_opts;
+EVO_API int evo_time_candidates(evo_check_t *c, const evo_launch_fn *launch, void *const *user,
+                                uint32_t P, uint32_t T, const evo_timing_opts *opts,
+                                void *stream, float *timings, float *clock_ratio);
+
+/*
  * Destroys a context: waits for the device to go idle, frees the library's scratch
  * memory.  NULL, unknown and already destroyed handles are ignored
  * (evo_check_destroy returns EVO_ERR_HANDLE for them and does nothing else).

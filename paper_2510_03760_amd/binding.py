@@ -63,6 +63,14 @@ class EvoPopSummary(ctypes.Structure):
 
 
 # numpy views of the two records, for reading results copied back to the host
+LAUNCH_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)   # evo_launch_fn
+
+
+class EvoTimingOpts(ctypes.Structure):
+    _fields_ = [("warmup", ctypes.c_uint32), ("flush_cache", ctypes.c_uint32),
+                ("reserved", ctypes.c_uint32 * 2)]
+
+
 STATS_DTYPE = np.dtype([
     ("n_mismatch", "<u8"), ("n_finite", "<u8"), ("sum_abs_err", "<f8"), ("sum_rel_err", "<f8"),
     ("max_abs_err", "<f4"), ("max_rel_err", "<f4"), ("flags", "<u4"), ("valid", "<u4"),
@@ -89,11 +97,13 @@ def _load() -> ctypes.CDLL:
     h.evo_fitness.argtypes = [vp, vp, vp, u32, u32, vp, vp, vp]
     h.evo_fitness_ex.argtypes = [vp, vp, vp, u32, u32, ctypes.c_int, vp, vp, vp]
     h.evo_select_elite.argtypes = [vp, vp, u32, u32, vp, vp, vp]
+    h.evo_time_candidates.argtypes = [vp, ctypes.POINTER(LAUNCH_FN), ctypes.POINTER(vp), u32, u32,
+                                      ctypes.POINTER(EvoTimingOpts), vp, vp, ctypes.POINTER(f32)]
     h.evo_check_destroy.argtypes = [vp]
     h.evo_strerror.argtypes = [ctypes.c_int]
     h.evo_strerror.restype = ctypes.c_char_p
     for name in ("evo_check_create", "evo_check_batch", "evo_check_segmented", "evo_check_cases",
-                 "evo_fitness", "evo_fitness_ex", "evo_select_elite",
+                 "evo_fitness", "evo_fitness_ex", "evo_select_elite", "evo_time_candidates",
                  "evo_check_destroy"):
         getattr(h, name).restype = ctypes.c_int
     return h
@@ -193,6 +203,23 @@ def evo_fitness_ex(ctx: int, timings, baseline, P: int, T: int, reducer: int, st
         raise EvoError(rc, "evo_fitness_ex")
 
 
+def evo_time_candidates(ctx: int, launches, T: int, stream, timings, warmup: int = 3,
+                        flush_cache: bool = False, want_clock_ratio: bool = True):
+    """``launches``: one Python callable per candidate, called as f(stream_pointer); each must
+    enqueue one run of its candidate on that stream.  Returns the clock ratios (or None)."""
+    P = len(launches)
+    keep = [LAUNCH_FN(lambda user, st, f=f: f(st)) for f in launches]   # keep the thunks alive
+    fns = (LAUNCH_FN * P)(*keep)
+    opts = EvoTimingOpts(int(warmup), 1 if flush_cache else 0)
+    ratios = (ctypes.c_float * P)() if want_clock_ratio else None
+    rc = lib.evo_time_candidates(ctx, fns, None, P, int(T), ctypes.byref(opts), _stream(stream),
+                                 _ptr(timings), ratios)
+    del keep
+    if rc != 0:
+        raise EvoError(rc, "evo_time_candidates")
+    return list(ratios) if ratios is not None else None
+
+
 def evo_select_elite(ctx: int, stats, P: int, k: int, stream, elite, n_elite=None) -> None:
     rc = lib.evo_select_elite(ctx, _ptr(stats), int(P), int(k), _stream(stream), _ptr(elite),
                               _ptr(n_elite))
@@ -262,6 +289,12 @@ class Checker:
         else:
             evo_fitness_ex(self.ctx, timings, baseline, P, T, reducer, st, stats, summary)
 
+
+    def time_candidates(self, launches, T: int, timings: torch.Tensor, warmup: int = 3,
+                        flush_cache: bool = False, stream=None):
+        return evo_time_candidates(self.ctx, launches, T,
+                                   stream if stream is not None else torch.cuda.current_stream(),
+                                   timings, warmup, flush_cache)
 
     def select_elite(self, stats: torch.Tensor, P: int, k: int, elite: torch.Tensor,
                      n_elite: Optional[torch.Tensor] = None, stream=None) -> None:

@@ -11,7 +11,8 @@ CSRC = os.path.join(_PKG, "csrc")
 INCLUDE = os.path.join(_ROOT, "include")
 LIB_PATH = os.path.join(_PKG, "libevo.so")
 
-SOURCES = ["evo_api.hip", "evo_check_kernel.hip", "evo_fitness_kernel.hip", "evo_select_kernel.hip"]
+SOURCES = ["evo_api.hip", "evo_check_kernel.hip", "evo_fitness_kernel.hip", "evo_select_kernel.hip",
+           "evo_timing_kernel.hip"]
 
 # -ffp-contract=off: every binary32 operation of the element rule is rounded on its
 # own (no fused multiply-add), as the definition in evo.h requires.

@@ -22,6 +22,9 @@ constexpr uint32_t kJobsPerCu = EVO_JOBS_PER_CU;
 constexpr uint32_t kMinTilesPerWave = 4;
 constexpr uint32_t kMaxP = 65535;
 constexpr int kStageSlots = 8;
+constexpr size_t kFlushBytes = 512u << 20;      // twice the last-level cache of MI355X
+constexpr uint32_t kProbeIterations = 20000;    // about 35 us at 2.4 GHz
+constexpr int kProbeSpinUp = 100;
 
 struct StageSlot {
     void *host = nullptr;      // pinned
@@ -49,6 +52,12 @@ struct evo_check {
     uint32_t *d_fit_ticket = nullptr;
     StageSlot slots[kStageSlots];
     int next_slot = 0;
+    // timing stage (evo_time_candidates)
+    std::vector<hipEvent_t> time_events;   // start/stop pairs, reused from candidate to candidate
+    void *d_flush = nullptr;               // kFlushBytes of scratch
+    float *h_times = nullptr;              // pinned staging of the timing table
+    size_t h_times_count = 0;
+    float *d_probe_sink = nullptr;
 };
 
 namespace {
@@ -445,6 +454,88 @@ int evo_select_elite(evo_check_t *c, const evo_stats *stats, uint32_t P, uint32_
     return dev(evo::launch_select(stats, P, k, elite, n_elite, static_cast<hipStream_t>(stream)));
 }
 
+int evo_time_candidates(evo_check_t *c, const evo_launch_fn *launch, void *const *user, uint32_t P,
+                        uint32_t T, const evo_timing_opts *opts, void *stream, float *timings,
+                        float *clock_ratio) {
+    if (!is_live(c)) return EVO_ERR_HANDLE;
+    if (!launch || !timings || !opts) return EVO_ERR_NULL;
+    if (P == 0 || T == 0 || T > EVO_FITNESS_MAX_T || P > kMaxP || opts->warmup > 1000000u)
+        return EVO_ERR_SIZE;
+    for (uint32_t p = 0; p < P; ++p)
+        if (!launch[p]) return EVO_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(timings) & 3u) return EVO_ERR_ALIGN;
+    int rc = bind_device(c);
+    if (rc != EVO_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    // resources, on first use: two events per timed run plus two probe pairs, the pinned
+    // staging table, the probe's sink, the flush buffer
+    const size_t n_events = 2 * (size_t)T + 4;
+    try {
+        while (c->time_events.size() < n_events) {
+            hipEvent_t e = nullptr;
+            EVO_TRY(hipEventCreate(&e));
+            c->time_events.push_back(e);
+        }
+    } catch (const std::bad_alloc &) {
+        return EVO_ERR_NOMEM;
+    }
+    const size_t count = (size_t)P * T;
+    if (count > c->h_times_count) {
+        if (c->h_times) EVO_TRY(hipHostFree(c->h_times));
+        c->h_times = nullptr;
+        c->h_times_count = 0;
+        void *h = nullptr;
+        EVO_TRY(hipHostMalloc(&h, count * sizeof(float), hipHostMallocDefault));
+        c->h_times = static_cast<float *>(h);
+        c->h_times_count = count;
+    }
+    if (!c->d_probe_sink) {
+        void *d = nullptr;
+        EVO_TRY(hipMalloc(&d, 256));
+        c->d_probe_sink = static_cast<float *>(d);
+    }
+    if (opts->flush_cache && !c->d_flush) EVO_TRY(hipMalloc(&c->d_flush, kFlushBytes));
+
+    hipEvent_t *ev = c->time_events.data();
+    hipEvent_t *probe = ev + 2 * (size_t)T;   // [0],[1] before, [2],[3] after
+    // An idle device sits at a low clock and the first launch of a kernel also loads its
+    // code: a few milliseconds of the probe before anything is timed.
+    for (int i = 0; i < kProbeSpinUp; ++i)
+        EVO_TRY(evo::launch_probe(c->d_probe_sink, kProbeIterations, st));
+    for (uint32_t p = 0; p < P; ++p) {
+        void *u = user ? user[p] : nullptr;
+        for (uint32_t w = 0; w < opts->warmup; ++w) launch[p](u, stream);
+        EVO_TRY(hipEventRecord(probe[0], st));
+        EVO_TRY(evo::launch_probe(c->d_probe_sink, kProbeIterations, st));
+        EVO_TRY(hipEventRecord(probe[1], st));
+        for (uint32_t t = 0; t < T; ++t) {
+            if (opts->flush_cache) EVO_TRY(evo::launch_flush(c->d_flush, kFlushBytes, p * T + t, st));
+            EVO_TRY(hipEventRecord(ev[2 * t], st));
+            launch[p](u, stream);
+            EVO_TRY(hipEventRecord(ev[2 * t + 1], st));
+        }
+        EVO_TRY(hipEventRecord(probe[2], st));
+        EVO_TRY(evo::launch_probe(c->d_probe_sink, kProbeIterations, st));
+        EVO_TRY(hipEventRecord(probe[3], st));
+        EVO_TRY(hipEventSynchronize(probe[3]));
+        for (uint32_t t = 0; t < T; ++t) {
+            float ms = 0.0f;
+            EVO_TRY(hipEventElapsedTime(&ms, ev[2 * t], ev[2 * t + 1]));
+            c->h_times[(size_t)p * T + t] = ms;
+        }
+        if (clock_ratio) {
+            float before = 0.0f, after = 0.0f;
+            EVO_TRY(hipEventElapsedTime(&before, probe[0], probe[1]));
+            EVO_TRY(hipEventElapsedTime(&after, probe[2], probe[3]));
+            clock_ratio[p] = before > 0.0f ? after / before : 0.0f;
+        }
+    }
+    EVO_TRY(hipMemcpyAsync(timings, c->h_times, count * sizeof(float), hipMemcpyHostToDevice, st));
+    EVO_TRY(hipStreamSynchronize(st));   // the staging table may be reused by the next call
+    return EVO_OK;
+}
+
 int evo_check_destroy(evo_check_t *c) {
     {
         std::lock_guard<std::mutex> lk(g_mu);
@@ -463,6 +554,10 @@ int evo_check_destroy(evo_check_t *c) {
             if (s.host) (void)hipHostFree(s.host);
             if (s.done) (void)hipEventDestroy(s.done);
         }
+        for (hipEvent_t e : c->time_events) (void)hipEventDestroy(e);
+        if (c->d_flush) (void)hipFree(c->d_flush);
+        if (c->h_times) (void)hipHostFree(c->h_times);
+        if (c->d_probe_sink) (void)hipFree(c->d_probe_sink);
         if (cur != -1 && cur != c->device) (void)hipSetDevice(cur);
     }
     delete c;

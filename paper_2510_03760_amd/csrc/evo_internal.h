@@ -174,4 +174,9 @@ hipError_t launch_fitness(const float *timings, const float *baseline, uint32_t 
 hipError_t launch_select(const evo_stats *stats, uint32_t P, uint32_t k, uint32_t *elite,
                          uint32_t *n_elite, hipStream_t stream);
 
+// Timing stage helpers: overwrite `bytes` of `buf` (a multiple of 4) with `value`; run a
+// fixed chain of `iterations` dependent FMAs in one wavefront (sink: 4 bytes of scratch).
+hipError_t launch_flush(void *buf, size_t bytes, uint32_t value, hipStream_t stream);
+hipError_t launch_probe(float *sink, uint32_t iterations, hipStream_t stream);
+
 }  // namespace evo

@@ -28,6 +28,8 @@ hipError_t launch_select(const evo_stats *, uint32_t, uint32_t, uint32_t *, uint
     ++g_launches;
     return hipSuccess;
 }
+hipError_t launch_flush(void *, size_t, uint32_t, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_probe(float *, uint32_t, hipStream_t) { ++g_launches; return hipSuccess; }
 }  // namespace evo
 
 static int g_fail = 0;
@@ -244,6 +246,28 @@ static void validation_cases() {
     EXPECT(evo_select_elite(c, stats, 65536, 4, nullptr, elite, nullptr) == EVO_ERR_SIZE);
     EXPECT(evo_select_elite(c, stats, 3, 2, nullptr, reinterpret_cast<uint32_t *>(arena + 3602),
                             nullptr) == EVO_ERR_ALIGN);
+
+    {   // timing stage
+        static int calls = 0;
+        const evo_launch_fn fns[2] = {[](void *, void *) { ++calls; }, [](void *, void *) { ++calls; }};
+        const evo_launch_fn holes[2] = {fns[0], nullptr};
+        const evo_timing_opts opts = {2, 0, {0, 0}};
+        const evo_timing_opts silly = {2000000, 0, {0, 0}};
+        float *tab = reinterpret_cast<float *>(arena + 2048);
+        EXPECT(evo_time_candidates(nullptr, fns, nullptr, 2, 5, &opts, nullptr, tab, nullptr) == EVO_ERR_HANDLE);
+        EXPECT(evo_time_candidates(c, nullptr, nullptr, 2, 5, &opts, nullptr, tab, nullptr) == EVO_ERR_NULL);
+        EXPECT(evo_time_candidates(c, holes, nullptr, 2, 5, &opts, nullptr, tab, nullptr) == EVO_ERR_NULL);
+        EXPECT(evo_time_candidates(c, fns, nullptr, 2, 5, nullptr, nullptr, tab, nullptr) == EVO_ERR_NULL);
+        EXPECT(evo_time_candidates(c, fns, nullptr, 2, 5, &opts, nullptr, nullptr, nullptr) == EVO_ERR_NULL);
+        EXPECT(evo_time_candidates(c, fns, nullptr, 0, 5, &opts, nullptr, tab, nullptr) == EVO_ERR_SIZE);
+        EXPECT(evo_time_candidates(c, fns, nullptr, 2, 0, &opts, nullptr, tab, nullptr) == EVO_ERR_SIZE);
+        EXPECT(evo_time_candidates(c, fns, nullptr, 2, EVO_FITNESS_MAX_T + 1, &opts, nullptr, tab, nullptr) ==
+               EVO_ERR_SIZE);
+        EXPECT(evo_time_candidates(c, fns, nullptr, 2, 5, &silly, nullptr, tab, nullptr) == EVO_ERR_SIZE);
+        EXPECT(evo_time_candidates(c, fns, nullptr, 2, 5, &opts, nullptr,
+                                   reinterpret_cast<float *>(arena + 2050), nullptr) == EVO_ERR_ALIGN);
+        EXPECT(calls == 0);
+    }
 
     EXPECT(evo::g_launches == 0);   // nothing above got past validation
 
