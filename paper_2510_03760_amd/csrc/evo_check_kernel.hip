@@ -1248,6 +1248,18 @@ __device__ __forceinline__ void check_body(const SegDesc *descs, const uint64_t 
     const uint32_t first = (chunk / kFold) * kFold;
     const uint32_t count = min(kFold, sd.n_chunks - first);
     __syncthreads();
+    if (sd.n_jobs == 1 && sd.n_cases <= 1) {
+        // The segment was this one job (small tensors: the call is bound by latency, and
+        // two tickets with their folds would double it): its rows are final.  They were
+        // written by this workgroup and the barrier above orders them before these loads.
+        for (uint32_t p = threadIdx.x; p < sd.P; p += kThreads) {
+            uint32_t group, gi;
+            locate(sd.P, p, &group, &gi);      // one group block: the group is the slot
+            const Partial a = partials[(uint64_t)job * kRowsPerJob + group * kG + gi];
+            write_stats(&stats[sd.stats_row0 + p], a, sd.n);
+        }
+        return;
+    }
     if (threadIdx.x == 0) {
         const uint32_t prev = __hip_atomic_fetch_add(&tickets[bundle], 1u, __ATOMIC_ACQ_REL,
                                                      __HIP_MEMORY_SCOPE_AGENT);
