@@ -1,0 +1,110 @@
+"""Candidates that try to pass without being right (the failure modes behind the inflated
+success counts discussed in the paper's AI-CUDA-Engineer replication appendix): outputs
+filled with NaN, Inf, zeros or a constant, outputs that are right except for a tail, outputs
+that were never written.  Every one of them must come out invalid, for every element type,
+and the rows must equal the oracle's.  Plus guard rows around the result buffer."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import synth  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def gu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_util
+    return gpu_util
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+FLOATS = [torch.float32, torch.bfloat16, torch.float16, torch.float64]
+
+
+@pytest.mark.parametrize("dtype", FLOATS + [torch.int32, torch.int64], ids=lambda d: str(d).split(".")[-1])
+def test_degenerate_candidates_are_invalid(gu, dtype):
+    _say("degenerate candidates %s" % dtype)
+    n = 300001
+    g = torch.Generator(device="cuda")
+    g.manual_seed(77)
+    is_float = dtype in FLOATS
+    if is_float:
+        ref = (torch.randn(n, generator=g, device="cuda") * 2 + 3).to(dtype)      # few values near 0
+    else:
+        ref = torch.randint(1, 1000, (n,), generator=g, device="cuda", dtype=dtype)
+    cands, names = [], []
+
+    def add(name, c):
+        names.append(name)
+        cands.append(c.to(dtype).contiguous())
+
+    add("copy", ref.clone())
+    add("zeros", torch.zeros_like(ref))
+    add("constant", torch.full_like(ref, 3))
+    tail = ref.clone()
+    tail[-7:] = 0                                   # right except for the last 7 elements
+    add("wrong tail", tail)
+    head = ref.clone()
+    head[0] = head[0] + 1 if not is_float else head[0] * 2 + 1
+    add("wrong first element", head)
+    bits = torch.randint(-2 ** 31, 2 ** 31 - 1, (2 * n,), generator=g, device="cuda", dtype=torch.int32)
+    raw = bits.view(torch.uint8)[: n * ref.element_size()].clone().view(dtype)
+    add("never written (random bits)", raw)
+    if is_float:
+        add("NaN filled", torch.full_like(ref, float("nan")))
+        add("Inf filled", torch.full_like(ref, float("inf")))
+        one_nan = ref.clone()
+        one_nan[n // 2] = float("nan")
+        add("one NaN", one_nan)
+        add("negated", -ref)
+    P = len(cands)
+    seg = synth.Segment(ref.contiguous(), cands, (n,), [True] * P)
+    w = synth.Workload("degenerate", [seg], 1e-2, 1e-2, torch.ones(P, 4, device="cuda"),
+                       torch.ones(4, device="cuda"))
+    chk, stats, want = gu.check_parity(w, label="degenerate %s" % dtype)
+    for name, row in zip(names, want):
+        if name == "copy":
+            assert row["valid"] == 1 and row["n_mismatch"] == 0, name
+        else:
+            assert row["valid"] == 0 and row["n_mismatch"] > 0, name
+    assert want[names.index("wrong tail")]["n_mismatch"] == 7
+    assert want[names.index("wrong first element")]["n_mismatch"] == 1
+    # an invalid candidate gets fitness 0 however fast it is
+    tim = torch.ones(P, 4, device="cuda")
+    tim[1:] = 1e-3                                   # everything but the copy is "1000x faster"
+    got, pop, fit = gu.fitness_parity(chk, stats, tim, torch.ones(4, device="cuda"), label="degenerate")
+    assert int(pop["best_idx"]) == 0 and int(pop["n_valid"]) == 1
+    assert float(pop["best_speedup"]) == 1.0 and np.all(got["fitness"][1:] == 0)
+    chk.close()
+
+
+def test_guard_rows_around_the_result_buffer(gu):
+    """The calls write the rows they are given and not a byte more."""
+    _say("guard rows")
+    import paper_2510_03760_amd as evo
+    P, n = 21, 100003
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3)
+    ref = torch.randn(n, generator=g, device="cuda")
+    cands = [ref + 1e-3 * torch.randn(n, generator=g, device="cuda") for _ in range(P)]
+    chk = evo.Checker(evo.EVO_F32, n, 1e-2, 1e-2)
+    big = torch.full(((P + 4) * 72,), 0x5A, dtype=torch.uint8, device="cuda")
+    rows = big[2 * 72:(P + 2) * 72]
+    chk.check_batch(ref, cands, rows)
+    tim = torch.rand(P, 10, device="cuda") + 0.5
+    guard_sum = torch.full((16 * 3,), 0x5A, dtype=torch.uint8, device="cuda")
+    chk.fitness(tim, tim[0].clone(), rows, guard_sum[16:32])
+    elite = torch.full((4 + 8,), -1, dtype=torch.int32, device="cuda")
+    chk.select_elite(rows, P, 4, elite[4:8])
+    torch.cuda.synchronize()
+    assert bool((big[: 2 * 72] == 0x5A).all()) and bool((big[(P + 2) * 72:] == 0x5A).all())
+    assert bool((guard_sum[:16] == 0x5A).all()) and bool((guard_sum[32:] == 0x5A).all())
+    assert bool((elite[:4] == -1).all()) and bool((elite[8:] == -1).all())
+    assert bool((elite[4:8] >= 0).all())
+    chk.close()
