@@ -168,7 +168,8 @@ def main() -> int:
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path is built and measured on ONE GPU; --gpus %d is not "
-              "supported (candidates shard trivially across GPUs, see DESIGN.md)" % args.gpus,
+              "supported (a population shards by candidate: every GPU checks the candidates it "
+              "ran, and only the 72-byte result rows are gathered)" % args.gpus,
               file=sys.stderr)
         return 2
 
