@@ -11,14 +11,19 @@ CSRC = os.path.join(_PKG, "csrc")
 INCLUDE = os.path.join(_ROOT, "include")
 LIB_PATH = os.path.join(_PKG, "libevo.so")
 
-SOURCES = ["evo_api.hip", "evo_check_kernel.hip", "evo_fitness_kernel.hip", "evo_select_kernel.hip",
+SOURCES = ["evo_api.hip", "evo_check_dispatch.hip", "evo_fitness_kernel.hip", "evo_select_kernel.hip",
            "evo_timing_kernel.hip"]
+# evo_check_inst.hip is compiled once per element-type set (bit 1 << evo_dtype): the six
+# single types and the set of all of them.
+CHECK_INST = "evo_check_inst.hip"
+CHECK_SETS = [1, 2, 4, 8, 16, 32, 63]
+HEADERS = ["evo_internal.h", "evo_rcp.h", "evo_check_device.h"]
 
 # -ffp-contract=off: every binary32 operation of the element rule is rounded on its
 # own (no fused multiply-add), as the definition in evo.h requires.
 # packed-fp32-ops off: plain one-lane-one-value fp32 instructions only.
 HIPCC_FLAGS = [
-    "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
+    "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
     "-ffp-contract=off", "-fno-fast-math",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-fvisibility=hidden", "-Wall", "-Wno-unused-function",
@@ -42,7 +47,7 @@ RCP_CHECK_PATH = os.path.join(_PKG, "rcp_check")
 def build_rcp_check() -> str:
     """Compiles the stand-alone device check of the reciprocal shortcut (evo_rcp.h)."""
     tmp = RCP_CHECK_PATH + ".tmp.%d" % os.getpid()
-    flags = [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC", "-fvisibility=hidden")]
+    flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-fvisibility=hidden")]
     cmd = [hipcc(), *flags, "-I", CSRC, "-o", tmp, os.path.join(CSRC, "rcp_check.hip")]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if res.returncode != 0:
@@ -57,7 +62,7 @@ READ_CEILING_PATH = os.path.join(_PKG, "read_ceiling")
 def build_read_ceiling() -> str:
     """Compiles the stand-alone read-only streaming probe (csrc/read_ceiling.hip)."""
     tmp = READ_CEILING_PATH + ".tmp.%d" % os.getpid()
-    flags = [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC", "-fvisibility=hidden")]
+    flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-fvisibility=hidden")]
     cmd = [hipcc(), *flags, "-o", tmp, os.path.join(CSRC, "read_ceiling.hip")]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if res.returncode != 0:
@@ -70,27 +75,51 @@ def is_stale() -> bool:
     if not os.path.exists(LIB_PATH):
         return True
     built = os.path.getmtime(LIB_PATH)
-    deps = sources() + [os.path.join(CSRC, "evo_internal.h"), os.path.join(CSRC, "evo_rcp.h"),
-                        os.path.join(INCLUDE, "evo.h")]
+    deps = sources() + [os.path.join(CSRC, CHECK_INST)] + [os.path.join(CSRC, h) for h in HEADERS] + [
+        os.path.join(INCLUDE, "evo.h")]
     return any(os.path.getmtime(d) > built for d in deps)
 
 
-def build(verbose: bool = False, extra_flags=()) -> str:
-    """Compiles every HIP source into paper_2510_03760_amd/libevo.so."""
-    tmp = LIB_PATH + ".tmp.%d" % os.getpid()
-    cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-I", INCLUDE, "-I", CSRC,
-           "-DEVO_BUILDING=1", "-o", tmp, *sources()]
-    if verbose:
-        print(" ".join(cmd), flush=True)
+def _compile(job):
+    src, obj, extra = job
+    cmd = [hipcc(), *HIPCC_FLAGS, *extra, "-I", INCLUDE, "-I", CSRC, "-DEVO_BUILDING=1", "-c", "-o", obj, src]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     # the host pass warns that it does not know the packed-fp32 feature: harmless
     out = "\n".join(l for l in res.stdout.splitlines()
                     if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + out)
-    if verbose and out.strip():
-        print(out)
-    os.replace(tmp, LIB_PATH)
+    return res.returncode, " ".join(cmd), out
+
+
+def build(verbose: bool = False, extra_flags=(), jobs: int = 0) -> str:
+    """Compiles every HIP source into paper_2510_03760_amd/libevo.so: one object per source
+    (and per element-type set of the check kernel), side by side, then one link."""
+    import shutil
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+    extra = list(extra_flags)
+    work = tempfile.mkdtemp(prefix="evo_build_")
+    try:
+        todo = [(os.path.join(CSRC, CHECK_INST), os.path.join(work, "check_%d.o" % m),
+                 extra + ["-DEVO_INST_DTS=%du" % m]) for m in reversed(CHECK_SETS)]   # longest first
+        todo += [(src, os.path.join(work, os.path.basename(src) + ".o"), extra) for src in sources()]
+        workers = jobs or max(1, min(len(todo), os.cpu_count() or 1, 16))
+        with ThreadPoolExecutor(max_workers=workers) as ex:
+            results = list(ex.map(_compile, todo))
+        for rc, cmd, out in results:
+            if verbose:
+                print(cmd, flush=True)
+                if out.strip():
+                    print(out)
+            if rc != 0:
+                raise RuntimeError("hipcc failed:\n" + cmd + "\n" + out)
+        tmp = LIB_PATH + ".tmp.%d" % os.getpid()
+        link = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + [t[1] for t in todo]
+        res = subprocess.run(link, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("link failed:\n" + res.stdout)
+        os.replace(tmp, LIB_PATH)
+    finally:
+        shutil.rmtree(work, ignore_errors=True)
     if not extra_flags:
         build_rcp_check()
         build_read_ceiling()

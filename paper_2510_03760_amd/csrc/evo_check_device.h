@@ -1,4 +1,6 @@
-// Batched / segmented tolerance check for gfx950 (MI355X).
+// Batched / segmented tolerance check for gfx950 (MI355X): the device code, as templates
+// over the set of element types a launch can meet.  evo_check_inst.hip instantiates it once
+// per set (one translation unit each, so that they compile side by side).
 //
 // Functional-correctness constraint g(p) = 0 of EvoEngineer (arXiv 2510.03760,
 // Sec. 3.1, Eq. 1) as evaluated by the functional-testing stage of Sec. 4.3, for a
@@ -25,6 +27,8 @@
 // Both give identical integers and maxima on the tiles the fast path accepts; the
 // sums differ only in summation order (fp32 over 8 non-negative terms in a tree,
 // then fp64), which stays far inside the 1e-6 relative budget of evo_stats.
+
+#pragma once
 
 #include <type_traits>
 
@@ -1320,47 +1324,26 @@ evo_check_kernel_inline(const InlineTable /*read via the segment pointer*/, uint
     check_body<DTS>(tab->descs, tab->ptrs, S, atol, rtol, n_first, partials, tickets, stats);
 }
 
-constexpr uint32_t kAllTypes = (1u << EVO_F32) | (1u << EVO_BF16) | (1u << EVO_F16) |
-                               (1u << EVO_F64) | (1u << EVO_I32) | (1u << EVO_I64);
-
 }  // namespace
 
-hipError_t launch_check(uint32_t dtype_set, const SegDesc *d_descs, const uint64_t *d_ptrs,
-                        uint32_t S, uint32_t total_jobs, float atol, float rtol, uint32_t n_first,
-                        Partial *partials, uint32_t *tickets, evo_stats *stats, hipStream_t stream) {
-#define EVO_LAUNCH(DTS_)                                                                         \
-    hipLaunchKernelGGL(evo_check_kernel<DTS_>, dim3(total_jobs), dim3(kThreads), 0, stream, d_descs, \
-                       d_ptrs, S, atol, rtol, n_first, partials, tickets, stats)
-    switch (dtype_set) {
-        case 1u << EVO_F32: EVO_LAUNCH(1u << EVO_F32); break;
-        case 1u << EVO_BF16: EVO_LAUNCH(1u << EVO_BF16); break;
-        case 1u << EVO_F16: EVO_LAUNCH(1u << EVO_F16); break;
-        case 1u << EVO_F64: EVO_LAUNCH(1u << EVO_F64); break;
-        case 1u << EVO_I32: EVO_LAUNCH(1u << EVO_I32); break;
-        case 1u << EVO_I64: EVO_LAUNCH(1u << EVO_I64); break;
-        default: EVO_LAUNCH(kAllTypes); break;
-    }
-#undef EVO_LAUNCH
+// The launchers of the instantiation for the element-type set DTS (declared in
+// evo_internal.h; one translation unit per set, see evo_check_inst.hip).
+template <uint32_t DTS>
+hipError_t launch_check_for(const SegDesc *d_descs, const uint64_t *d_ptrs, uint32_t S,
+                            uint32_t total_jobs, float atol, float rtol, uint32_t n_first,
+                            Partial *partials, uint32_t *tickets, evo_stats *stats,
+                            hipStream_t stream) {
+    hipLaunchKernelGGL(evo_check_kernel<DTS>, dim3(total_jobs), dim3(kThreads), 0, stream, d_descs,
+                       d_ptrs, S, atol, rtol, n_first, partials, tickets, stats);
     return hipGetLastError();
 }
 
-hipError_t launch_check_inline(uint32_t dtype_set, const InlineTable &tab, uint32_t S,
-                               uint32_t total_jobs, float atol, float rtol, uint32_t n_first,
-                               Partial *partials, uint32_t *tickets, evo_stats *stats,
-                               hipStream_t stream) {
-#define EVO_LAUNCH(DTS_)                                                                        \
-    hipLaunchKernelGGL(evo_check_kernel_inline<DTS_>, dim3(total_jobs), dim3(kThreads), 0, stream, \
-                       tab, S, atol, rtol, n_first, partials, tickets, stats)
-    switch (dtype_set) {
-        case 1u << EVO_F32: EVO_LAUNCH(1u << EVO_F32); break;
-        case 1u << EVO_BF16: EVO_LAUNCH(1u << EVO_BF16); break;
-        case 1u << EVO_F16: EVO_LAUNCH(1u << EVO_F16); break;
-        case 1u << EVO_F64: EVO_LAUNCH(1u << EVO_F64); break;
-        case 1u << EVO_I32: EVO_LAUNCH(1u << EVO_I32); break;
-        case 1u << EVO_I64: EVO_LAUNCH(1u << EVO_I64); break;
-        default: EVO_LAUNCH(kAllTypes); break;
-    }
-#undef EVO_LAUNCH
+template <uint32_t DTS>
+hipError_t launch_check_inline_for(const InlineTable &tab, uint32_t S, uint32_t total_jobs,
+                                   float atol, float rtol, uint32_t n_first, Partial *partials,
+                                   uint32_t *tickets, evo_stats *stats, hipStream_t stream) {
+    hipLaunchKernelGGL(evo_check_kernel_inline<DTS>, dim3(total_jobs), dim3(kThreads), 0, stream,
+                       tab, S, atol, rtol, n_first, partials, tickets, stats);
     return hipGetLastError();
 }
 

@@ -166,6 +166,20 @@ hipError_t launch_check_inline(uint32_t dtype_set, const InlineTable &tab, uint3
                                Partial *partials, uint32_t *tickets, evo_stats *stats,
                                hipStream_t stream);
 
+// The same two launchers of one instantiation (DTS = its element-type set); each set is
+// compiled in a translation unit of its own.
+constexpr uint32_t kAllTypes = (1u << EVO_F32) | (1u << EVO_BF16) | (1u << EVO_F16) |
+                               (1u << EVO_F64) | (1u << EVO_I32) | (1u << EVO_I64);
+template <uint32_t DTS>
+hipError_t launch_check_for(const SegDesc *d_descs, const uint64_t *d_ptrs, uint32_t S,
+                            uint32_t total_jobs, float atol, float rtol, uint32_t n_first,
+                            Partial *partials, uint32_t *tickets, evo_stats *stats,
+                            hipStream_t stream);
+template <uint32_t DTS>
+hipError_t launch_check_inline_for(const InlineTable &tab, uint32_t S, uint32_t total_jobs,
+                                   float atol, float rtol, uint32_t n_first, Partial *partials,
+                                   uint32_t *tickets, evo_stats *stats, hipStream_t stream);
+
 // base_median: two floats of device scratch (the baseline's median and mean).
 hipError_t launch_fitness(const float *timings, const float *baseline, uint32_t P, uint32_t T,
                           uint32_t reducer, evo_stats *stats, evo_pop_summary *summary,
