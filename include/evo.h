@@ -238,6 +238,21 @@ EVO_API int evo_fitness_ex(evo_check_t *c, const float *timings, const float *ba
                            evo_stats *stats, evo_pop_summary *summary);
 
 /*
+ * The whole evaluation of a population in one call: evo_check_cases (K >= 1 test cases of the
+ * same P candidates; K = 1 is evo_check_batch on cases[0]) followed by evo_fitness_ex, with
+ * the same results as those two calls in that order.  When the K descriptors and K*P
+ * candidate pointers fit the kernel argument block (K <= 8, K*P <= 384) it is ONE launch: the
+ * timing rows are reduced by the first workgroups of the grid while the tensors stream, and
+ * the last of them or of the check to finish computes speedup, fitness and the population
+ * figures.  Larger tables run as two launches.
+ * Arguments and errors: as evo_check_cases and evo_fitness_ex; P is cases[0].P_s.
+ */
+EVO_API int evo_evaluate(evo_check_t *c, const evo_segment *cases, uint32_t K,
+                         const float *timings, const float *baseline, uint32_t T,
+                         int reducer /* evo_reducer */, void *stream, evo_stats *stats,
+                         evo_pop_summary *summary);
+
+/*
  * Population management of Sec. 3.2.2 (elite preservation): the indices of the k
  * candidates with the largest fitness, best first, equal fitness in index order.  Only
  * feasible candidates (fitness > 0: valid, with usable timings) qualify; slots beyond

@@ -97,13 +97,14 @@ def _load() -> ctypes.CDLL:
     h.evo_fitness.argtypes = [vp, vp, vp, u32, u32, vp, vp, vp]
     h.evo_fitness_ex.argtypes = [vp, vp, vp, u32, u32, ctypes.c_int, vp, vp, vp]
     h.evo_select_elite.argtypes = [vp, vp, u32, u32, vp, vp, vp]
+    h.evo_evaluate.argtypes = [vp, ctypes.POINTER(EvoSegment), u32, vp, vp, u32, ctypes.c_int, vp, vp, vp]
     h.evo_time_candidates.argtypes = [vp, ctypes.POINTER(LAUNCH_FN), ctypes.POINTER(vp), u32, u32,
                                       ctypes.POINTER(EvoTimingOpts), vp, vp, ctypes.POINTER(f32)]
     h.evo_check_destroy.argtypes = [vp]
     h.evo_strerror.argtypes = [ctypes.c_int]
     h.evo_strerror.restype = ctypes.c_char_p
     for name in ("evo_check_create", "evo_check_batch", "evo_check_segmented", "evo_check_cases",
-                 "evo_fitness", "evo_fitness_ex", "evo_select_elite", "evo_time_candidates",
+                 "evo_fitness", "evo_fitness_ex", "evo_select_elite", "evo_time_candidates", "evo_evaluate",
                  "evo_check_destroy"):
         getattr(h, name).restype = ctypes.c_int
     return h
@@ -203,6 +204,17 @@ def evo_fitness_ex(ctx: int, timings, baseline, P: int, T: int, reducer: int, st
         raise EvoError(rc, "evo_fitness_ex")
 
 
+def evo_evaluate(ctx: int, cases: Sequence[dict], K: int, timings, baseline, T: int, reducer: int,
+                 stream, stats, summary=None) -> None:
+    """``cases`` as for evo_check_cases."""
+    c_segs, keep = _segment_array(cases)
+    rc = lib.evo_evaluate(ctx, c_segs, int(K), _ptr(timings), _ptr(baseline), int(T), int(reducer),
+                          _stream(stream), _ptr(stats), _ptr(summary))
+    del keep
+    if rc != 0:
+        raise EvoError(rc, "evo_evaluate")
+
+
 def evo_time_candidates(ctx: int, launches, T: int, stream, timings, warmup: int = 3,
                         flush_cache: bool = False, want_clock_ratio: bool = True):
     """``launches``: one Python callable per candidate, called as f(stream_pointer); each must
@@ -289,6 +301,12 @@ class Checker:
         else:
             evo_fitness_ex(self.ctx, timings, baseline, P, T, reducer, st, stats, summary)
 
+
+    def evaluate(self, cases: Sequence[dict], timings: torch.Tensor, baseline: torch.Tensor,
+                 stats: torch.Tensor, summary: Optional[torch.Tensor] = None, stream=None,
+                 reducer: int = EVO_REDUCE_MEDIAN) -> None:
+        evo_evaluate(self.ctx, cases, len(cases), timings, baseline, timings.shape[1], reducer,
+                     stream if stream is not None else torch.cuda.current_stream(), stats, summary)
 
     def time_candidates(self, launches, T: int, timings: torch.Tensor, warmup: int = 3,
                         flush_cache: bool = False, stream=None):

@@ -17,7 +17,7 @@ SOURCES = ["evo_api.hip", "evo_check_dispatch.hip", "evo_fitness_kernel.hip", "e
 # single types and the set of all of them.
 CHECK_INST = "evo_check_inst.hip"
 CHECK_SETS = [1, 2, 4, 8, 16, 32, 63]
-HEADERS = ["evo_internal.h", "evo_rcp.h", "evo_check_device.h"]
+HEADERS = ["evo_internal.h", "evo_rcp.h", "evo_check_device.h", "evo_fitness_device.h"]
 
 # -ffp-contract=off: every binary32 operation of the element rule is rounded on its
 # own (no fused multiply-add), as the definition in evo.h requires.

@@ -50,6 +50,8 @@ struct evo_check {
     size_t n_tickets = 0;
     float *d_base_median = nullptr;
     uint32_t *d_fit_ticket = nullptr;
+    float *d_fit_rows = nullptr;     // (median, mean) pairs of evo_evaluate
+    size_t fit_rows_count = 0;
     StageSlot slots[kStageSlots];
     int next_slot = 0;
     // timing stage (evo_time_candidates)
@@ -131,6 +133,17 @@ int ensure_fitness_scratch(evo_check *c, hipStream_t stream) {
     EVO_TRY(hipMemsetAsync(p, 0, 256, stream));
     c->d_base_median = static_cast<float *>(p);
     c->d_fit_ticket = reinterpret_cast<uint32_t *>(static_cast<char *>(p) + 128);
+    return EVO_OK;
+}
+
+int ensure_fit_rows(evo_check *c, size_t P) {
+    if (P <= c->fit_rows_count) return EVO_OK;
+    if (c->d_fit_rows) EVO_TRY(hipFree(c->d_fit_rows));
+    c->d_fit_rows = nullptr;
+    c->fit_rows_count = 0;
+    const size_t cap = std::max<size_t>(2 * P, 256);
+    EVO_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_fit_rows), cap * 2 * sizeof(float)));
+    c->fit_rows_count = cap;
     return EVO_OK;
 }
 
@@ -251,8 +264,10 @@ bool partition_fits(const std::vector<HostSeg> &segs) {
     return true;
 }
 
+// fit: when given, the timing reduction is part of the same work (evo_evaluate): one launch
+// when the table fits the kernel argument block, else the check and then the fitness kernel.
 int run_check(evo_check *c, const std::vector<HostSeg> &segs, hipStream_t stream,
-              evo_stats *stats) {
+              evo_stats *stats, const evo::FitLaunch *fit = nullptr) {
     int rc = bind_device(c);
     if (rc != EVO_OK) return rc;
 
@@ -301,6 +316,9 @@ int run_check(evo_check *c, const std::vector<HostSeg> &segs, hipStream_t stream
             for (uint32_t p = 0; p < segs[s].P; ++p)
                 tab.ptrs[descs[s].ptr0 + p] = reinterpret_cast<uint64_t>(segs[s].cand_ptrs[p]);
         }
+        if (fit)
+            return dev(evo::launch_evaluate(dtype_set, tab, (uint32_t)S, total_jobs, c->atol, c->rtol,
+                                            c->n_cus, c->d_partials, c->d_tickets, stats, *fit, stream));
         return dev(evo::launch_check_inline(dtype_set, tab, (uint32_t)S, total_jobs, c->atol, c->rtol,
                                             c->n_cus, c->d_partials, c->d_tickets, stats, stream));
     }
@@ -322,10 +340,13 @@ int run_check(evo_check *c, const std::vector<HostSeg> &segs, hipStream_t stream
     EVO_TRY(hipEventRecord(slot->done, stream));
     slot->in_flight = true;
 
-    return dev(evo::launch_check(
+    rc = dev(evo::launch_check(
         dtype_set, static_cast<const SegDesc *>(c->d_table),
         reinterpret_cast<const uint64_t *>(static_cast<char *>(c->d_table) + desc_bytes), (uint32_t)S,
         total_jobs, c->atol, c->rtol, c->n_cus, c->d_partials, c->d_tickets, stats, stream));
+    if (rc != EVO_OK || !fit) return rc;
+    return dev(evo::launch_fitness(fit->timings, fit->baseline, fit->P, fit->T, fit->reducer, stats,
+                                   fit->summary, fit->base, fit->ticket, stream));
 }
 
 }  // namespace
@@ -454,6 +475,38 @@ int evo_select_elite(evo_check_t *c, const evo_stats *stats, uint32_t P, uint32_
     return dev(evo::launch_select(stats, P, k, elite, n_elite, static_cast<hipStream_t>(stream)));
 }
 
+int evo_evaluate(evo_check_t *c, const evo_segment *cases, uint32_t K, const float *timings,
+                 const float *baseline, uint32_t T, int reducer, void *stream, evo_stats *stats,
+                 evo_pop_summary *summary) {
+    if (!is_live(c)) return EVO_ERR_HANDLE;
+    if (!cases || !stats || !timings || !baseline) return EVO_ERR_NULL;
+    if (K == 0 || T == 0 || T > EVO_FITNESS_MAX_T) return EVO_ERR_SIZE;
+    if (reducer != EVO_REDUCE_MEDIAN && reducer != EVO_REDUCE_MEAN) return EVO_ERR_SIZE;
+    if ((reinterpret_cast<uintptr_t>(timings) & 3u) || (reinterpret_cast<uintptr_t>(baseline) & 3u) ||
+        (reinterpret_cast<uintptr_t>(stats) & 7u) || (reinterpret_cast<uintptr_t>(summary) & 3u))
+        return EVO_ERR_ALIGN;
+    try {
+        std::vector<HostSeg> hs(K);
+        for (uint32_t k = 0; k < K; ++k) {
+            hs[k] = HostSeg{cases[k].ref, cases[k].cand_ptrs, cases[k].n_elems, cases[k].P_s,
+                            cases[k].dtype, 0u, 0u, K};
+            const int rc = validate_seg(hs[k]);
+            if (rc != EVO_OK) return rc;
+            if (cases[k].P_s != cases[0].P_s || cases[k].stats_row0 != 0) return EVO_ERR_SIZE;
+        }
+        int rc = bind_device(c);
+        if (rc != EVO_OK) return rc;
+        hipStream_t st = static_cast<hipStream_t>(stream);
+        if ((rc = ensure_fitness_scratch(c, st)) != EVO_OK) return rc;
+        if ((rc = ensure_fit_rows(c, cases[0].P_s)) != EVO_OK) return rc;
+        const evo::FitLaunch fit{timings, baseline, summary, c->d_base_median, c->d_fit_rows,
+                                 c->d_fit_ticket, cases[0].P_s, T, (uint32_t)reducer};
+        return run_check(c, hs, st, stats, &fit);
+    } catch (const std::bad_alloc &) {
+        return EVO_ERR_NOMEM;
+    }
+}
+
 int evo_time_candidates(evo_check_t *c, const evo_launch_fn *launch, void *const *user, uint32_t P,
                         uint32_t T, const evo_timing_opts *opts, void *stream, float *timings,
                         float *clock_ratio) {
@@ -550,6 +603,7 @@ int evo_check_destroy(evo_check_t *c) {
         if (c->d_partials) (void)hipFree(c->d_partials);
         if (c->d_tickets) (void)hipFree(c->d_tickets);
         if (c->d_base_median) (void)hipFree(c->d_base_median);
+        if (c->d_fit_rows) (void)hipFree(c->d_fit_rows);
         for (StageSlot &s : c->slots) {
             if (s.host) (void)hipHostFree(s.host);
             if (s.done) (void)hipEventDestroy(s.done);

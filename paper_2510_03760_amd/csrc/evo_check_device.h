@@ -33,6 +33,7 @@
 #include <type_traits>
 
 #include "evo_internal.h"
+#include "evo_fitness_device.h"
 #include "evo_rcp.h"
 
 namespace evo {
@@ -1171,12 +1172,15 @@ __device__ __forceinline__ void write_case_group(const SegDesc *descs, const Seg
 // DTS = set of element types (bit 1 << evo_dtype) this instantiation can meet.  A launch
 // whose segments all have one element type gets a kernel that holds only that type's
 // code, so that its register allocation is not the worst case over all types.
+// job / total_jobs: this workgroup's job and the number of jobs of the launch (the grid may
+// hold other workgroups too, see evo_evaluate_kernel).  Returns true, in every thread, in a
+// workgroup that has just written evo_stats rows.
 template <uint32_t DTS>
-__device__ __forceinline__ void check_body(const SegDesc *descs, const uint64_t *ptr_table,
+__device__ __forceinline__ bool check_body(const SegDesc *descs, const uint64_t *ptr_table,
                                            uint32_t S, float atol, float rtol, uint32_t n_first,
+                                           uint32_t job, uint32_t total_jobs,
                                            Partial *partials, uint32_t *tickets, evo_stats *stats) {
     // Which segment does this workgroup belong to?  (job0 is ascending.)
-    const uint32_t job = blockIdx.x;
     uint32_t lo = 0, hi = S;
     while (hi - lo > 1) {
         const uint32_t mid = (lo + hi) >> 1;
@@ -1243,8 +1247,8 @@ __device__ __forceinline__ void check_body(const SegDesc *descs, const uint64_t 
     // 2-10 us, on a path that nothing overlaps once the last tile has been streamed.
     __shared__ uint32_t is_last;
     __shared__ Partial fold[kThreads];
-    Partial *rows1 = partials + (uint64_t)gridDim.x * kRowsPerJob;
-    uint32_t *seg_tickets = tickets + gridDim.x;
+    Partial *rows1 = partials + (uint64_t)total_jobs * kRowsPerJob;
+    uint32_t *seg_tickets = tickets + total_jobs;
     const uint32_t gblock = job_local / sd.n_chunks;
     const uint32_t chunk = job_local - gblock * sd.n_chunks;
     const uint32_t units = (sd.n_chunks + kFold - 1) / kFold;        // bundles per group block
@@ -1262,7 +1266,7 @@ __device__ __forceinline__ void check_body(const SegDesc *descs, const uint64_t 
             const Partial a = partials[(uint64_t)job * kRowsPerJob + group * kG + gi];
             write_stats(&stats[sd.stats_row0 + p], a, sd.n);
         }
-        return;
+        return true;
     }
     if (threadIdx.x == 0) {
         const uint32_t prev = __hip_atomic_fetch_add(&tickets[bundle], 1u, __ATOMIC_ACQ_REL,
@@ -1270,7 +1274,7 @@ __device__ __forceinline__ void check_body(const SegDesc *descs, const uint64_t 
         is_last = (prev == count - 1) ? 1u : 0u;
     }
     __syncthreads();
-    if (!is_last) return;
+    if (!is_last) return false;
     fold_bundle(sd, gblock, first, count, partials, rows1 + (uint64_t)bundle * kRowsPerJob, fold);
     if (threadIdx.x == 0) {
         __hip_atomic_store(&tickets[bundle], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1280,12 +1284,12 @@ __device__ __forceinline__ void check_body(const SegDesc *descs, const uint64_t 
         is_last = (prev == n_bundles - 1) ? 1u : 0u;
     }
     __syncthreads();
-    if (!is_last) return;
-    Partial *case_rows = rows1 + (uint64_t)gridDim.x * kRowsPerJob;
+    if (!is_last) return false;
+    Partial *case_rows = rows1 + (uint64_t)total_jobs * kRowsPerJob;
     finalize_segment(sd, rows1, units, stats, case_rows, fold);
     if (threadIdx.x == 0)
         __hip_atomic_store(&seg_tickets[s], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (sd.n_cases <= 1) return;
+    if (sd.n_cases <= 1) return true;
 
     // The segment is one case of a case group: third ticket, and the last case merges.
     uint32_t *case_tickets = seg_tickets + S;
@@ -1296,10 +1300,11 @@ __device__ __forceinline__ void check_body(const SegDesc *descs, const uint64_t 
         is_last = (prev == sd.n_cases - 1) ? 1u : 0u;
     }
     __syncthreads();
-    if (!is_last) return;
+    if (!is_last) return false;
     write_case_group(descs, sd, case_rows, stats);
     if (threadIdx.x == 0)
         __hip_atomic_store(&case_tickets[sd.case0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return true;
 }
 
 template <uint32_t DTS>
@@ -1308,7 +1313,8 @@ evo_check_kernel(const SegDesc *__restrict__ descs, const uint64_t *__restrict__
                  uint32_t S, float atol, float rtol, uint32_t n_first,
                  Partial *__restrict__ partials, uint32_t *__restrict__ tickets,
                  evo_stats *__restrict__ stats) {
-    check_body<DTS>(descs, ptr_table, S, atol, rtol, n_first, partials, tickets, stats);
+    (void)check_body<DTS>(descs, ptr_table, S, atol, rtol, n_first, blockIdx.x, gridDim.x, partials, tickets,
+                          stats);
 }
 
 // Same kernel with the table inside the kernel argument block.  The block is read in
@@ -1321,7 +1327,56 @@ evo_check_kernel_inline(const InlineTable /*read via the segment pointer*/, uint
                         float rtol, uint32_t n_first, Partial *__restrict__ partials,
                         uint32_t *__restrict__ tickets, evo_stats *__restrict__ stats) {
     const InlineTable *tab = (const InlineTable *)__builtin_amdgcn_kernarg_segment_ptr();
-    check_body<DTS>(tab->descs, tab->ptrs, S, atol, rtol, n_first, partials, tickets, stats);
+    (void)check_body<DTS>(tab->descs, tab->ptrs, S, atol, rtol, n_first, blockIdx.x, gridDim.x, partials,
+                          tickets, stats);
+}
+
+// The whole evaluation of a population in one launch: the check of evo_check_kernel_inline
+// and the timing reduction of evo_fitness_kernel.  The first P + 1 workgroups of the grid
+// reduce the timing rows (they take microseconds and free their slots for check jobs); the
+// others are check jobs.  Speedup, fitness and the population figures need every median and
+// every valid flag: each timing workgroup and the workgroup that writes the evo_stats rows
+// take a ticket, and whoever draws the last of the P + 2 does the rest.  Only for launches
+// with one result-writing event: one segment, or one case group.
+struct FitArgs {
+    const float *timings;
+    const float *baseline;
+    evo_pop_summary *summary;
+    float *base;          // two floats of scratch: baseline median and mean
+    float *rows;          // P (median, mean) pairs of scratch
+    uint32_t *ticket;     // zero between launches
+    uint32_t P, T, reducer;
+};
+
+template <uint32_t DTS>
+__global__ void __launch_bounds__(kThreads, EVO_WAVES_PER_EU)
+evo_evaluate_kernel(const InlineTable /*read via the segment pointer*/, uint32_t S, float atol,
+                    float rtol, uint32_t n_first, Partial *__restrict__ partials,
+                    uint32_t *__restrict__ tickets, evo_stats *__restrict__ stats, const FitArgs fit) {
+    const InlineTable *tab = (const InlineTable *)__builtin_amdgcn_kernarg_segment_ptr();
+    const uint32_t n_rows = fit.P + 1;
+    bool last;
+    if (blockIdx.x < n_rows) {
+        // the pairs go to scratch: the evo_stats rows are written whole, later, by the check
+        last = fitness_row_and_ticket(fit.timings, fit.baseline, blockIdx.x, fit.P, fit.T, stats, fit.rows,
+                                      fit.base, fit.ticket, n_rows);
+    } else {
+        if (!check_body<DTS>(tab->descs, tab->ptrs, S, atol, rtol, n_first, blockIdx.x - n_rows,
+                             gridDim.x - n_rows, partials, tickets, stats))
+            return;
+        __shared__ uint32_t drew_last;
+        __syncthreads();   // every row of this workgroup is written before thread 0's release
+        if (threadIdx.x == 0) {
+            const uint32_t prev = __hip_atomic_fetch_add(fit.ticket, 1u, __ATOMIC_ACQ_REL,
+                                                         __HIP_MEMORY_SCOPE_AGENT);
+            drew_last = (prev == n_rows) ? 1u : 0u;
+        }
+        __syncthreads();
+        last = drew_last != 0;
+    }
+    if (!last) return;
+    fitness_finish(fit.P, fit.reducer, stats, fit.summary, fit.base, fit.rows);
+    if (threadIdx.x == 0) __hip_atomic_store(fit.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 }  // namespace
@@ -1344,6 +1399,16 @@ hipError_t launch_check_inline_for(const InlineTable &tab, uint32_t S, uint32_t 
                                    uint32_t *tickets, evo_stats *stats, hipStream_t stream) {
     hipLaunchKernelGGL(evo_check_kernel_inline<DTS>, dim3(total_jobs), dim3(kThreads), 0, stream,
                        tab, S, atol, rtol, n_first, partials, tickets, stats);
+    return hipGetLastError();
+}
+
+template <uint32_t DTS>
+hipError_t launch_evaluate_for(const InlineTable &tab, uint32_t S, uint32_t total_jobs, float atol,
+                               float rtol, uint32_t n_first, Partial *partials, uint32_t *tickets,
+                               evo_stats *stats, const FitLaunch &f, hipStream_t stream) {
+    const FitArgs fit{f.timings, f.baseline, f.summary, f.base, f.rows, f.ticket, f.P, f.T, f.reducer};
+    hipLaunchKernelGGL(evo_evaluate_kernel<DTS>, dim3(total_jobs + f.P + 1), dim3(kThreads), 0, stream,
+                       tab, S, atol, rtol, n_first, partials, tickets, stats, fit);
     return hipGetLastError();
 }
 

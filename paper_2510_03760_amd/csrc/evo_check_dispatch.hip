@@ -40,4 +40,23 @@ hipError_t launch_check_inline(uint32_t dtype_set, const InlineTable &tab, uint3
 #undef EVO_LAUNCH
 }
 
+hipError_t launch_evaluate(uint32_t dtype_set, const InlineTable &tab, uint32_t S, uint32_t total_jobs,
+                           float atol, float rtol, uint32_t n_first, Partial *partials,
+                           uint32_t *tickets, evo_stats *stats, const FitLaunch &fit,
+                           hipStream_t stream) {
+#define EVO_LAUNCH(DTS_)                                                                          \
+    return launch_evaluate_for<DTS_>(tab, S, total_jobs, atol, rtol, n_first, partials, tickets,  \
+                                     stats, fit, stream)
+    switch (dtype_set) {
+        case 1u << EVO_F32: EVO_LAUNCH(1u << EVO_F32);
+        case 1u << EVO_BF16: EVO_LAUNCH(1u << EVO_BF16);
+        case 1u << EVO_F16: EVO_LAUNCH(1u << EVO_F16);
+        case 1u << EVO_F64: EVO_LAUNCH(1u << EVO_F64);
+        case 1u << EVO_I32: EVO_LAUNCH(1u << EVO_I32);
+        case 1u << EVO_I64: EVO_LAUNCH(1u << EVO_I64);
+        default: EVO_LAUNCH(kAllTypes);
+    }
+#undef EVO_LAUNCH
+}
+
 }  // namespace evo

@@ -149,7 +149,7 @@ struct InlineTable {
     SegDesc descs[kInlineSegs];
     uint64_t ptrs[kInlinePtrs];
 };
-static_assert(sizeof(InlineTable) <= 3600, "kernel argument block must stay below 4 KiB");
+static_assert(sizeof(InlineTable) <= 3600, "kernel argument block must stay below 4 KiB");   // + other arguments
 
 // Scratch layout of one launch (J = workgroups, S = segments, C = candidate pointers):
 //   partials: J*kRowsPerJob first-level rows | J*kRowsPerJob second-level rows | C case rows
@@ -166,6 +166,22 @@ hipError_t launch_check_inline(uint32_t dtype_set, const InlineTable &tab, uint3
                                Partial *partials, uint32_t *tickets, evo_stats *stats,
                                hipStream_t stream);
 
+// The check and the timing reduction in one launch (small launches only: the table travels
+// in the kernel argument block; exactly one segment or one case group).
+struct FitLaunch {
+    const float *timings;
+    const float *baseline;
+    evo_pop_summary *summary;
+    float *base;          // two floats of device scratch
+    float *rows;          // 2 * P floats of device scratch
+    uint32_t *ticket;     // device, zero between launches
+    uint32_t P, T, reducer;
+};
+hipError_t launch_evaluate(uint32_t dtype_set, const InlineTable &tab, uint32_t S, uint32_t total_jobs,
+                           float atol, float rtol, uint32_t n_first, Partial *partials,
+                           uint32_t *tickets, evo_stats *stats, const FitLaunch &fit,
+                           hipStream_t stream);
+
 // The same two launchers of one instantiation (DTS = its element-type set); each set is
 // compiled in a translation unit of its own.
 constexpr uint32_t kAllTypes = (1u << EVO_F32) | (1u << EVO_BF16) | (1u << EVO_F16) |
@@ -179,6 +195,10 @@ template <uint32_t DTS>
 hipError_t launch_check_inline_for(const InlineTable &tab, uint32_t S, uint32_t total_jobs,
                                    float atol, float rtol, uint32_t n_first, Partial *partials,
                                    uint32_t *tickets, evo_stats *stats, hipStream_t stream);
+template <uint32_t DTS>
+hipError_t launch_evaluate_for(const InlineTable &tab, uint32_t S, uint32_t total_jobs, float atol,
+                               float rtol, uint32_t n_first, Partial *partials, uint32_t *tickets,
+                               evo_stats *stats, const FitLaunch &fit, hipStream_t stream);
 
 // base_median: two floats of device scratch (the baseline's median and mean).
 hipError_t launch_fitness(const float *timings, const float *baseline, uint32_t P, uint32_t T,

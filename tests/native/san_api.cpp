@@ -28,6 +28,8 @@ hipError_t launch_select(const evo_stats *, uint32_t, uint32_t, uint32_t *, uint
     ++g_launches;
     return hipSuccess;
 }
+hipError_t launch_evaluate(uint32_t, const InlineTable &, uint32_t, uint32_t, float, float, uint32_t, Partial *,
+                           uint32_t *, evo_stats *, const FitLaunch &, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_flush(void *, size_t, uint32_t, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_probe(float *, uint32_t, hipStream_t) { ++g_launches; return hipSuccess; }
 }  // namespace evo
@@ -246,6 +248,22 @@ static void validation_cases() {
     EXPECT(evo_select_elite(c, stats, 65536, 4, nullptr, elite, nullptr) == EVO_ERR_SIZE);
     EXPECT(evo_select_elite(c, stats, 3, 2, nullptr, reinterpret_cast<uint32_t *>(arena + 3602),
                             nullptr) == EVO_ERR_ALIGN);
+
+    // evaluation in one call
+    EXPECT(evo_evaluate(nullptr, cs, 2, tim, base, 5, 0, nullptr, stats, pop) == EVO_ERR_HANDLE);
+    EXPECT(evo_evaluate(c, nullptr, 2, tim, base, 5, 0, nullptr, stats, pop) == EVO_ERR_NULL);
+    EXPECT(evo_evaluate(c, cs, 2, nullptr, base, 5, 0, nullptr, stats, pop) == EVO_ERR_NULL);
+    EXPECT(evo_evaluate(c, cs, 2, tim, nullptr, 5, 0, nullptr, stats, pop) == EVO_ERR_NULL);
+    EXPECT(evo_evaluate(c, cs, 2, tim, base, 5, 0, nullptr, nullptr, pop) == EVO_ERR_NULL);
+    EXPECT(evo_evaluate(c, cs, 0, tim, base, 5, 0, nullptr, stats, pop) == EVO_ERR_SIZE);
+    EXPECT(evo_evaluate(c, cs, 2, tim, base, 0, 0, nullptr, stats, pop) == EVO_ERR_SIZE);
+    EXPECT(evo_evaluate(c, cs, 2, tim, base, EVO_FITNESS_MAX_T + 1, 0, nullptr, stats, pop) == EVO_ERR_SIZE);
+    EXPECT(evo_evaluate(c, cs, 2, tim, base, 5, 7, nullptr, stats, pop) == EVO_ERR_SIZE);
+    EXPECT(evo_evaluate(c, cs, 2, reinterpret_cast<const float *>(arena + 2050), base, 5, 0, nullptr, stats,
+                        pop) == EVO_ERR_ALIGN);
+    cs[1].P_s = 2;
+    EXPECT(evo_evaluate(c, cs, 2, tim, base, 5, 0, nullptr, stats, pop) == EVO_ERR_SIZE);
+    cs[1].P_s = 3;
 
     {   // timing stage
         static int calls = 0;
