@@ -104,6 +104,9 @@ def _load_locked(path, key):
         lib.oracle_select_elite.argtypes = [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint32,
                                             ctypes.c_void_p]
         lib.oracle_select_elite.restype = ctypes.c_uint32
+        lib.oracle_select_elite_diverse.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32,
+                                                    ctypes.c_uint32, ctypes.c_void_p]
+        lib.oracle_select_elite_diverse.restype = ctypes.c_uint32
         lib.oracle_half_to_float.argtypes = [ctypes.c_uint16]
         lib.oracle_half_to_float.restype = ctypes.c_float
         lib.oracle_acc_size.restype = ctypes.c_uint32
@@ -226,6 +229,18 @@ def select_elite(fitness_values, k: int, lib_path: str = None) -> dict:
     return {"elite": out[:k].copy(), "n_elite": int(n)}
 
 
+def select_elite_diverse(fitness_values, keys, k: int, lib_path: str = None) -> dict:
+    """Indices of the k best feasible candidates with pairwise different keys, best first."""
+    lib = _load(lib_path)
+    f = np.ascontiguousarray(fitness_values, dtype=np.float32).reshape(-1)
+    ky = np.ascontiguousarray(keys, dtype=np.uint32).reshape(-1)
+    if ky.size != f.size:
+        raise ValueError("one key per candidate")
+    out = np.empty(max(1, k), np.uint32)
+    n = lib.oracle_select_elite_diverse(f.ctypes.data, ky.ctypes.data, f.size, k, out.ctypes.data)
+    return {"elite": out[:k].copy(), "n_elite": int(n)}
+
+
 class Variant:
     """The same interface bound to another build of the C file (used by the tests
     that check the pins catch planted mistakes)."""
@@ -252,6 +267,9 @@ class Variant:
 
     def select_elite(self, fitness_values, k):
         return select_elite(fitness_values, k, self.lib_path)
+
+    def select_elite_diverse(self, fitness_values, keys, k):
+        return select_elite_diverse(fitness_values, keys, k, self.lib_path)
 
     def half_to_float(self, bits):
         return half_to_float(bits, self.lib_path)

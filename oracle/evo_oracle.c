@@ -450,4 +450,39 @@ uint32_t oracle_select_elite(const float *fitness, uint32_t P, uint32_t k, uint3
     return filled;
 }
 
+/*
+ * Elite preservation with diversity maintenance (the third population-management strategy
+ * of Sec. 3.2.2): as oracle_select_elite, but no two selected candidates share a key.  The
+ * key is the caller's notion of "the same solution" (a hash of the kernel source, say); of
+ * the feasible candidates with one key only the best (lowest index on ties) can be
+ * selected.  Repeated scan; returns the number of slots filled, unused slots hold P.
+ */
+uint32_t oracle_select_elite_diverse(const float *fit, const uint32_t *keys, uint32_t P,
+                                     uint32_t k, uint32_t *elite)
+{
+    uint32_t filled = 0;
+    for (uint32_t r = 0; r < k; ++r)
+        elite[r] = P;
+    for (uint32_t r = 0; r < k; ++r) {
+        uint32_t top = P;
+        for (uint32_t i = 0; i < P; ++i) {
+            int key_taken = 0;
+            if (!(fit[i] > 0.0f))
+                continue;
+            for (uint32_t q = 0; q < r; ++q)
+                if (keys[elite[q]] == keys[i])
+                    key_taken = 1;
+            if (key_taken)
+                continue;
+            if (top == P || fit[i] > fit[top])
+                top = i; /* strict: of equal fitness the first wins */
+        }
+        if (top == P)
+            break;
+        elite[r] = top;
+        filled = r + 1;
+    }
+    return filled;
+}
+
 uint32_t oracle_acc_size(void) { return (uint32_t)sizeof(oracle_check_acc); }

@@ -553,10 +553,46 @@ def pin_mean_reducer(orc):
         assert _same_f32(got["speedup"][p], bm / m)
 
 
+def pin_select_elite_diverse(orc):
+    """Diversity-keeping elite selection against a stable library sort with first-occurrence
+    filtering, and a hand-made case."""
+    f = np.array([0.5, 2.0, 0.0, 2.0, 1.5, 0.0, 3.0, 2.0, 3.0], np.float32)
+    keys = np.array([7, 1, 1, 1, 2, 9, 3, 4, 3], np.uint32)
+    got = orc.select_elite_diverse(f, keys, 4)
+    # 6 (3.0, key 3) ; 8 has key 3 again ; 1 (2.0, key 1) ; 3 has key 1 again ; 7 (2.0, key 4) ; 4
+    assert got["elite"].tolist() == [6, 1, 7, 4] and got["n_elite"] == 4
+    got = orc.select_elite_diverse(f, keys, 9)
+    assert got["elite"].tolist() == [6, 1, 7, 4, 0, 9, 9, 9, 9] and got["n_elite"] == 5
+    # all keys different: the plain selection; all keys equal: only the best
+    assert orc.select_elite_diverse(f, np.arange(9, dtype=np.uint32), 4)["elite"].tolist() == \
+        orc.select_elite(f, 4)["elite"].tolist()
+    got = orc.select_elite_diverse(f, np.zeros(9, np.uint32), 3)
+    assert got["elite"].tolist() == [6, 9, 9] and got["n_elite"] == 1
+    # an infeasible candidate does not block its key
+    got = orc.select_elite_diverse(np.array([0.0, 1.0], np.float32), np.array([5, 5], np.uint32), 2)
+    assert got["elite"].tolist() == [1, 2] and got["n_elite"] == 1
+    rng = np.random.default_rng(8)
+    for P, k, nkeys in ((1, 1, 1), (17, 4, 5), (256, 8, 30), (1000, 1000, 400), (333, 50, 10)):
+        f = rng.choice(np.array([0, 0.5, 0.75, 1, 1.25, 2, np.inf], np.float32), P)
+        some = rng.random(P) < 0.3
+        f[some] = rng.random(int(some.sum())).astype(np.float32)
+        keys = rng.integers(0, nkeys, P).astype(np.uint32) * np.uint32(2654435761)
+        order = np.lexsort((np.arange(P), -f.astype(np.float64)))
+        want, seen = [], set()
+        for i in order:
+            if f[i] > 0 and int(keys[i]) not in seen:
+                seen.add(int(keys[i]))
+                want.append(int(i))
+        want = want[:k]
+        got = orc.select_elite_diverse(f, keys, k)
+        assert got["n_elite"] == len(want)
+        assert got["elite"].tolist() == want + [P] * (k - len(want)), (P, k)
+
+
 ALL_PINS = [
     pin_truth_table, pin_flag_classes, pin_worked_check_examples, pin_worked_fitness_examples,
     pin_numpy_isclose, pin_sums_and_maxima, pin_invariants, pin_bf16_widening, pin_f16_widening,
     pin_median_and_speedup, pin_unusable_timing_rows, pin_select_elite,
     pin_f64_truth_table, pin_f64_numpy_isclose_sums_maxima, pin_f64_agrees_with_f32_where_both_are_exact,
-    pin_integer_equality, pin_mean_reducer,
+    pin_integer_equality, pin_mean_reducer, pin_select_elite_diverse,
 ]

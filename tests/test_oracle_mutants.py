@@ -68,6 +68,9 @@ MUTANTS = [
     ("int_not_counted_finite", "        diff32 = (float)diff;\n        a->n_finite += 1;", "        diff32 = (float)diff;"),
     ("mean_reducer_keeps_median_baseline", "speedup[p] = base_mean / mean_ms[p];", "speedup[p] = base_median / mean_ms[p];"),
     ("mean_reducer_ignored", "else if (reducer == ORACLE_REDUCE_MEAN)", "else if (0)"),
+    ("diverse_ignores_keys", "                if (keys[elite[q]] == keys[i])\n                    key_taken = 1;", "                if (elite[q] == i)\n                    key_taken = 1;"),
+    ("diverse_infeasible_blocks_key", "            int key_taken = 0;\n            if (!(fit[i] > 0.0f))\n                continue;", "            int key_taken = 0;\n            if (0)\n                continue;"),
+    ("diverse_last_of_ties", "                top = i; /* strict: of equal fitness the first wins */", "                top = i; /* mutated */\n            else if (fit[i] == fit[top]) top = i;"),
     ("mean_reducer_always", "else if (reducer == ORACLE_REDUCE_MEAN)", "else if (1)"),
 ]
 
