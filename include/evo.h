@@ -268,6 +268,19 @@ EVO_API int evo_select_elite(evo_check_t *c, const evo_stats *stats, uint32_t P,
                              void *stream, uint32_t *elite, uint32_t *n_elite);
 
 /*
+ * evo_select_elite with diversity maintenance (the third population-management strategy of
+ * Sec. 3.2.2): keys[p] is the caller's notion of "the same solution" (a hash of the kernel
+ * source, say), and no two selected candidates share a key -- of the feasible candidates with
+ * one key only the best (lowest index on ties) competes.  n_elite is min(k, number of
+ * distinct keys among the feasible candidates).
+ *   keys   device, P entries
+ * Errors: as evo_select_elite, plus EVO_ERR_NULL / EVO_ERR_ALIGN for keys, EVO_ERR_NOMEM.
+ */
+EVO_API int evo_select_elite_diverse(evo_check_t *c, const evo_stats *stats, const uint32_t *keys,
+                                     uint32_t P, uint32_t k, void *stream, uint32_t *elite,
+                                     uint32_t *n_elite);
+
+/*
  * Timing stage of the evaluator (Sec. 4.3: the execution time of a candidate is collected
  * over 100 runs; the appendix on threats to validity names run-to-run noise): produces the
  * P x T table of milliseconds that evo_fitness consumes.  For every candidate p the library

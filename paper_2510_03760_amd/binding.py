@@ -97,6 +97,7 @@ def _load() -> ctypes.CDLL:
     h.evo_fitness.argtypes = [vp, vp, vp, u32, u32, vp, vp, vp]
     h.evo_fitness_ex.argtypes = [vp, vp, vp, u32, u32, ctypes.c_int, vp, vp, vp]
     h.evo_select_elite.argtypes = [vp, vp, u32, u32, vp, vp, vp]
+    h.evo_select_elite_diverse.argtypes = [vp, vp, vp, u32, u32, vp, vp, vp]
     h.evo_evaluate.argtypes = [vp, ctypes.POINTER(EvoSegment), u32, vp, vp, u32, ctypes.c_int, vp, vp, vp]
     h.evo_time_candidates.argtypes = [vp, ctypes.POINTER(LAUNCH_FN), ctypes.POINTER(vp), u32, u32,
                                       ctypes.POINTER(EvoTimingOpts), vp, vp, ctypes.POINTER(f32)]
@@ -104,7 +105,7 @@ def _load() -> ctypes.CDLL:
     h.evo_strerror.argtypes = [ctypes.c_int]
     h.evo_strerror.restype = ctypes.c_char_p
     for name in ("evo_check_create", "evo_check_batch", "evo_check_segmented", "evo_check_cases",
-                 "evo_fitness", "evo_fitness_ex", "evo_select_elite", "evo_time_candidates", "evo_evaluate",
+                 "evo_fitness", "evo_fitness_ex", "evo_select_elite", "evo_time_candidates", "evo_evaluate", "evo_select_elite_diverse",
                  "evo_check_destroy"):
         getattr(h, name).restype = ctypes.c_int
     return h
@@ -204,6 +205,13 @@ def evo_fitness_ex(ctx: int, timings, baseline, P: int, T: int, reducer: int, st
         raise EvoError(rc, "evo_fitness_ex")
 
 
+def evo_select_elite_diverse(ctx: int, stats, keys, P: int, k: int, stream, elite, n_elite=None) -> None:
+    rc = lib.evo_select_elite_diverse(ctx, _ptr(stats), _ptr(keys), int(P), int(k), _stream(stream),
+                                      _ptr(elite), _ptr(n_elite))
+    if rc != 0:
+        raise EvoError(rc, "evo_select_elite_diverse")
+
+
 def evo_evaluate(ctx: int, cases: Sequence[dict], K: int, timings, baseline, T: int, reducer: int,
                  stream, stats, summary=None) -> None:
     """``cases`` as for evo_check_cases."""
@@ -301,6 +309,13 @@ class Checker:
         else:
             evo_fitness_ex(self.ctx, timings, baseline, P, T, reducer, st, stats, summary)
 
+
+    def select_elite_diverse(self, stats: torch.Tensor, keys: torch.Tensor, P: int, k: int,
+                             elite: torch.Tensor, n_elite: Optional[torch.Tensor] = None,
+                             stream=None) -> None:
+        evo_select_elite_diverse(self.ctx, stats, keys, P, k,
+                                 stream if stream is not None else torch.cuda.current_stream(), elite,
+                                 n_elite)
 
     def evaluate(self, cases: Sequence[dict], timings: torch.Tensor, baseline: torch.Tensor,
                  stats: torch.Tensor, summary: Optional[torch.Tensor] = None, stream=None,

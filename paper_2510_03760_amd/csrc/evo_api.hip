@@ -52,6 +52,8 @@ struct evo_check {
     uint32_t *d_fit_ticket = nullptr;
     float *d_fit_rows = nullptr;     // (median, mean) pairs of evo_evaluate
     size_t fit_rows_count = 0;
+    uint32_t *d_rep = nullptr;       // key representatives of evo_select_elite_diverse
+    size_t rep_count = 0;
     StageSlot slots[kStageSlots];
     int next_slot = 0;
     // timing stage (evo_time_candidates)
@@ -475,6 +477,28 @@ int evo_select_elite(evo_check_t *c, const evo_stats *stats, uint32_t P, uint32_
     return dev(evo::launch_select(stats, P, k, elite, n_elite, static_cast<hipStream_t>(stream)));
 }
 
+int evo_select_elite_diverse(evo_check_t *c, const evo_stats *stats, const uint32_t *keys, uint32_t P,
+                             uint32_t k, void *stream, uint32_t *elite, uint32_t *n_elite) {
+    if (!is_live(c)) return EVO_ERR_HANDLE;
+    if (!stats || !keys || !elite) return EVO_ERR_NULL;
+    if (P == 0 || k == 0 || k > P || P > kMaxP) return EVO_ERR_SIZE;
+    if ((reinterpret_cast<uintptr_t>(stats) & 7u) || (reinterpret_cast<uintptr_t>(keys) & 3u) ||
+        (reinterpret_cast<uintptr_t>(elite) & 3u) || (reinterpret_cast<uintptr_t>(n_elite) & 3u))
+        return EVO_ERR_ALIGN;
+    const int rc = bind_device(c);
+    if (rc != EVO_OK) return rc;
+    if (P > c->rep_count) {
+        if (c->d_rep) EVO_TRY(hipFree(c->d_rep));
+        c->d_rep = nullptr;
+        c->rep_count = 0;
+        const size_t cap = std::max<size_t>(2 * (size_t)P, 1024);
+        EVO_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_rep), cap * sizeof(uint32_t)));
+        c->rep_count = cap;
+    }
+    return dev(evo::launch_select_diverse(stats, keys, c->d_rep, P, k, elite, n_elite,
+                                          static_cast<hipStream_t>(stream)));
+}
+
 int evo_evaluate(evo_check_t *c, const evo_segment *cases, uint32_t K, const float *timings,
                  const float *baseline, uint32_t T, int reducer, void *stream, evo_stats *stats,
                  evo_pop_summary *summary) {
@@ -604,6 +628,7 @@ int evo_check_destroy(evo_check_t *c) {
         if (c->d_tickets) (void)hipFree(c->d_tickets);
         if (c->d_base_median) (void)hipFree(c->d_base_median);
         if (c->d_fit_rows) (void)hipFree(c->d_fit_rows);
+        if (c->d_rep) (void)hipFree(c->d_rep);
         for (StageSlot &s : c->slots) {
             if (s.host) (void)hipHostFree(s.host);
             if (s.done) (void)hipEventDestroy(s.done);

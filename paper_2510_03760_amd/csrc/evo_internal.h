@@ -208,6 +208,11 @@ hipError_t launch_fitness(const float *timings, const float *baseline, uint32_t 
 hipError_t launch_select(const evo_stats *stats, uint32_t P, uint32_t k, uint32_t *elite,
                          uint32_t *n_elite, hipStream_t stream);
 
+// The same with one key per candidate and no two selected candidates sharing a key.
+// rep: P words of device scratch.
+hipError_t launch_select_diverse(const evo_stats *stats, const uint32_t *keys, uint32_t *rep, uint32_t P,
+                                 uint32_t k, uint32_t *elite, uint32_t *n_elite, hipStream_t stream);
+
 // Timing stage helpers: overwrite `bytes` of `buf` (a multiple of 4) with `value`; run a
 // fixed chain of `iterations` dependent FMAs in one wavefront (sink: 4 bytes of scratch).
 hipError_t launch_flush(void *buf, size_t bytes, uint32_t value, hipStream_t stream);

@@ -28,6 +28,8 @@ hipError_t launch_select(const evo_stats *, uint32_t, uint32_t, uint32_t *, uint
     ++g_launches;
     return hipSuccess;
 }
+hipError_t launch_select_diverse(const evo_stats *, const uint32_t *, uint32_t *, uint32_t, uint32_t, uint32_t *,
+                                 uint32_t *, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_evaluate(uint32_t, const InlineTable &, uint32_t, uint32_t, float, float, uint32_t, Partial *,
                            uint32_t *, evo_stats *, const FitLaunch &, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_flush(void *, size_t, uint32_t, hipStream_t) { ++g_launches; return hipSuccess; }
@@ -248,6 +250,17 @@ static void validation_cases() {
     EXPECT(evo_select_elite(c, stats, 65536, 4, nullptr, elite, nullptr) == EVO_ERR_SIZE);
     EXPECT(evo_select_elite(c, stats, 3, 2, nullptr, reinterpret_cast<uint32_t *>(arena + 3602),
                             nullptr) == EVO_ERR_ALIGN);
+
+    {
+        const uint32_t *keys = reinterpret_cast<const uint32_t *>(arena + 3700);
+        EXPECT(evo_select_elite_diverse(nullptr, stats, keys, 3, 2, nullptr, elite, nullptr) == EVO_ERR_HANDLE);
+        EXPECT(evo_select_elite_diverse(c, stats, nullptr, 3, 2, nullptr, elite, nullptr) == EVO_ERR_NULL);
+        EXPECT(evo_select_elite_diverse(c, nullptr, keys, 3, 2, nullptr, elite, nullptr) == EVO_ERR_NULL);
+        EXPECT(evo_select_elite_diverse(c, stats, keys, 3, 0, nullptr, elite, nullptr) == EVO_ERR_SIZE);
+        EXPECT(evo_select_elite_diverse(c, stats, keys, 3, 4, nullptr, elite, nullptr) == EVO_ERR_SIZE);
+        EXPECT(evo_select_elite_diverse(c, stats, reinterpret_cast<const uint32_t *>(arena + 3701), 3, 2,
+                                        nullptr, elite, nullptr) == EVO_ERR_ALIGN);
+    }
 
     // evaluation in one call
     EXPECT(evo_evaluate(nullptr, cs, 2, tim, base, 5, 0, nullptr, stats, pop) == EVO_ERR_HANDLE);

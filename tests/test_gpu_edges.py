@@ -471,6 +471,44 @@ def test_select_elite(gu, P, k):
         chk.close()
 
 
+@pytest.mark.parametrize("P,k,nkeys", [(1, 1, 1), (9, 4, 3), (256, 8, 30), (300, 300, 300), (1000, 64, 7),
+                                       (4097, 100, 500), (65535, 300, 2000)])
+def test_select_elite_diverse(gu, P, k, nkeys):
+    _say("elite diverse P=%d k=%d keys=%d" % (P, k, nkeys))
+    import oracle
+    import paper_2510_03760_amd as evo
+    rng = np.random.default_rng(P + k)
+    f = rng.choice(np.array([0, 0.5, 0.75, 1, 1.25, 2, np.inf], np.float32), P)
+    some = rng.random(P) < 0.4
+    f[some] = rng.random(int(some.sum())).astype(np.float32)
+    keys = (rng.integers(0, nkeys, P).astype(np.uint32) * np.uint32(2654435761))
+    chk = evo.Checker(evo.EVO_F32, 1, 0.0, 0.0)
+    stats = chk.new_stats(P)
+    view = stats.view(P, 72)
+    view[:, 60:64] = torch.from_numpy(f.view(np.uint8).copy()).to("cuda").view(P, 4)
+    dkeys = torch.from_numpy(keys.view(np.int32).copy()).to("cuda")
+    elite = torch.full((k + 2,), -7, dtype=torch.int32, device="cuda")
+    n_elite = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    for _ in range(2):                                   # second call reuses the scratch
+        chk.select_elite_diverse(stats, dkeys, P, k, elite[1:k + 1], n_elite)
+    torch.cuda.synchronize()
+    want = oracle.select_elite_diverse(f, keys, k)
+    assert elite[1:k + 1].cpu().numpy().astype(np.uint32).tolist() == want["elite"].tolist()
+    assert int(n_elite[0]) == want["n_elite"]
+    assert int(elite[0]) == -7 and int(elite[k + 1]) == -7
+    chosen = [int(i) for i in want["elite"] if i < P]
+    assert len(set(int(keys[i]) for i in chosen)) == len(chosen)
+    # all keys different: the plain selection
+    uniq = torch.arange(P, dtype=torch.int32, device="cuda")
+    plain = torch.zeros(k, dtype=torch.int32, device="cuda")
+    div = torch.zeros(k, dtype=torch.int32, device="cuda")
+    chk.select_elite(stats, P, k, plain)
+    chk.select_elite_diverse(stats, uniq, P, k, div)
+    torch.cuda.synchronize()
+    assert torch.equal(plain, div)
+    chk.close()
+
+
 def test_errors_on_live_device(gu):
     """Argument errors are reported before anything is enqueued, also with a GPU."""
     _say("errors")
