@@ -8,6 +8,9 @@ Two stand-alone drivers under tests/native/ are compiled and run here:
                    populations against the invariants the kernel's indexing relies on
                    (hipcc; only the host pass is instrumented, kernels are stubbed out).
 
+* tsan_api.cpp  -- contexts created, used and destroyed from four threads at once under
+                   ThreadSanitizer (the registry of live handles is the shared state).
+
 GPU code is not instrumented and no kernel is launched.
 """
 from __future__ import annotations
@@ -58,3 +61,21 @@ def test_c_abi_host_side_under_sanitizers(tmp_path):
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     assert res.returncode == 0, res.stdout[-4000:]
     assert "san_api: ok" in _run(exe)
+
+
+def test_c_abi_handles_from_several_threads_under_tsan(tmp_path):
+    hipcc = "/opt/rocm/bin/hipcc" if os.path.exists("/opt/rocm/bin/hipcc") else shutil.which("hipcc")
+    if not hipcc:
+        pytest.skip("hipcc not found")
+    exe = str(tmp_path / "tsan_api")
+    cmd = [hipcc, "-x", "hip", "--offload-arch=gfx950", "-std=c++17", "-O1", "-g",
+           "-Xarch_host", "-fsanitize=thread",
+           "-I", os.path.join(ROOT, "include"),
+           "-I", os.path.join(ROOT, "paper_2510_03760_amd", "csrc"),
+           "-o", exe, os.path.join(NATIVE, "tsan_api.cpp"), "-lpthread"]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert res.returncode == 0, res.stdout[-4000:]
+    run = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=300)
+    assert run.returncode == 0, run.stdout[-4000:]
+    assert "ThreadSanitizer" not in run.stdout, run.stdout[-4000:]
+    assert "tsan_api: ok" in run.stdout
