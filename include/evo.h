@@ -69,7 +69,8 @@ typedef enum {
     EVO_ERR_DTYPE  = -2, /* unknown element type                                */
     EVO_ERR_SIZE   = -3, /* zero or out-of-range count (n, P, S, T, rows)       */
     EVO_ERR_TOL    = -4, /* tolerance negative, NaN or infinite                 */
-    EVO_ERR_ALIGN  = -5, /* a tensor pointer is not aligned to its element size */
+    EVO_ERR_ALIGN  = -5, /* a tensor pointer is not aligned to its element size, or */
+                         /* an output pointer not to its record (stats: 8 bytes) */
     EVO_ERR_DEVICE = -6, /* a HIP call failed (no device, launch error, ...)    */
     EVO_ERR_NOMEM  = -7, /* host or device allocation failed                    */
     EVO_ERR_HANDLE = -8  /* not a live context (never created, or destroyed)    */
@@ -162,7 +163,8 @@ EVO_API int evo_check_create(evo_check_t **out, evo_dtype dtype, uint64_t n_elem
  *   stats      device, P rows, written by the enqueued work
  * Each reference element is fetched from memory once and compared with all P
  * candidates.  Tensor pointers must be aligned to the element size; 16-byte
- * alignment gives the fast path.
+ * alignment gives the fast path.  `stats` must be 8-byte aligned (here and in
+ * every other call that writes evo_stats rows).
  * Errors: EVO_ERR_HANDLE, EVO_ERR_NULL (ref, cand_ptrs, any cand_ptrs[i], stats),
  * EVO_ERR_SIZE (P == 0 or P > 65535), EVO_ERR_ALIGN, EVO_ERR_NOMEM, EVO_ERR_DEVICE.
  */
@@ -300,7 +302,7 @@ EVO_API int evo_select_elite_diverse(evo_check_t *c, const evo_stats *stats, con
  * scratch buffer on first use.
  * Errors: EVO_ERR_HANDLE, EVO_ERR_NULL (launch, any launch[p], timings, opts),
  * EVO_ERR_SIZE (P == 0, T == 0, T > EVO_FITNESS_MAX_T, P > 65535, warmup > 1000000),
- * EVO_ERR_ALIGN (timings), EVO_ERR_NOMEM, EVO_ERR_DEVICE.
+ * EVO_ERR_ALIGN (timings, clock_ratio), EVO_ERR_NOMEM, EVO_ERR_DEVICE.
  */
 typedef void (*evo_launch_fn)(void *user, void *stream);
 typedef struct evo_timing_opts {

@@ -215,7 +215,7 @@ void partition(const std::vector<HostSeg> &segs, uint32_t target_jobs, std::vect
         d.dtype = h.dtype;
         d.stats_row0 = h.row0;
         d.n_groups = evo::group_count(h.P);
-        d.gpw = std::min<uint32_t>(pow2_ceil(d.n_groups), evo::kWaves);
+        d.gpw = std::min<uint32_t>(pow2_ceil(d.n_groups), EVO_GPW_MAX);
         d.case0 = h.n_cases > 1 ? h.case0 : (uint32_t)s;
         d.n_cases = h.n_cases;
         const uint64_t tiles = (h.n + evo::tile_elems(h.dtype) - 1) / evo::tile_elems(h.dtype);
@@ -384,6 +384,7 @@ int evo_check_batch(evo_check_t *c, const void *ref, const void *const *cand_ptr
                     void *stream, evo_stats *stats) {
     if (!is_live(c)) return EVO_ERR_HANDLE;
     if (!stats) return EVO_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(stats) & 7u) return EVO_ERR_ALIGN;
     HostSeg h{ref, cand_ptrs, c->n_elems, P, (uint32_t)c->dtype, 0u, 0u, 1u};
     const int rc = validate_seg(h);
     if (rc != EVO_OK) return rc;
@@ -399,6 +400,7 @@ int evo_check_segmented(evo_check_t *c, const evo_segment *segs, uint32_t S, voi
                         evo_stats *stats, uint32_t n_rows) {
     if (!is_live(c)) return EVO_ERR_HANDLE;
     if (!segs || !stats) return EVO_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(stats) & 7u) return EVO_ERR_ALIGN;
     if (S == 0 || n_rows == 0) return EVO_ERR_SIZE;
     try {
         std::vector<HostSeg> hs(S);
@@ -425,6 +427,7 @@ int evo_check_cases(evo_check_t *c, const evo_segment *cases, uint32_t K, void *
                     evo_stats *stats) {
     if (!is_live(c)) return EVO_ERR_HANDLE;
     if (!cases || !stats) return EVO_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(stats) & 7u) return EVO_ERR_ALIGN;
     if (K == 0) return EVO_ERR_SIZE;
     try {
         std::vector<HostSeg> hs(K);
@@ -540,7 +543,8 @@ int evo_time_candidates(evo_check_t *c, const evo_launch_fn *launch, void *const
         return EVO_ERR_SIZE;
     for (uint32_t p = 0; p < P; ++p)
         if (!launch[p]) return EVO_ERR_NULL;
-    if (reinterpret_cast<uintptr_t>(timings) & 3u) return EVO_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(timings) & 3u) || (reinterpret_cast<uintptr_t>(clock_ratio) & 3u))
+        return EVO_ERR_ALIGN;
     int rc = bind_device(c);
     if (rc != EVO_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);

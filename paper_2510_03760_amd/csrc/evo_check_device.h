@@ -903,7 +903,21 @@ __device__ __forceinline__ void run_job(const SegDesc &sd, const uint64_t *ptr_t
     const uint64_t n = sd.n;
     const uint64_t n_full = n / kTileElems;                         // full tiles
     const uint64_t n_tiles = (n + kTileElems - 1) / kTileElems;     // with the ragged one
-    const TileWalk walk{sd.n_chunks, chunk, tpw, tl};
+    // Workgroups whose indices are congruent modulo 8 run on one XCD, and so do the chunks
+    // of a segment whose numbers are congruent modulo 8.  The chunks of such a class are
+    // placed side by side in the window, so that each XCD (each L2) streams one contiguous
+    // eighth of it.  Dealt round-robin instead, every address that an XCD touches during
+    // one step has the same bits 11..13 whenever a workgroup's share of the window is a
+    // single tile (four candidate groups side by side): 12 % slower on 64 bf16 candidates
+    // of 32 MiB each, 3 % on the ragged fp32 mix, no difference with four tiles per
+    // workgroup.
+#if EVO_XCD_BLOCKS
+    const uint32_t per_class = sd.n_chunks / 8u, longer = sd.n_chunks % 8u, cls = chunk % 8u;
+    const uint32_t place = cls * per_class + (cls < longer ? cls : longer) + chunk / 8u;
+#else
+    const uint32_t place = chunk;
+#endif
+    const TileWalk walk{sd.n_chunks, place, tpw, tl};
 
     if (lane < kG) {
         exact_acc[wave][lane] = ExactAcc{0.0, 0.0, 0.0f, 0.0f, 0u, 0u, 0u, 0u};

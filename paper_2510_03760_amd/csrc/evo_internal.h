@@ -34,6 +34,12 @@ namespace evo {
 #ifndef EVO_JOBS_PER_CU
 #define EVO_JOBS_PER_CU 2    // workgroups the partitioner creates per compute unit
 #endif
+#ifndef EVO_XCD_BLOCKS
+#define EVO_XCD_BLOCKS 1     // 1: the chunks of one XCD are neighbours in the window, 0: dealt round-robin
+#endif
+#ifndef EVO_GPW_MAX
+#define EVO_GPW_MAX 4        // most candidate groups one workgroup takes side by side (1, 2 or 4)
+#endif
 
 // Launch geometry of the check kernel.  A workgroup is 4 wavefronts of 64 lanes.
 // Each wavefront owns one group of candidates (a power of two, at most kG) and

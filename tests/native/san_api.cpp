@@ -172,6 +172,13 @@ static void validation_cases() {
     EXPECT(evo_check_batch(c, ref, cands, 65536, nullptr, stats) == EVO_ERR_SIZE);
     EXPECT(evo_check_batch(c, arena + 2, cands, 3, nullptr, stats) == EVO_ERR_ALIGN);
     {
+        evo_stats *odd = reinterpret_cast<evo_stats *>(reinterpret_cast<char *>(stats) + 4);
+        evo_segment one = {ref, cands, 100, 3, EVO_F32, 0, 0};
+        EXPECT(evo_check_batch(c, ref, cands, 3, nullptr, odd) == EVO_ERR_ALIGN);
+        EXPECT(evo_check_segmented(c, &one, 1, nullptr, odd, 3) == EVO_ERR_ALIGN);
+        EXPECT(evo_check_cases(c, &one, 1, nullptr, odd) == EVO_ERR_ALIGN);
+    }
+    {
         const void *bad[3] = {arena + 16, nullptr, arena + 48};
         EXPECT(evo_check_batch(c, ref, bad, 3, nullptr, stats) == EVO_ERR_NULL);
         bad[1] = arena + 33;
@@ -297,6 +304,8 @@ static void validation_cases() {
         EXPECT(evo_time_candidates(c, fns, nullptr, 2, 5, &silly, nullptr, tab, nullptr) == EVO_ERR_SIZE);
         EXPECT(evo_time_candidates(c, fns, nullptr, 2, 5, &opts, nullptr,
                                    reinterpret_cast<float *>(arena + 2050), nullptr) == EVO_ERR_ALIGN);
+        EXPECT(evo_time_candidates(c, fns, nullptr, 2, 5, &opts, nullptr, tab,
+                                   reinterpret_cast<float *>(arena + 2050)) == EVO_ERR_ALIGN);
         EXPECT(calls == 0);
     }
 
