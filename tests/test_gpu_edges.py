@@ -85,6 +85,23 @@ def test_population_sizes(gu, P):
         chk.close()
 
 
+@pytest.mark.parametrize("P", [3, 17, 40, 65])
+def test_every_chunk_count_up_to_24(gu, P):
+    """Sizes that give a segment 1, 2, ..., 24 chunks (so also counts that are not multiples
+    of the number of XCDs), with one, two and four candidate groups per workgroup: every tile
+    must be visited exactly once whatever the placement of chunks inside a window (a lost or
+    doubled tile changes n_finite and the sums)."""
+    groups = (P + 15) // 16 if P % 16 == 0 else P // 16 + bin(P % 16).count("1")
+    gpw = min(4, 1 << (groups - 1).bit_length())
+    tiles_per_chunk = 4 * (4 // gpw)        # smallest share of a wavefront x tile slots
+    for chunks in range(1, 25):
+        n = 512 * tiles_per_chunk * chunks - 300
+        _say("P=%d chunks=%d n=%d" % (P, chunks, n))
+        w = _mixed(n, P, 7000 + 31 * P + chunks, torch.float32, special=(chunks % 5 == 0))
+        chk, stats, want = gu.check_parity(w, label="chunks%d" % chunks)
+        chk.close()
+
+
 def test_reciprocal_shortcut_is_exact_on_this_device(gu):
     """The kernel's 1/|r| shortcut (rcp + one FMA Newton step) equals the correctly rounded
     division for every binary32 input it is used on; checked exhaustively on the device."""
