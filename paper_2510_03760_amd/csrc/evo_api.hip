@@ -198,15 +198,66 @@ uint32_t pow2_ceil(uint32_t v) {
     return p;
 }
 
-// Splits every segment into jobs (workgroups) of similar cost.  Cost unit: one
-// wavefront pass over one tile with one candidate group.  The launch is sized to the
-// machine (a fixed number of workgroups per compute unit, all resident at once), so
-// that the per-job epilogue -- cross-lane reduction, partial rows, ticket -- is paid
-// once per wavefront slot and not once per few tiles.
+// What one step of a workgroup costs, in tile loads: its largest candidate group plus the
+// reference.  A single candidate keeps one tile less in flight than the load pipeline
+// holds, and its steps were measured 1.2x slower than their bytes: counted as 3.
+uint32_t step_cost(uint32_t P) {
+    uint32_t b = evo::kG;
+    if (P < (uint32_t)evo::kG)
+        for (b = 1; b * 2 <= P;) b *= 2;
+    return std::max<uint32_t>(b + 1, 3u);
+}
+
+// Share of a layout's wavefront slots that hold a full candidate group.
+double full_share(uint32_t n_full, uint32_t n_groups) {
+    const uint32_t gpw = std::min<uint32_t>(pow2_ceil(n_groups), EVO_GPW_MAX);
+    const uint32_t slots = (n_groups + gpw - 1) / gpw * gpw;
+    return (double)n_full / slots;
+}
+
+// A population whose size is not a multiple of the group size ends in one to four smaller
+// groups.  Where those take wavefront slots that full groups could have had (17 candidates:
+// one full group beside a single candidate, so half of all wavefronts idle most of the time
+// and the launch runs at 0.74 of the 16-candidate rate; 33 bf16 candidates: 0.62), the
+// segment is cut in two: the full groups, and the rest as a segment of its own whose jobs
+// the partitioner sizes by their cost (33 candidates: 0.76).  The price is a second read
+// of the reference (1/(P+1) more bytes), so a segment stays whole where the small groups
+// ride in slots that would be empty anyway (100 candidates = 6 full groups + 4: 0.83 whole,
+// 0.74 cut), where it is short, and in case groups (one accumulator over several segments).
+constexpr uint64_t kSplitMinTiles = 1024;
+
+void split_remainders(const std::vector<HostSeg> &in, std::vector<HostSeg> &out) {
+    out.clear();
+    out.reserve(in.size() * 2);
+    for (const HostSeg &h : in) {
+        const uint32_t rem = h.P % (uint32_t)evo::kG, n_full = h.P / (uint32_t)evo::kG;
+        const uint64_t tiles = (h.n + evo::tile_elems(h.dtype) - 1) / evo::tile_elems(h.dtype);
+        const bool gains = n_full > 0 && rem != 0 &&
+                           full_share(n_full, n_full) - full_share(n_full, evo::group_count(h.P)) >= 0.25;
+        if (h.n_cases > 1 || !gains || tiles < kSplitMinTiles) {
+            out.push_back(h);
+            continue;
+        }
+        HostSeg full = h, rest = h;
+        full.P = h.P - rem;
+        rest.P = rem;
+        rest.cand_ptrs = h.cand_ptrs + full.P;
+        rest.row0 = h.row0 + full.P;
+        out.push_back(full);
+        out.push_back(rest);
+    }
+}
+
+// Splits every segment into jobs (workgroups) of similar cost.  Cost unit: one tile load
+// of one wavefront; a step of a workgroup costs its largest candidate group plus the
+// reference.  The launch is sized to the machine (a fixed number of workgroups per
+// compute unit, all resident at once), so that the per-job epilogue -- cross-lane
+// reduction, partial rows, ticket -- is paid once per wavefront slot and not once per few
+// tiles.
 void partition(const std::vector<HostSeg> &segs, uint32_t target_jobs, std::vector<SegDesc> &descs,
                uint32_t &total_jobs) {
     descs.resize(segs.size());
-    uint64_t wave_tiles = 0;
+    uint64_t cost = 0;   // summed over all jobs: steps x cost of a step
     for (size_t s = 0; s < segs.size(); ++s) {
         const HostSeg &h = segs[s];
         SegDesc &d = descs[s];
@@ -219,13 +270,13 @@ void partition(const std::vector<HostSeg> &segs, uint32_t target_jobs, std::vect
         d.case0 = h.n_cases > 1 ? h.case0 : (uint32_t)s;
         d.n_cases = h.n_cases;
         const uint64_t tiles = (h.n + evo::tile_elems(h.dtype) - 1) / evo::tile_elems(h.dtype);
-        wave_tiles += tiles * d.n_groups;
+        const uint32_t tpw = evo::kWaves / d.gpw;
+        const uint32_t gblocks = (d.n_groups + d.gpw - 1) / d.gpw;
+        cost += (tiles + tpw - 1) / tpw * gblocks * step_cost(h.P);
     }
-    // tiles one wavefront should take per job
-    uint64_t per_wave = (wave_tiles + (uint64_t)target_jobs * evo::kWaves - 1) /
-                        ((uint64_t)target_jobs * evo::kWaves);
-    per_wave = std::min<uint64_t>(std::max<uint64_t>(per_wave, kMinTilesPerWave),
-                                  evo::kMaxTilesPerWave);
+    // cost one job should take
+    uint64_t per_job = (cost + target_jobs - 1) / target_jobs;
+    if (per_job == 0) per_job = 1;
     // The rounding up per segment can push the total past the number of workgroups the
     // machine holds at once, and the surplus would run as a second round after everything
     // else: coarsen until the launch fits (it cannot when there are more segments than
@@ -233,10 +284,17 @@ void partition(const std::vector<HostSeg> &segs, uint32_t target_jobs, std::vect
     uint32_t job0 = 0;
     for (int attempt = 0; attempt < 64; ++attempt) {
         job0 = 0;
+        bool any_free = false;   // some segment could still take longer jobs
         for (size_t s = 0; s < segs.size(); ++s) {
             SegDesc &d = descs[s];
             const uint64_t tiles = (d.n + evo::tile_elems(d.dtype) - 1) / evo::tile_elems(d.dtype);
             const uint32_t tpw = evo::kWaves / d.gpw;
+            const uint32_t per_step = step_cost(d.P);
+            // tiles one wavefront takes per job
+            uint64_t per_wave = (per_job + per_step - 1) / per_step;
+            per_wave = std::max<uint64_t>(per_wave, kMinTilesPerWave);
+            if (per_wave < evo::kMaxTilesPerWave) any_free = true;
+            else per_wave = evo::kMaxTilesPerWave;
             const uint64_t per_chunk = per_wave * tpw;
             const uint64_t chunks = (tiles + per_chunk - 1) / per_chunk;
             d.n_chunks = (uint32_t)chunks;
@@ -245,10 +303,9 @@ void partition(const std::vector<HostSeg> &segs, uint32_t target_jobs, std::vect
             d.job0 = job0;
             job0 += d.n_jobs;
         }
-        if (job0 <= target_jobs || per_wave >= evo::kMaxTilesPerWave) break;
-        // next candidate: scale by the overshoot, at least one tile more
-        per_wave = std::min<uint64_t>(std::max<uint64_t>(per_wave + 1, per_wave * job0 / target_jobs),
-                                      evo::kMaxTilesPerWave);
+        if (job0 <= target_jobs || !any_free) break;
+        // next candidate: scale by the overshoot, at least one unit more
+        per_job = std::max<uint64_t>(per_job + 1, per_job * job0 / target_jobs);
     }
     total_jobs = job0;
 }
@@ -268,10 +325,16 @@ bool partition_fits(const std::vector<HostSeg> &segs) {
 
 // fit: when given, the timing reduction is part of the same work (evo_evaluate): one launch
 // when the table fits the kernel argument block, else the check and then the fitness kernel.
-int run_check(evo_check *c, const std::vector<HostSeg> &segs, hipStream_t stream,
+int run_check(evo_check *c, const std::vector<HostSeg> &whole, hipStream_t stream,
               evo_stats *stats, const evo::FitLaunch *fit = nullptr) {
     int rc = bind_device(c);
     if (rc != EVO_OK) return rc;
+    std::vector<HostSeg> segs;
+    try {
+        split_remainders(whole, segs);
+    } catch (const std::bad_alloc &) {
+        return EVO_ERR_NOMEM;
+    }
 
     if (c->n_cus == 0) {
         int cus = 0;
@@ -318,9 +381,13 @@ int run_check(evo_check *c, const std::vector<HostSeg> &segs, hipStream_t stream
             for (uint32_t p = 0; p < segs[s].P; ++p)
                 tab.ptrs[descs[s].ptr0 + p] = reinterpret_cast<uint64_t>(segs[s].cand_ptrs[p]);
         }
-        if (fit)
+        if (fit) {
+            // one case group writes its rows once; independent segments write theirs each
+            evo::FitLaunch f = *fit;
+            f.writers = segs[0].n_cases > 1 ? 1u : (uint32_t)S;
             return dev(evo::launch_evaluate(dtype_set, tab, (uint32_t)S, total_jobs, c->atol, c->rtol,
-                                            c->n_cus, c->d_partials, c->d_tickets, stats, *fit, stream));
+                                            c->n_cus, c->d_partials, c->d_tickets, stats, f, stream));
+        }
         return dev(evo::launch_check_inline(dtype_set, tab, (uint32_t)S, total_jobs, c->atol, c->rtol,
                                             c->n_cus, c->d_partials, c->d_tickets, stats, stream));
     }
@@ -527,7 +594,7 @@ int evo_evaluate(evo_check_t *c, const evo_segment *cases, uint32_t K, const flo
         if ((rc = ensure_fitness_scratch(c, st)) != EVO_OK) return rc;
         if ((rc = ensure_fit_rows(c, cases[0].P_s)) != EVO_OK) return rc;
         const evo::FitLaunch fit{timings, baseline, summary, c->d_base_median, c->d_fit_rows,
-                                 c->d_fit_ticket, cases[0].P_s, T, (uint32_t)reducer};
+                                 c->d_fit_ticket, cases[0].P_s, T, (uint32_t)reducer, 1u};
         return run_check(c, hs, st, stats, &fit);
     } catch (const std::bad_alloc &) {
         return EVO_ERR_NOMEM;

@@ -1349,9 +1349,9 @@ evo_check_kernel_inline(const InlineTable /*read via the segment pointer*/, uint
 // and the timing reduction of evo_fitness_kernel.  The first P + 1 workgroups of the grid
 // reduce the timing rows (they take microseconds and free their slots for check jobs); the
 // others are check jobs.  Speedup, fitness and the population figures need every median and
-// every valid flag: each timing workgroup and the workgroup that writes the evo_stats rows
-// take a ticket, and whoever draws the last of the P + 2 does the rest.  Only for launches
-// with one result-writing event: one segment, or one case group.
+// every valid flag: each timing workgroup and every workgroup that writes evo_stats rows (one
+// per case group, else one per segment; `writers` in all) take a ticket, and whoever draws
+// the last of the P + 1 + writers does the rest.
 struct FitArgs {
     const float *timings;
     const float *baseline;
@@ -1360,6 +1360,7 @@ struct FitArgs {
     float *rows;          // P (median, mean) pairs of scratch
     uint32_t *ticket;     // zero between launches
     uint32_t P, T, reducer;
+    uint32_t writers;     // workgroups whose check_body returns true
 };
 
 template <uint32_t DTS>
@@ -1373,7 +1374,7 @@ evo_evaluate_kernel(const InlineTable /*read via the segment pointer*/, uint32_t
     if (blockIdx.x < n_rows) {
         // the pairs go to scratch: the evo_stats rows are written whole, later, by the check
         last = fitness_row_and_ticket(fit.timings, fit.baseline, blockIdx.x, fit.P, fit.T, stats, fit.rows,
-                                      fit.base, fit.ticket, n_rows);
+                                      fit.base, fit.ticket, n_rows + fit.writers - 1u);
     } else {
         if (!check_body<DTS>(tab->descs, tab->ptrs, S, atol, rtol, n_first, blockIdx.x - n_rows,
                              gridDim.x - n_rows, partials, tickets, stats))
@@ -1383,7 +1384,7 @@ evo_evaluate_kernel(const InlineTable /*read via the segment pointer*/, uint32_t
         if (threadIdx.x == 0) {
             const uint32_t prev = __hip_atomic_fetch_add(fit.ticket, 1u, __ATOMIC_ACQ_REL,
                                                          __HIP_MEMORY_SCOPE_AGENT);
-            drew_last = (prev == n_rows) ? 1u : 0u;
+            drew_last = (prev == n_rows + fit.writers - 1u) ? 1u : 0u;
         }
         __syncthreads();
         last = drew_last != 0;
@@ -1420,7 +1421,8 @@ template <uint32_t DTS>
 hipError_t launch_evaluate_for(const InlineTable &tab, uint32_t S, uint32_t total_jobs, float atol,
                                float rtol, uint32_t n_first, Partial *partials, uint32_t *tickets,
                                evo_stats *stats, const FitLaunch &f, hipStream_t stream) {
-    const FitArgs fit{f.timings, f.baseline, f.summary, f.base, f.rows, f.ticket, f.P, f.T, f.reducer};
+    const FitArgs fit{f.timings, f.baseline, f.summary, f.base, f.rows, f.ticket, f.P, f.T, f.reducer,
+                      f.writers};
     hipLaunchKernelGGL(evo_evaluate_kernel<DTS>, dim3(total_jobs + f.P + 1), dim3(kThreads), 0, stream,
                        tab, S, atol, rtol, n_first, partials, tickets, stats, fit);
     return hipGetLastError();

@@ -182,6 +182,7 @@ struct FitLaunch {
     float *rows;          // 2 * P floats of device scratch
     uint32_t *ticket;     // device, zero between launches
     uint32_t P, T, reducer;
+    uint32_t writers;     // workgroups that write evo_stats rows (one per segment or case group)
 };
 hipError_t launch_evaluate(uint32_t dtype_set, const InlineTable &tab, uint32_t S, uint32_t total_jobs,
                            float atol, float rtol, uint32_t n_first, Partial *partials,

@@ -125,6 +125,83 @@ static void partition_cases() {
     EXPECT(!partition_fits(std::vector<HostSeg>(1, h)));
 }
 
+// split_remainders(): a segment stays whole or is cut in two; the parts cover its
+// candidates and rows once, in order; case groups, populations below one full group,
+// multiples of the group size and short segments stay whole; 17, 33 and 65 candidates are
+// cut, 100 are not.  And partition() sizes jobs by cost: of two equally long segments the
+// one with 16 candidates gets 17/3 times the jobs of the one with a single candidate.
+static void split_cases() {
+    static const void *ptrs[70000];
+    for (int it = 0; it < 2000; ++it) {
+        const uint32_t S = 1 + (uint32_t)(rng() % 6);
+        std::vector<HostSeg> segs(S), out;
+        uint32_t row0 = 0;
+        for (HostSeg &h : segs) {
+            h.n = 1 + rng() % (1ull << (int)(rng() % 28));
+            h.P = rng() % 4 == 0 ? 1 + (uint32_t)(rng() % kMaxP) : 1 + (uint32_t)(rng() % 70);
+            h.dtype = (uint32_t)(rng() % 6);
+            h.ref = ptrs;
+            h.cand_ptrs = ptrs;
+            h.row0 = row0;
+            h.n_cases = rng() % 5 == 0 ? 3u : 1u;
+            row0 += h.P;
+        }
+        split_remainders(segs, out);
+        size_t o = 0;
+        for (const HostSeg &h : segs) {
+            const uint64_t te = evo::tile_elems(h.dtype);
+            const bool must_stay = h.n_cases > 1 || h.P < 16 || h.P % 16 == 0 || (h.n + te - 1) / te < 1024;
+            EXPECT(o < out.size());
+            if (out[o].P == h.P) {
+                EXPECT(out[o].row0 == h.row0 && out[o].cand_ptrs == h.cand_ptrs);
+                EXPECT(out[o].n == h.n && out[o].dtype == h.dtype && out[o].n_cases == h.n_cases);
+                o += 1;
+            } else {
+                EXPECT(!must_stay);
+                EXPECT(o + 1 < out.size());
+                if (o + 1 >= out.size()) break;
+                const HostSeg &a = out[o], &b = out[o + 1];
+                EXPECT(a.P % 16 == 0 && a.P > 0 && b.P > 0 && b.P < 16 && a.P + b.P == h.P);
+                EXPECT(a.row0 == h.row0 && b.row0 == h.row0 + a.P);
+                EXPECT(a.cand_ptrs == h.cand_ptrs && b.cand_ptrs == h.cand_ptrs + a.P);
+                EXPECT(a.ref == h.ref && b.ref == h.ref && a.n == h.n && b.n == h.n);
+                EXPECT(a.dtype == h.dtype && b.dtype == h.dtype && a.n_cases == 1 && b.n_cases == 1);
+                o += 2;
+            }
+        }
+        EXPECT(o == out.size());
+    }
+    {
+        const uint32_t Ps[] = {17, 33, 65, 100, 49, 32, 12};
+        const size_t parts[] = {2, 2, 2, 1, 1, 1, 1};
+        for (int i = 0; i < 7; ++i) {
+            HostSeg h{};
+            h.n = 1ull << 24;
+            h.P = Ps[i];
+            h.dtype = EVO_F32;
+            h.ref = ptrs;
+            h.cand_ptrs = ptrs;
+            h.n_cases = 1;
+            std::vector<HostSeg> out;
+            split_remainders(std::vector<HostSeg>(1, h), out);
+            EXPECT(out.size() == parts[i]);
+        }
+    }
+    HostSeg a{}, b{};
+    a.n = b.n = 1ull << 26;
+    a.dtype = b.dtype = EVO_F32;
+    a.n_cases = b.n_cases = 1;
+    a.P = 16;
+    b.P = 1;
+    b.row0 = 16;
+    std::vector<HostSeg> two{a, b};
+    std::vector<SegDesc> d;
+    uint32_t total = 0;
+    partition(two, 512, d, total);
+    EXPECT(total <= 512 && total >= 500);
+    EXPECT(d[0].n_jobs > 5 * d[1].n_jobs && d[0].n_jobs < 6 * d[1].n_jobs);
+}
+
 static void group_cases() {
     for (uint32_t P = 1; P <= 300; ++P) {
         const uint32_t G = evo::group_count(P);
@@ -349,6 +426,7 @@ static void validation_cases() {
 int main() {
     group_cases();
     partition_cases();
+    split_cases();
     validation_cases();
     std::puts(g_fail ? "san_api: FAILED" : "san_api: ok");
     return g_fail ? 1 : 0;

@@ -48,6 +48,8 @@ def _cases(K, n, P, dtype, seed):
     (3, 200001, 21, torch.float16, 7, 1),
     (5, 60001, 100, torch.float32, 100, 0),       # 500 pointers: two launches, same results
     (9, 30001, 8, torch.float32, 64, 0),          # 9 cases: two launches
+    (1, 700001, 33, torch.float32, 100, 0),       # cut into 32 + 1 candidates: two writers of rows
+    (1, 1200001, 37, torch.bfloat16, 9, 1),       # 32 + 5
 ])
 def test_evaluate_equals_check_then_fitness(gu, K, n, P, dtype, T, reducer):
     _say("evaluate K=%d n=%d P=%d %s T=%d reducer=%d" % (K, n, P, dtype, T, reducer))
