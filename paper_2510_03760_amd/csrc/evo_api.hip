@@ -208,22 +208,33 @@ uint32_t step_cost(uint32_t P) {
     return std::max<uint32_t>(b + 1, 3u);
 }
 
-// Share of a layout's wavefront slots that hold a full candidate group.
-double full_share(uint32_t n_full, uint32_t n_groups) {
-    const uint32_t gpw = std::min<uint32_t>(pow2_ceil(n_groups), EVO_GPW_MAX);
-    const uint32_t slots = (n_groups + gpw - 1) / gpw * gpw;
-    return (double)n_full / slots;
+// The candidates beyond the last full group would be up to four groups of different sizes
+// side by side, and the wavefronts of the small ones would idle while the largest works
+// (7 bf16 candidates as 4 + 2 + 1: 0.47 of peak, 15 as 8 + 4 + 2 + 1: 0.54).  They are
+// walked as ONE group of the next power of two instead, the missing candidates standing in
+// as copies of the reference pointer: their loads hit the cache behind the reference's
+// own, their statistics are computed and dropped.
+uint32_t padded_population(uint32_t P) {
+    const uint32_t rem = P % (uint32_t)evo::kG;
+    return P - rem + (rem ? pow2_ceil(rem) : 0u);
 }
 
-// A population whose size is not a multiple of the group size ends in one to four smaller
-// groups.  Where those take wavefront slots that full groups could have had (17 candidates:
-// one full group beside a single candidate, so half of all wavefronts idle most of the time
-// and the launch runs at 0.74 of the 16-candidate rate; 33 bf16 candidates: 0.62), the
-// segment is cut in two: the full groups, and the rest as a segment of its own whose jobs
-// the partitioner sizes by their cost (33 candidates: 0.76).  The price is a second read
-// of the reference (1/(P+1) more bytes), so a segment stays whole where the small groups
-// ride in slots that would be empty anyway (100 candidates = 6 full groups + 4: 0.83 whole,
-// 0.74 cut), where it is short, and in case groups (one accumulator over several segments).
+// Share of a layout's wavefront slots that hold a group of at least half the full size.
+double heavy_share(uint32_t n_heavy, uint32_t n_groups) {
+    const uint32_t gpw = std::min<uint32_t>(pow2_ceil(n_groups), EVO_GPW_MAX);
+    const uint32_t slots = (n_groups + gpw - 1) / gpw * gpw;
+    return (double)n_heavy / slots;
+}
+
+// A small last group (1, 2 or 4 candidates) beside full groups leaves its wavefront idle
+// most of the time.  Where that costs a quarter or more of the wavefront slots (17
+// candidates: one full group beside a single candidate, 0.74 of the 16-candidate rate; 33
+// bf16 candidates: 0.62), the segment is cut in two: the full groups, and the rest as a
+// segment of its own whose jobs the partitioner sizes by their cost (33 candidates: 0.75).
+// The price is a second read of the reference (1/(P+1) more bytes), so a segment stays
+// whole where the small group rides in a slot that would be empty anyway (100 candidates =
+// 6 full groups + 4: 0.83 whole, 0.74 cut), where it is short, and in case groups (one
+// accumulator over several segments).
 constexpr uint64_t kSplitMinTiles = 1024;
 
 void split_remainders(const std::vector<HostSeg> &in, std::vector<HostSeg> &out) {
@@ -232,8 +243,8 @@ void split_remainders(const std::vector<HostSeg> &in, std::vector<HostSeg> &out)
     for (const HostSeg &h : in) {
         const uint32_t rem = h.P % (uint32_t)evo::kG, n_full = h.P / (uint32_t)evo::kG;
         const uint64_t tiles = (h.n + evo::tile_elems(h.dtype) - 1) / evo::tile_elems(h.dtype);
-        const bool gains = n_full > 0 && rem != 0 &&
-                           full_share(n_full, n_full) - full_share(n_full, evo::group_count(h.P)) >= 0.25;
+        const bool gains = n_full > 0 && rem != 0 && rem <= (uint32_t)evo::kG / 4 &&
+                           heavy_share(n_full, n_full) - heavy_share(n_full, n_full + 1) >= 0.25;
         if (h.n_cases > 1 || !gains || tiles < kSplitMinTiles) {
             out.push_back(h);
             continue;
@@ -262,17 +273,18 @@ void partition(const std::vector<HostSeg> &segs, uint32_t target_jobs, std::vect
         const HostSeg &h = segs[s];
         SegDesc &d = descs[s];
         d.n = h.n;
-        d.P = h.P;
+        d.P = padded_population(h.P);
+        d.n_pad = (uint16_t)(d.P - h.P);
         d.dtype = h.dtype;
         d.stats_row0 = h.row0;
-        d.n_groups = evo::group_count(h.P);
-        d.gpw = std::min<uint32_t>(pow2_ceil(d.n_groups), EVO_GPW_MAX);
+        d.n_groups = evo::group_count(d.P);
+        d.gpw = (uint16_t)std::min<uint32_t>(pow2_ceil(d.n_groups), EVO_GPW_MAX);
         d.case0 = h.n_cases > 1 ? h.case0 : (uint32_t)s;
         d.n_cases = h.n_cases;
         const uint64_t tiles = (h.n + evo::tile_elems(h.dtype) - 1) / evo::tile_elems(h.dtype);
         const uint32_t tpw = evo::kWaves / d.gpw;
         const uint32_t gblocks = (d.n_groups + d.gpw - 1) / d.gpw;
-        cost += (tiles + tpw - 1) / tpw * gblocks * step_cost(h.P);
+        cost += (tiles + tpw - 1) / tpw * gblocks * step_cost(d.P);
     }
     // cost one job should take
     uint64_t per_job = (cost + target_jobs - 1) / target_jobs;
@@ -352,9 +364,9 @@ int run_check(evo_check *c, const std::vector<HostSeg> &whole, hipStream_t strea
         return EVO_ERR_NOMEM;
     }
     uint32_t dtype_set = 0;
-    for (const HostSeg &h : segs) {
-        total_ptrs += h.P;
-        dtype_set |= 1u << h.dtype;
+    for (size_t s = 0; s < segs.size(); ++s) {
+        total_ptrs += descs[s].P;
+        dtype_set |= 1u << segs[s].dtype;
     }
 
     const size_t S = segs.size();
@@ -369,7 +381,7 @@ int run_check(evo_check *c, const std::vector<HostSeg> &whole, hipStream_t strea
     for (size_t s = 0; s < S; ++s) {
         descs[s].ref = segs[s].ref;
         descs[s].ptr0 = off;
-        off += segs[s].P;
+        off += descs[s].P;
     }
 
     if (S <= evo::kInlineSegs && total_ptrs <= evo::kInlinePtrs) {
@@ -378,8 +390,9 @@ int run_check(evo_check *c, const std::vector<HostSeg> &whole, hipStream_t strea
         std::memset(&tab, 0, sizeof tab);
         for (size_t s = 0; s < S; ++s) {
             tab.descs[s] = descs[s];
-            for (uint32_t p = 0; p < segs[s].P; ++p)
-                tab.ptrs[descs[s].ptr0 + p] = reinterpret_cast<uint64_t>(segs[s].cand_ptrs[p]);
+            for (uint32_t p = 0; p < descs[s].P; ++p)
+                tab.ptrs[descs[s].ptr0 + p] =
+                    reinterpret_cast<uint64_t>(p < segs[s].P ? segs[s].cand_ptrs[p] : segs[s].ref);
         }
         if (fit) {
             // one case group writes its rows once; independent segments write theirs each
@@ -401,8 +414,9 @@ int run_check(evo_check *c, const std::vector<HostSeg> &whole, hipStream_t strea
     char *hb = static_cast<char *>(slot->host);
     uint64_t *hptrs = reinterpret_cast<uint64_t *>(hb + desc_bytes);
     for (size_t s = 0; s < S; ++s)
-        for (uint32_t p = 0; p < segs[s].P; ++p)
-            hptrs[descs[s].ptr0 + p] = reinterpret_cast<uint64_t>(segs[s].cand_ptrs[p]);
+        for (uint32_t p = 0; p < descs[s].P; ++p)
+            hptrs[descs[s].ptr0 + p] =
+                reinterpret_cast<uint64_t>(p < segs[s].P ? segs[s].cand_ptrs[p] : segs[s].ref);
     std::memcpy(hb, descs.data(), desc_bytes);
 
     EVO_TRY(hipMemcpyAsync(c->d_table, hb, blob_bytes, hipMemcpyHostToDevice, stream));

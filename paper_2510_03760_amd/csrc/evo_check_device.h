@@ -468,11 +468,11 @@ struct TileWalk {
 // too.  Candidates of a tile that the fast path must not settle (anything non-finite,
 // overflow) are recorded in redo[tile slot] for the exact path.  Ends with the
 // lanes -> wavefront reduction into wpart[0 .. NC).
-template <uint32_t DT, int NC, bool REF_STREAM>
+template <uint32_t DT, int NC, bool REF_STREAM, bool PADDED>
 __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_ptr_of_lane,
                                                const TileWalk walk, uint64_t t_fend,
                                                float atol, float rtol, int lane, bool second_round,
-                                               uint16_t *redo, Partial *wpart) {
+                                               uint32_t n_real, uint16_t *redo, Partial *wpart) {
     using TL = Tile<DT>;
     constexpr int kE = TL::kE;
     constexpr int kNV = TL::kNV;
@@ -543,17 +543,26 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_p
             uint32_t redo_mask = 0;
 #pragma unroll
             for (int g = 0; g < NC; ++g) {
-                float c[kE];
-#pragma unroll
-                for (int j = 0; j < kNV; ++j) widen<DT>(buf[g % D][j], &c[j * TL::kVec]);
+                // PADDED: the group's last NC - n_real candidates are stand-ins; nothing is
+                // loaded or computed for them (n_real > NC / 2, so the candidates that the
+                // pipeline requests ahead of a tile are always real)
+                const bool real = !PADDED || (uint32_t)g < n_real;
                 float d[kE], q[kE];
+                if (real) {
+                    float c[kE];
 #pragma unroll
-                for (int e = 0; e < kE; ++e) d[e] = c[e] - r[e];
+                    for (int j = 0; j < kNV; ++j) widen<DT>(buf[g % D][j], &c[j * TL::kVec]);
+#pragma unroll
+                    for (int e = 0; e < kE; ++e) d[e] = c[e] - r[e];
+                }
                 // refill the slot: candidate g+D of this tile, or g+D-NC of the next
+                if (!PADDED || (uint32_t)((g + D) % NC) < n_real) {
 #pragma unroll
-                for (int j = 0; j < kNV; ++j)
-                    buf[g % D][j] = load16<true>(cptr[(g + D) % NC] + (g + D < NC ? off : off_next) + j * 1024,
-                                           lane_off);
+                    for (int j = 0; j < kNV; ++j)
+                        buf[g % D][j] = load16<true>(cptr[(g + D) % NC] + (g + D < NC ? off : off_next) + j * 1024,
+                                               lane_off);
+                }
+                if (!real) continue;
 #pragma unroll
                 for (int e = 0; e < kE; ++e) q[e] = __builtin_fabsf(d[e]) * inv[e];
                 // fp32 pairwise trees over the tile's kE non-negative terms (log2 kE
@@ -658,12 +667,12 @@ __device__ __forceinline__ uint64_t u64_of(uint32_t lo, uint32_t hi) { return ((
 //   integers |c - r| as an exact unsigned integer; running maximum as an integer (kept in
 //            the two 32-bit words of the accumulator's maxima), sum of the exactly
 //            converted differences in binary64; nothing is ever left to the exact path.
-template <uint32_t DT, int NC, bool REF_STREAM>
+template <uint32_t DT, int NC, bool REF_STREAM, bool PADDED>
 __device__ __forceinline__ uint32_t fast_tiles_wide(const char *rptr, uint64_t cand_ptr_of_lane,
                                                     const TileWalk walk, uint64_t t_fend,
                                                     float atol, float rtol, int lane,
-                                                    bool second_round, uint16_t *redo,
-                                                    Partial *wpart) {
+                                                    bool second_round, uint32_t n_real,
+                                                    uint16_t *redo, Partial *wpart) {
     using TL = Tile<DT>;
     constexpr bool kInt = kIsInt<DT>;
     constexpr int kE = TL::kE;
@@ -730,14 +739,18 @@ __device__ __forceinline__ uint32_t fast_tiles_wide(const char *rptr, uint64_t c
             uint32_t redo_mask = 0;
 #pragma unroll
             for (int g = 0; g < NC; ++g) {
+                const bool real = !PADDED || (uint32_t)g < n_real;   // see fast_tiles
                 u32x4 cw[kNV];
 #pragma unroll
                 for (int j = 0; j < kNV; ++j) cw[j] = buf[g % D][j];
                 // refill the slot: candidate g+D of this tile, or g+D-NC of the next
+                if (!PADDED || (uint32_t)((g + D) % NC) < n_real) {
 #pragma unroll
-                for (int j = 0; j < kNV; ++j)
-                    buf[g % D][j] = load16<true>(cptr[(g + D) % NC] + (g + D < NC ? off : off_next) + j * 1024,
-                                           lane_off);
+                    for (int j = 0; j < kNV; ++j)
+                        buf[g % D][j] = load16<true>(cptr[(g + D) % NC] + (g + D < NC ? off : off_next) + j * 1024,
+                                               lane_off);
+                }
+                if (!real) continue;
                 if constexpr (DT == EVO_F64) {
                     double d[kE], q[kE];
 #pragma unroll
@@ -879,7 +892,11 @@ __device__ __forceinline__ uint32_t fast_tiles_wide(const char *rptr, uint64_t c
 }
 
 // One job: a chunk of tiles of one segment for up to kWaves candidate groups.
-template <uint32_t DT>
+// SKIP: instantiate the fast path a second time for groups that end in stand-ins, without
+// their loads and arithmetic (off in the all-types kernel, where the stand-ins are loaded --
+// their pointer is the reference's -- and evaluated like candidates: same results, and the
+// largest translation unit stays a quarter of the compile time).
+template <uint32_t DT, bool SKIP>
 __device__ __forceinline__ void run_job(const SegDesc &sd, const uint64_t *ptr_table, uint32_t job_local,
                         uint32_t job_global, float atol, float rtol, bool second_round,
                         Partial *partials, ExactAcc (*exact_acc)[kG],
@@ -934,24 +951,33 @@ __device__ __forceinline__ void run_job(const SegDesc &sd, const uint64_t *ptr_t
     }
     const bool vec_ok = ((uintptr_t)rptr & 15u) == 0 && ballot((cand_ptr_of_lane & 15u) != 0) == 0;
 
+    // the segment's last group may end in stand-ins (SegDesc::n_pad)
+    const uint32_t n_real = __builtin_amdgcn_readfirstlane(group + 1 == sd.n_groups ? nc - sd.n_pad : nc);
     uint32_t any_redo = 0;
     if (vec_ok && nc > 0) {
         uint16_t *rd = redo[wave];
         Partial *wp = wave_part[wave];
         // the reference tile is shared by the workgroup's wavefronts iff gpw > 1
+#define EVO_TILES(FN_, NC_)                                                                    \
+    any_redo = (gpw == 1)                                                                      \
+        ? FN_<DT, NC_, true, false>(rptr, cand_ptr_of_lane, walk, n_full, atol, rtol, lane,     \
+                                    second_round, n_real, rd, wp)                               \
+        : FN_<DT, NC_, false, false>(rptr, cand_ptr_of_lane, walk, n_full, atol, rtol, lane,    \
+                                     second_round, n_real, rd, wp)
+#define EVO_TILES_PADDED(FN_, NC_)                                                             \
+    any_redo = FN_<DT, NC_, true, (SKIP && NC_ >= 4)>(rptr, cand_ptr_of_lane, walk, n_full, atol, rtol, \
+                                                      lane, second_round, n_real, rd, wp)
+        // A segment that is a single group with stand-ins (so gpw == 1) skips them.  Beside
+        // full groups the workgroup ends with its full groups anyway, and the stand-ins
+        // are loaded (cache hits) and evaluated like candidates.
+        const bool skip = SKIP && sd.n_groups == 1 && n_real < nc;
 #define EVO_FAST(NC_)                                                                          \
     if constexpr (kIsWide<DT>) {                                                               \
-        any_redo = (gpw == 1)                                                                  \
-            ? fast_tiles_wide<DT, NC_, true>(rptr, cand_ptr_of_lane, walk, n_full, atol, rtol, lane, \
-                                             second_round, rd, wp)                              \
-            : fast_tiles_wide<DT, NC_, false>(rptr, cand_ptr_of_lane, walk, n_full, atol, rtol, lane, \
-                                              second_round, rd, wp);                            \
+        if (NC_ >= 4 && skip) { EVO_TILES_PADDED(fast_tiles_wide, NC_); }                      \
+        else { EVO_TILES(fast_tiles_wide, NC_); }                                              \
     } else {                                                                                   \
-        any_redo = (gpw == 1)                                                                  \
-            ? fast_tiles<DT, NC_, true>(rptr, cand_ptr_of_lane, walk, n_full, atol, rtol, lane,  \
-                                        second_round, rd, wp)                                   \
-            : fast_tiles<DT, NC_, false>(rptr, cand_ptr_of_lane, walk, n_full, atol, rtol, lane, \
-                                         second_round, rd, wp);                                 \
+        if (NC_ >= 4 && skip) { EVO_TILES_PADDED(fast_tiles, NC_); }                           \
+        else { EVO_TILES(fast_tiles, NC_); }                                                   \
     }
         switch (nc) {
 #if EVO_KG > 8
@@ -963,12 +989,14 @@ __device__ __forceinline__ void run_job(const SegDesc &sd, const uint64_t *ptr_t
             default: EVO_FAST(1); break;
         }
 #undef EVO_FAST
+#undef EVO_TILES
+#undef EVO_TILES_PADDED
     }
 
     // Exact path over whatever is left: tiles the fast path flagged, the ragged last
     // tile of the segment, and everything when some tensor is not 16-byte aligned.
     if (nc > 0) {
-        const uint32_t all_mask = (1u << nc) - 1u;
+        const uint32_t all_mask = (1u << n_real) - 1u;   // stand-ins are never evaluated
         const uint32_t k_all = walk.steps_below(n_tiles);
         uint32_t k = 0;
         if (vec_ok && !any_redo) {
@@ -979,7 +1007,7 @@ __device__ __forceinline__ void run_job(const SegDesc &sd, const uint64_t *ptr_t
         for (; k < k_all; ++k) {
             const uint64_t t = walk.at(k);
             uint32_t m = all_mask;
-            if (vec_ok && t < n_full) m = any_redo ? (uint32_t)redo[wave][k] : 0u;
+            if (vec_ok && t < n_full) m = any_redo ? (uint32_t)redo[wave][k] & all_mask : 0u;
             m = __builtin_amdgcn_readfirstlane(m);
             while (m) {
                 const int g = __builtin_ctz(m);
@@ -1153,7 +1181,7 @@ __device__ __forceinline__ void finalize_segment(const SegDesc &sd, const Partia
         }
         fold[threadIdx.x] = a;
         __syncthreads();
-        if (ri == 0 && p < sd.P) {
+        if (ri == 0 && p < sd.P - sd.n_pad) {
             for (uint32_t k = 1; k < R; ++k) add_partial(a, fold[threadIdx.x + k]);
             if (sd.n_cases <= 1) {
                 write_stats(&stats[sd.stats_row0 + p], a, sd.n);
@@ -1169,7 +1197,7 @@ __device__ __forceinline__ void finalize_segment(const SegDesc &sd, const Partia
 // case order.
 __device__ __forceinline__ void write_case_group(const SegDesc *descs, const SegDesc &sd, const Partial *case_rows,
                                  evo_stats *stats) {
-    for (uint32_t p = threadIdx.x; p < sd.P; p += kThreads) {
+    for (uint32_t p = threadIdx.x; p < sd.P - sd.n_pad; p += kThreads) {
         Partial a{};
         uint64_t n_elems = 0;
         for (uint32_t k = 0; k < sd.n_cases; ++k) {
@@ -1216,34 +1244,35 @@ __device__ __forceinline__ bool check_body(const SegDesc *descs, const uint64_t 
     __shared__ ExactAcc exact_acc[kWaves][kG];
     __shared__ Partial wave_part[kWaves][kG];
     __shared__ uint16_t redo[kWaves][kMaxTilesPerWave];
+    constexpr bool kSkip = (DTS & (DTS - 1u)) == 0;   // one element type: see run_job
     if constexpr ((DTS & (1u << EVO_BF16)) != 0) {
         if (sd.dtype == EVO_BF16 || DTS == (1u << EVO_BF16))
-            run_job<EVO_BF16>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
+            run_job<EVO_BF16, kSkip>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
                              wave_part, redo);
     }
     if constexpr ((DTS & (1u << EVO_F16)) != 0) {
         if (sd.dtype == EVO_F16 || DTS == (1u << EVO_F16))
-            run_job<EVO_F16>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
+            run_job<EVO_F16, kSkip>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
                              wave_part, redo);
     }
     if constexpr ((DTS & (1u << EVO_F32)) != 0) {
         if (sd.dtype == EVO_F32 || DTS == (1u << EVO_F32))
-            run_job<EVO_F32>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
+            run_job<EVO_F32, kSkip>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
                              wave_part, redo);
     }
     if constexpr ((DTS & (1u << EVO_F64)) != 0) {
         if (sd.dtype == EVO_F64 || DTS == (1u << EVO_F64))
-            run_job<EVO_F64>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
+            run_job<EVO_F64, kSkip>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
                              wave_part, redo);
     }
     if constexpr ((DTS & (1u << EVO_I32)) != 0) {
         if (sd.dtype == EVO_I32 || DTS == (1u << EVO_I32))
-            run_job<EVO_I32>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
+            run_job<EVO_I32, kSkip>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
                              wave_part, redo);
     }
     if constexpr ((DTS & (1u << EVO_I64)) != 0) {
         if (sd.dtype == EVO_I64 || DTS == (1u << EVO_I64))
-            run_job<EVO_I64>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
+            run_job<EVO_I64, kSkip>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
                              wave_part, redo);
     }
 
@@ -1274,7 +1303,7 @@ __device__ __forceinline__ bool check_body(const SegDesc *descs, const uint64_t 
         // The segment was this one job (small tensors: the call is bound by latency, and
         // two tickets with their folds would double it): its rows are final.  They were
         // written by this workgroup and the barrier above orders them before these loads.
-        for (uint32_t p = threadIdx.x; p < sd.P; p += kThreads) {
+        for (uint32_t p = threadIdx.x; p < sd.P - sd.n_pad; p += kThreads) {
             uint32_t group, gi;
             locate(sd.P, p, &group, &gi);      // one group block: the group is the slot
             const Partial a = partials[(uint64_t)job * kRowsPerJob + group * kG + gi];

@@ -120,7 +120,7 @@ struct SegDesc {
     const void *ref;
     uint64_t ptr0;              // index of the segment's first candidate pointer in the table
     uint64_t n;                 // elements per tensor
-    uint32_t P;
+    uint32_t P;                 // candidates the kernel walks: the caller's plus n_pad
     uint32_t dtype;
     uint32_t stats_row0;
     uint32_t job0;              // first workgroup index of this segment
@@ -128,7 +128,9 @@ struct SegDesc {
     uint32_t n_chunks;          // workgroups that share the tiles of one group block
     uint32_t case0;             // first segment of the case group this segment belongs to
     uint32_t n_groups;          // candidate groups
-    uint32_t gpw;               // groups per workgroup: 1, 2 or 4
+    uint16_t gpw;               // groups per workgroup: 1, 2 or 4
+    uint16_t n_pad;             // trailing candidates that are stand-ins (their pointer is the
+                                // reference's); they get no evo_stats row
     uint32_t n_cases;           // segments in that case group (1: the segment stands alone)
 };
 static_assert(sizeof(SegDesc) == 64, "SegDesc layout");

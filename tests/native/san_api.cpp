@@ -54,6 +54,7 @@ static uint64_t rng() {
 // Invariants of partition():
 //  1. jobs of consecutive segments are consecutive, total_jobs is their sum;
 //  2. n_jobs = ceil(n_groups / gpw) * n_chunks, gpw in {1, 2, 4}, gpw <= pow2_ceil(n_groups);
+//     the groups are those of the population padded to full groups plus one power of two;
 //  3. the tile slots of a segment's workgroups cover all its tiles;
 //  4. no wavefront walks more than kMaxTilesPerWave tiles in one job (the size of the
 //     kernel's per-wavefront redo list);
@@ -70,9 +71,18 @@ static void check_partition(const std::vector<HostSeg> &segs, uint32_t target) {
         const uint64_t te = evo::tile_elems(segs[s].dtype);
         const uint64_t tiles = (segs[s].n + te - 1) / te;
         EXPECT(d[s].job0 == job);
-        EXPECT(d[s].n == segs[s].n && d[s].P == segs[s].P && d[s].dtype == segs[s].dtype);
+        EXPECT(d[s].n == segs[s].n && d[s].dtype == segs[s].dtype);
+        {
+            // the last group is filled up to a power of two with stand-ins: fewer of them
+            // than it has real candidates
+            const uint32_t rem = segs[s].P % 16, last = d[s].P % 16;
+            EXPECT(d[s].P - d[s].n_pad == segs[s].P && d[s].P / 16 == segs[s].P / 16 + (rem > 8 && last == 0 ? 1 : 0));
+            EXPECT((last & (last - 1)) == 0);
+            EXPECT(rem == 0 ? d[s].n_pad == 0 : d[s].n_pad < rem);
+            EXPECT(d[s].n_groups == segs[s].P / 16 + (rem ? 1u : 0u));
+        }
         EXPECT(d[s].stats_row0 == segs[s].row0);
-        EXPECT(d[s].n_groups == evo::group_count(segs[s].P));
+        EXPECT(d[s].n_groups == evo::group_count(d[s].P));
         EXPECT(d[s].gpw == 1 || d[s].gpw == 2 || d[s].gpw == 4);
         EXPECT(d[s].gpw <= pow2_ceil(d[s].n_groups));
         const uint32_t gblocks = (d[s].n_groups + d[s].gpw - 1) / d[s].gpw;
@@ -172,9 +182,9 @@ static void split_cases() {
         EXPECT(o == out.size());
     }
     {
-        const uint32_t Ps[] = {17, 33, 65, 100, 49, 32, 12};
-        const size_t parts[] = {2, 2, 2, 1, 1, 1, 1};
-        for (int i = 0; i < 7; ++i) {
+        const uint32_t Ps[] = {17, 33, 65, 100, 49, 32, 12, 27, 20, 24};
+        const size_t parts[] = {2, 2, 2, 1, 1, 1, 1, 1, 2, 1};
+        for (int i = 0; i < 10; ++i) {
             HostSeg h{};
             h.n = 1ull << 24;
             h.P = Ps[i];
