@@ -66,7 +66,8 @@ def _mixed_f64(n, P, seed):
     return ref, cands
 
 
-@pytest.mark.parametrize("n,P", [(1, 1), (255, 3), (256, 16), (257, 5), (70001, 21), ((1 << 20) + 3, 8)])
+@pytest.mark.parametrize("n,P", [(1, 1), (255, 3), (256, 16), (257, 5), (70001, 21), ((1 << 20) + 3, 8),
+                                 (70001, 11), (300001, 7), (150001, 3)])
 def test_f64_special_values_and_ragged_sizes(gu, n, P):
     _say("f64 n=%d P=%d" % (n, P))
     ref, cands = _mixed_f64(n, P, 100 + n % 97)
@@ -127,7 +128,8 @@ def _mixed_int(n, P, seed, dtype):
 
 
 @pytest.mark.parametrize("dtype", [torch.int32, torch.int64], ids=["i32", "i64"])
-@pytest.mark.parametrize("n,P", [(1, 1), (511, 3), (512, 16), (513, 5), (70001, 21), ((1 << 20) + 3, 8)])
+@pytest.mark.parametrize("n,P", [(1, 1), (511, 3), (512, 16), (513, 5), (70001, 21), ((1 << 20) + 3, 8),
+                                 (70001, 11), (300001, 7), (150001, 3)])
 def test_integer_tensors(gu, dtype, n, P):
     _say("%s n=%d P=%d" % (dtype, n, P))
     ref, cands = _mixed_int(n, P, 200 + n % 89, dtype)
