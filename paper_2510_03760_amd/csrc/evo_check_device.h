@@ -442,6 +442,106 @@ __device__ __forceinline__ const char *lane_ptr(uint64_t v, uint32_t src) {
     return reinterpret_cast<const char *>(((uint64_t)hi << 32) | lo);
 }
 
+// Exact path for a FULL, 16-byte-aligned tile that the fast path has handed back (something
+// non-finite in it): the same rule as exact_tile_narrow, element by element, but on tiles
+// fetched the way the fast path fetches them, the reference tile once for all flagged
+// candidates and four candidates per memory round trip.  A launch whose reference holds a few
+// thousand Inf/NaN sites spends its last few hundred microseconds here, one wavefront at a
+// time waiting for memory: 16 round trips per tile of 8 candidates became 2.
+template <uint32_t DT>
+__device__ __forceinline__ void exact_eval_loaded(const float (&r0)[Tile<DT>::kE],
+                                                  const u32x4 (&craw)[Tile<DT>::kNV], int lane, float atol,
+                                                  float rtol, ExactAcc *out) {
+    using TL = Tile<DT>;
+    constexpr int kE = TL::kE;
+    float r[kE], c[kE];
+#pragma unroll
+    for (int e = 0; e < kE; ++e) r[e] = r0[e];
+#pragma unroll
+    for (int j = 0; j < TL::kNV; ++j) widen<DT>(craw[j], &c[j * TL::kVec]);
+    float max_abs = 0.0f, max_rel = 0.0f;
+    double sum_abs = 0.0, sum_rel = 0.0;
+    uint32_t n_mismatch = 0, n_excluded = 0, flags = 0;
+    // rolled: the element in front is evaluated, then both lists move up by one
+#pragma unroll 1
+    for (int it = 0; it < kE; ++it) {
+        const float rr = r[0], cc = c[0];
+        const float ar = __builtin_fabsf(rr);
+        const float ac = __builtin_fabsf(cc);
+        const float scaled = rtol * ar;
+        const float tol = atol + scaled;
+        const bool r_nan = rr != rr, c_nan = cc != cc;
+        const bool r_inf = ar == kInf, c_inf = ac == kInf;
+        const bool both = !r_nan && !c_nan && !r_inf && !c_inf;
+        const float d = __builtin_fabsf(cc - rr);
+        const bool match = (cc == rr) || (both && d <= tol);
+        n_mismatch += popc64(ballot(!match));
+        n_excluded += popc64(ballot(!both));
+        if (ballot(c_nan)) flags |= EVO_F_CAND_NAN;
+        if (ballot(c_inf)) flags |= EVO_F_CAND_INF;
+        if (ballot(r_nan)) flags |= EVO_F_REF_NAN;
+        if (ballot(r_inf)) flags |= EVO_F_REF_INF;
+        if (ballot(c_nan != r_nan)) flags |= EVO_F_NAN_SITE_DIFF;
+        if (ballot((c_inf || r_inf) && !c_nan && !r_nan && cc != rr)) flags |= EVO_F_INF_DIFF;
+        if (both) {
+            float inv = 0.0f;
+            if (ar >= kFltMin) inv = 1.0f / ar;
+            const float q = d * inv;
+            max_abs = d > max_abs ? d : max_abs;
+            max_rel = q > max_rel ? q : max_rel;
+            sum_abs += (double)d;
+            sum_rel += (double)q;
+        }
+#pragma unroll
+        for (int e = 0; e + 1 < kE; ++e) {
+            r[e] = r[e + 1];
+            c[e] = c[e + 1];
+        }
+    }
+    exact_commit(out, lane, max_abs, max_rel, sum_abs, sum_rel, n_mismatch, n_excluded, flags);
+}
+
+// tile_byte_off: byte offset of the tile in every tensor; mask: the flagged candidates of the
+// wavefront's group (wave-uniform, not 0); acc: the wavefront's LDS records, one per candidate.
+template <uint32_t DT>
+__device__ __forceinline__ void exact_flagged_tile(const char *rptr, uint64_t cand_ptr_of_lane,
+                                                   uint64_t tile_byte_off, uint32_t mask, int lane,
+                                                   float atol, float rtol, ExactAcc *acc) {
+    using TL = Tile<DT>;
+    constexpr int kB = 4;   // candidates per round trip
+    const uint32_t lane_off = (uint32_t)lane * 16u;
+    u32x4 rraw[TL::kNV];
+#pragma unroll
+    for (int j = 0; j < TL::kNV; ++j) rraw[j] = load16<false>(rptr + tile_byte_off + j * 1024, lane_off);
+    bool first = true;
+    float r0[TL::kE];
+    while (mask) {
+        uint32_t g[kB];
+#pragma unroll
+        for (int b = 0; b < kB; ++b) {
+            g[b] = mask ? (uint32_t)__builtin_ctz(mask) : 0xffffffffu;
+            mask &= mask - 1u;   // 0 stays 0
+        }
+        u32x4 craw[kB][TL::kNV];
+#pragma unroll
+        for (int b = 0; b < kB; ++b) {
+            if (g[b] != 0xffffffffu) {
+                const char *cp = lane_ptr(cand_ptr_of_lane, g[b]) + tile_byte_off;
+#pragma unroll
+                for (int j = 0; j < TL::kNV; ++j) craw[b][j] = load16<true>(cp + j * 1024, lane_off);
+            }
+        }
+        if (first) {
+#pragma unroll
+            for (int j = 0; j < TL::kNV; ++j) widen<DT>(rraw[j], &r0[j * TL::kVec]);
+            first = false;
+        }
+#pragma unroll
+        for (int b = 0; b < kB; ++b)
+            if (g[b] != 0xffffffffu) exact_eval_loaded<DT>(r0, craw[b], lane, atol, rtol, &acc[g[b]]);
+    }
+}
+
 // The tiles of one wavefront.  In step k the wavefront slots of a group block together
 // cover one contiguous window of n_slots tiles of every tensor, so that at any moment
 // the whole grid reads a few MiB-sized windows (DRAM pages and TLB entries are shared
@@ -998,23 +1098,43 @@ __device__ __forceinline__ void run_job(const SegDesc &sd, const uint64_t *ptr_t
     if (nc > 0) {
         const uint32_t all_mask = (1u << n_real) - 1u;   // stand-ins are never evaluated
         const uint32_t k_all = walk.steps_below(n_tiles);
-        uint32_t k = 0;
-        if (vec_ok && !any_redo) {
-            // nothing flagged: only the ragged tile can be left, and only the last step
-            // of the walk can land on it
-            k = (k_all > 0 && n_full < n_tiles && walk.at(k_all - 1) == n_full) ? k_all - 1 : k_all;
-        }
-        for (; k < k_all; ++k) {
-            const uint64_t t = walk.at(k);
-            uint32_t m = all_mask;
-            if (vec_ok && t < n_full) m = any_redo ? (uint32_t)redo[wave][k] & all_mask : 0u;
-            m = __builtin_amdgcn_readfirstlane(m);
+        auto one_by_one = [&](uint64_t t, uint32_t m) {
             while (m) {
                 const int g = __builtin_ctz(m);
                 m &= m - 1;
                 exact_tile<DT>(rptr, lane_ptr(cand_ptr_of_lane, (uint32_t)g), n,
                                t * (uint64_t)kTileElems, lane, atol, rtol, &exact_acc[wave][g]);
             }
+        };
+        if (vec_ok) {
+            const uint32_t k_fast = walk.steps_below(n_full);   // the steps the fast path took
+            if (any_redo) {
+                // The list of flagged tiles is scanned 64 steps at a time, and a tile's number
+                // (a 64-bit division) is only worked out for the flagged ones: step by step,
+                // the scan alone took 0.4 us per step, 400 us after a 2^30-element launch.
+                for (uint32_t k0 = 0; k0 < k_fast; k0 += (uint32_t)kLanes) {
+                    const uint32_t kk = k0 + (uint32_t)lane;
+                    const uint32_t v = kk < k_fast ? (uint32_t)redo[wave][kk] & all_mask : 0u;
+                    uint64_t hits = ballot(v != 0);
+                    while (hits) {
+                        const uint32_t b = (uint32_t)__builtin_ctzll(hits);
+                        hits &= hits - 1;
+                        const uint32_t m = __builtin_amdgcn_readlane(v, b);
+                        const uint64_t t = walk.at(k0 + b);
+                        if constexpr (!kIsWide<DT>) {
+                            exact_flagged_tile<DT>(rptr, cand_ptr_of_lane,
+                                                   t * ((uint64_t)kTileElems * elem_bytes(DT)), m, lane, atol,
+                                                   rtol, exact_acc[wave]);
+                        } else {
+                            one_by_one(t, m);
+                        }
+                    }
+                }
+            }
+            // the ragged tile: only the last step of the walk can land on it
+            if (k_all > k_fast) one_by_one(walk.at(k_all - 1), all_mask);
+        } else {
+            for (uint32_t k = 0; k < k_all; ++k) one_by_one(walk.at(k), all_mask);
         }
         if ((uint32_t)lane < nc) {
             const ExactAcc x = exact_acc[wave][lane];
