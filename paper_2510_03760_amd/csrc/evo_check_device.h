@@ -442,106 +442,6 @@ __device__ __forceinline__ const char *lane_ptr(uint64_t v, uint32_t src) {
     return reinterpret_cast<const char *>(((uint64_t)hi << 32) | lo);
 }
 
-// Exact path for a FULL, 16-byte-aligned tile that the fast path has handed back (something
-// non-finite in it): the same rule as exact_tile_narrow, element by element, but on tiles
-// fetched the way the fast path fetches them, the reference tile once for all flagged
-// candidates and four candidates per memory round trip.  A launch whose reference holds a few
-// thousand Inf/NaN sites spends its last few hundred microseconds here, one wavefront at a
-// time waiting for memory: 16 round trips per tile of 8 candidates became 2.
-template <uint32_t DT>
-__device__ __forceinline__ void exact_eval_loaded(const float (&r0)[Tile<DT>::kE],
-                                                  const u32x4 (&craw)[Tile<DT>::kNV], int lane, float atol,
-                                                  float rtol, ExactAcc *out) {
-    using TL = Tile<DT>;
-    constexpr int kE = TL::kE;
-    float r[kE], c[kE];
-#pragma unroll
-    for (int e = 0; e < kE; ++e) r[e] = r0[e];
-#pragma unroll
-    for (int j = 0; j < TL::kNV; ++j) widen<DT>(craw[j], &c[j * TL::kVec]);
-    float max_abs = 0.0f, max_rel = 0.0f;
-    double sum_abs = 0.0, sum_rel = 0.0;
-    uint32_t n_mismatch = 0, n_excluded = 0, flags = 0;
-    // rolled: the element in front is evaluated, then both lists move up by one
-#pragma unroll 1
-    for (int it = 0; it < kE; ++it) {
-        const float rr = r[0], cc = c[0];
-        const float ar = __builtin_fabsf(rr);
-        const float ac = __builtin_fabsf(cc);
-        const float scaled = rtol * ar;
-        const float tol = atol + scaled;
-        const bool r_nan = rr != rr, c_nan = cc != cc;
-        const bool r_inf = ar == kInf, c_inf = ac == kInf;
-        const bool both = !r_nan && !c_nan && !r_inf && !c_inf;
-        const float d = __builtin_fabsf(cc - rr);
-        const bool match = (cc == rr) || (both && d <= tol);
-        n_mismatch += popc64(ballot(!match));
-        n_excluded += popc64(ballot(!both));
-        if (ballot(c_nan)) flags |= EVO_F_CAND_NAN;
-        if (ballot(c_inf)) flags |= EVO_F_CAND_INF;
-        if (ballot(r_nan)) flags |= EVO_F_REF_NAN;
-        if (ballot(r_inf)) flags |= EVO_F_REF_INF;
-        if (ballot(c_nan != r_nan)) flags |= EVO_F_NAN_SITE_DIFF;
-        if (ballot((c_inf || r_inf) && !c_nan && !r_nan && cc != rr)) flags |= EVO_F_INF_DIFF;
-        if (both) {
-            float inv = 0.0f;
-            if (ar >= kFltMin) inv = 1.0f / ar;
-            const float q = d * inv;
-            max_abs = d > max_abs ? d : max_abs;
-            max_rel = q > max_rel ? q : max_rel;
-            sum_abs += (double)d;
-            sum_rel += (double)q;
-        }
-#pragma unroll
-        for (int e = 0; e + 1 < kE; ++e) {
-            r[e] = r[e + 1];
-            c[e] = c[e + 1];
-        }
-    }
-    exact_commit(out, lane, max_abs, max_rel, sum_abs, sum_rel, n_mismatch, n_excluded, flags);
-}
-
-// tile_byte_off: byte offset of the tile in every tensor; mask: the flagged candidates of the
-// wavefront's group (wave-uniform, not 0); acc: the wavefront's LDS records, one per candidate.
-template <uint32_t DT>
-__device__ __forceinline__ void exact_flagged_tile(const char *rptr, uint64_t cand_ptr_of_lane,
-                                                   uint64_t tile_byte_off, uint32_t mask, int lane,
-                                                   float atol, float rtol, ExactAcc *acc) {
-    using TL = Tile<DT>;
-    constexpr int kB = 4;   // candidates per round trip
-    const uint32_t lane_off = (uint32_t)lane * 16u;
-    u32x4 rraw[TL::kNV];
-#pragma unroll
-    for (int j = 0; j < TL::kNV; ++j) rraw[j] = load16<false>(rptr + tile_byte_off + j * 1024, lane_off);
-    bool first = true;
-    float r0[TL::kE];
-    while (mask) {
-        uint32_t g[kB];
-#pragma unroll
-        for (int b = 0; b < kB; ++b) {
-            g[b] = mask ? (uint32_t)__builtin_ctz(mask) : 0xffffffffu;
-            mask &= mask - 1u;   // 0 stays 0
-        }
-        u32x4 craw[kB][TL::kNV];
-#pragma unroll
-        for (int b = 0; b < kB; ++b) {
-            if (g[b] != 0xffffffffu) {
-                const char *cp = lane_ptr(cand_ptr_of_lane, g[b]) + tile_byte_off;
-#pragma unroll
-                for (int j = 0; j < TL::kNV; ++j) craw[b][j] = load16<true>(cp + j * 1024, lane_off);
-            }
-        }
-        if (first) {
-#pragma unroll
-            for (int j = 0; j < TL::kNV; ++j) widen<DT>(rraw[j], &r0[j * TL::kVec]);
-            first = false;
-        }
-#pragma unroll
-        for (int b = 0; b < kB; ++b)
-            if (g[b] != 0xffffffffu) exact_eval_loaded<DT>(r0, craw[b], lane, atol, rtol, &acc[g[b]]);
-    }
-}
-
 // The tiles of one wavefront.  In step k the wavefront slots of a group block together
 // cover one contiguous window of n_slots tiles of every tensor, so that at any moment
 // the whole grid reads a few MiB-sized windows (DRAM pages and TLB entries are shared
@@ -552,7 +452,8 @@ struct TileWalk {
     uint32_t n_chunks, chunk, tpw, tl;
     __device__ __forceinline__ uint64_t window() const { return (uint64_t)n_chunks * tpw; }
     __device__ __forceinline__ uint64_t at(uint32_t k) const {
-        const uint32_t c = (uint32_t)(((uint64_t)chunk + (uint64_t)k * kRotate) % n_chunks);
+        // 32 bits suffice: chunk < n_chunks <= 2^30 and k <= kMaxTilesPerWave
+        const uint32_t c = (chunk + k * kRotate) % n_chunks;
         return ((uint64_t)k * n_chunks + c) * tpw + tl;
     }
     // number of steps k = 0, 1, ... whose tile lies below `limit`
@@ -561,6 +462,126 @@ struct TileWalk {
         return full + (at(full) < limit ? 1u : 0u);
     }
 };
+
+// Exact path for the FULL, 16-byte-aligned tiles of ONE candidate that the fast path has
+// handed back (bit `bit` of redo_w[k] for step k < k_fast): the rule of evo.h, element by
+// element, as in exact_tile_narrow, but
+//  * on tiles fetched the way the fast path fetches them, four tiles per memory round trip,
+//  * with the counts and flags kept per lane (vector compares and selects; no wave-wide
+//    ballot per element), and
+//  * with one cross-lane reduction for the whole candidate instead of one per tile.
+// A candidate that is NaN or Inf throughout -- what a broken kernel tends to produce -- has
+// every one of its tiles handed back; with a reduction and eleven ballots per tile that cost
+// 2.7 us per tile, 25 % on top of a launch of 16 candidates for each such candidate.
+template <uint32_t DT>
+__device__ __forceinline__ void exact_candidate_pass(const char *rptr, const char *cptr, const TileWalk walk,
+                                                     uint32_t k_fast, uint32_t bit, const uint16_t *redo_w,
+                                                     int lane, float atol, float rtol, ExactAcc *out) {
+    using TL = Tile<DT>;
+    constexpr int kE = TL::kE;
+    constexpr int kNV = TL::kNV;
+    constexpr int kB = 4;   // tiles per round trip
+    constexpr uint64_t kTileBytes = (uint64_t)tile_elems(DT) * sizeof(typename TL::elem_t);
+    const uint32_t lane_off = (uint32_t)lane * 16u;
+    float max_abs = 0.0f, max_rel = 0.0f;
+    double sum_abs = 0.0, sum_rel = 0.0;
+    uint32_t n_mismatch = 0, n_excluded = 0, flags = 0;   // of this lane
+    for (uint32_t k0 = 0; k0 < k_fast; k0 += (uint32_t)kLanes) {
+        const uint32_t kk = k0 + (uint32_t)lane;
+        const uint32_t v = kk < k_fast ? (uint32_t)redo_w[kk] : 0u;
+        uint64_t hits = ballot(((v >> bit) & 1u) != 0);
+        while (hits) {
+            uint64_t off[kB];
+            bool has[kB];
+#pragma unroll
+            for (int b = 0; b < kB; ++b) {
+                has[b] = hits != 0;
+                const uint32_t idx = has[b] ? (uint32_t)__builtin_ctzll(hits) : 0u;
+                hits &= hits - 1;   // 0 stays 0
+                off[b] = walk.at(k0 + idx) * kTileBytes;
+            }
+            u32x4 rraw[kB][kNV], craw[kB][kNV];
+#pragma unroll
+            for (int b = 0; b < kB; ++b) {
+                if (has[b]) {
+#pragma unroll
+                    for (int j = 0; j < kNV; ++j) {
+                        rraw[b][j] = load16<false>(rptr + off[b] + j * 1024, lane_off);
+                        craw[b][j] = load16<true>(cptr + off[b] + j * 1024, lane_off);
+                    }
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < kB; ++b) {
+                if (!has[b]) continue;
+                float r[kE], c[kE];
+#pragma unroll
+                for (int j = 0; j < kNV; ++j) {
+                    widen<DT>(rraw[b][j], &r[j * TL::kVec]);
+                    widen<DT>(craw[b][j], &c[j * TL::kVec]);
+                }
+#pragma unroll
+                for (int e = 0; e < kE; ++e) {
+                    const float rr = r[e], cc = c[e];
+                    const float ar = __builtin_fabsf(rr);
+                    const float ac = __builtin_fabsf(cc);
+                    const float scaled = rtol * ar;
+                    const float tol = atol + scaled;
+                    const bool r_nan = rr != rr, c_nan = cc != cc;
+                    const bool r_inf = ar == kInf, c_inf = ac == kInf;
+                    const bool both = !r_nan && !c_nan && !r_inf && !c_inf;
+                    const float d = __builtin_fabsf(cc - rr);
+                    const bool match = (cc == rr) || (both && d <= tol);
+                    n_mismatch += match ? 0u : 1u;
+                    n_excluded += both ? 0u : 1u;
+                    flags |= (c_nan ? EVO_F_CAND_NAN : 0u) | (c_inf ? EVO_F_CAND_INF : 0u) |
+                             (r_nan ? EVO_F_REF_NAN : 0u) | (r_inf ? EVO_F_REF_INF : 0u) |
+                             (c_nan != r_nan ? EVO_F_NAN_SITE_DIFF : 0u) |
+                             ((c_inf || r_inf) && !c_nan && !r_nan && cc != rr ? EVO_F_INF_DIFF : 0u);
+                    float inv = 0.0f;
+                    if (both && ar >= kFltMin) inv = 1.0f / ar;
+                    // 0 is the identity of both maxima and both sums (every term is >= +0)
+                    const float dm = both ? d : 0.0f;
+                    const float qm = both ? d * inv : 0.0f;
+                    max_abs = dm > max_abs ? dm : max_abs;
+                    max_rel = qm > max_rel ? qm : max_rel;
+                    sum_abs += (double)dm;
+                    sum_rel += (double)qm;
+                }
+            }
+        }
+    }
+    // lanes -> wavefront, once: the counts travel as binary64 (exact below 2^53)
+    uint32_t ma_bits = __builtin_bit_cast(uint32_t, max_abs), mr_bits = __builtin_bit_cast(uint32_t, max_rel);
+    uint32_t zero_a = 0, zero_b = 0;
+    double mis = (double)n_mismatch, exc = (double)n_excluded;
+#define EVO_STEP(CTRL_, MASK_)                            \
+    reduce_step<CTRL_, MASK_>(ma_bits, sum_abs);          \
+    reduce_step<CTRL_, MASK_>(mr_bits, sum_rel);          \
+    reduce_step<CTRL_, MASK_>(zero_a, mis);               \
+    reduce_step<CTRL_, MASK_>(zero_b, exc)
+    EVO_WAVE_REDUCE(EVO_STEP);
+#undef EVO_STEP
+    max_abs = last_lane_f32(ma_bits);
+    max_rel = last_lane_f32(mr_bits);
+    sum_abs = last_lane_f64(sum_abs);
+    sum_rel = last_lane_f64(sum_rel);
+    mis = last_lane_f64(mis);
+    exc = last_lane_f64(exc);
+    uint32_t all_flags = 0;
+#pragma unroll
+    for (uint32_t f = 1u; f <= EVO_F_INF_DIFF; f <<= 1)
+        if (ballot((flags & f) != 0)) all_flags |= f;
+    if (lane == 0) {
+        out->sum_abs += sum_abs;
+        out->sum_rel += sum_rel;
+        out->max_abs = __builtin_fmaxf(out->max_abs, max_abs);
+        out->max_rel = __builtin_fmaxf(out->max_rel, max_rel);
+        out->n_mismatch += (uint32_t)mis;
+        out->n_excluded += (uint32_t)exc;
+        out->flags |= all_flags;
+    }
+}
 
 // Fast path of one wavefront over its full tiles walk.at(0), walk.at(1), ... (those below
 // t_fend) for a full group of NC candidates.  Straight-line code per candidate apart from the
@@ -1109,24 +1130,28 @@ __device__ __forceinline__ void run_job(const SegDesc &sd, const uint64_t *ptr_t
         if (vec_ok) {
             const uint32_t k_fast = walk.steps_below(n_full);   // the steps the fast path took
             if (any_redo) {
-                // The list of flagged tiles is scanned 64 steps at a time, and a tile's number
-                // (a 64-bit division) is only worked out for the flagged ones: step by step,
-                // the scan alone took 0.4 us per step, 400 us after a 2^30-element launch.
-                for (uint32_t k0 = 0; k0 < k_fast; k0 += (uint32_t)kLanes) {
-                    const uint32_t kk = k0 + (uint32_t)lane;
-                    const uint32_t v = kk < k_fast ? (uint32_t)redo[wave][kk] & all_mask : 0u;
-                    uint64_t hits = ballot(v != 0);
-                    while (hits) {
-                        const uint32_t b = (uint32_t)__builtin_ctzll(hits);
-                        hits &= hits - 1;
-                        const uint32_t m = __builtin_amdgcn_readlane(v, b);
-                        const uint64_t t = walk.at(k0 + b);
-                        if constexpr (!kIsWide<DT>) {
-                            exact_flagged_tile<DT>(rptr, cand_ptr_of_lane,
-                                                   t * ((uint64_t)kTileElems * elem_bytes(DT)), m, lane, atol,
-                                                   rtol, exact_acc[wave]);
-                        } else {
-                            one_by_one(t, m);
+                if constexpr (!kIsWide<DT>) {
+                    // candidate by candidate
+                    uint32_t cm = __builtin_amdgcn_readfirstlane(any_redo & all_mask);
+                    while (cm) {
+                        const uint32_t g = (uint32_t)__builtin_ctz(cm);
+                        cm &= cm - 1;
+                        exact_candidate_pass<DT>(rptr, lane_ptr(cand_ptr_of_lane, g), walk, k_fast, g,
+                                                 redo[wave], lane, atol, rtol, &exact_acc[wave][g]);
+                    }
+                } else {
+                    // The list of flagged tiles is scanned 64 steps at a time, and a tile's
+                    // number (a division) is only worked out for the flagged ones: step by
+                    // step, the scan alone took 0.4 us per step, 400 us after a 2^30-element
+                    // launch.
+                    for (uint32_t k0 = 0; k0 < k_fast; k0 += (uint32_t)kLanes) {
+                        const uint32_t kk = k0 + (uint32_t)lane;
+                        const uint32_t v = kk < k_fast ? (uint32_t)redo[wave][kk] & all_mask : 0u;
+                        uint64_t hits = ballot(v != 0);
+                        while (hits) {
+                            const uint32_t b = (uint32_t)__builtin_ctzll(hits);
+                            hits &= hits - 1;
+                            one_by_one(walk.at(k0 + b), __builtin_amdgcn_readlane(v, b));
                         }
                     }
                 }
