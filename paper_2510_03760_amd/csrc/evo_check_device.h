@@ -593,7 +593,8 @@ template <uint32_t DT, int NC, bool REF_STREAM, bool PADDED>
 __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_ptr_of_lane,
                                                const TileWalk walk, uint64_t t_fend,
                                                float atol, float rtol, int lane, bool second_round,
-                                               uint32_t n_real, uint16_t *redo, Partial *wpart) {
+                                               uint32_t n_real, uint16_t *redo, Partial *wpart,
+                                               ExactAcc *xacc) {
     using TL = Tile<DT>;
     constexpr int kE = TL::kE;
     constexpr int kNV = TL::kNV;
@@ -724,7 +725,23 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_p
                     acc[g].sum_rel = s_rel;
                     n_mismatch[g] += mism;
                 } else {
-                    redo_mask |= 1u << g;
+                    // What a broken kernel tends to produce: a tile that is NaN throughout.
+                    // Over a finite reference tile that is the case iff every difference is
+                    // NaN, and then the tile's share is known without looking further:
+                    // every element mismatches and is excluded from the statistics.
+                    uint64_t other = 0;
+#pragma unroll
+                    for (int e = 0; e < kE; ++e)
+                        other |= ballot(!(d[e] != d[e]) || !(__builtin_fabsf(r[e]) < kInf));
+                    if (other == 0) {
+                        n_mismatch[g] += (uint32_t)tile_elems(DT);
+                        if (lane == 0) {
+                            xacc[g].n_excluded += (uint32_t)tile_elems(DT);
+                            xacc[g].flags |= EVO_F_CAND_NAN | EVO_F_NAN_SITE_DIFF;
+                        }
+                    } else {
+                        redo_mask |= 1u << g;
+                    }
                 }
             }
             if (lane == 0) redo[slot] = (uint16_t)redo_mask;
@@ -793,7 +810,7 @@ __device__ __forceinline__ uint32_t fast_tiles_wide(const char *rptr, uint64_t c
                                                     const TileWalk walk, uint64_t t_fend,
                                                     float atol, float rtol, int lane,
                                                     bool second_round, uint32_t n_real,
-                                                    uint16_t *redo, Partial *wpart) {
+                                                    uint16_t *redo, Partial *wpart, ExactAcc * /*xacc*/) {
     using TL = Tile<DT>;
     constexpr bool kInt = kIsInt<DT>;
     constexpr int kE = TL::kE;
@@ -1082,12 +1099,12 @@ __device__ __forceinline__ void run_job(const SegDesc &sd, const uint64_t *ptr_t
 #define EVO_TILES(FN_, NC_)                                                                    \
     any_redo = (gpw == 1)                                                                      \
         ? FN_<DT, NC_, true, false>(rptr, cand_ptr_of_lane, walk, n_full, atol, rtol, lane,     \
-                                    second_round, n_real, rd, wp)                               \
+                                    second_round, n_real, rd, wp, exact_acc[wave])              \
         : FN_<DT, NC_, false, false>(rptr, cand_ptr_of_lane, walk, n_full, atol, rtol, lane,    \
-                                     second_round, n_real, rd, wp)
+                                     second_round, n_real, rd, wp, exact_acc[wave])
 #define EVO_TILES_PADDED(FN_, NC_)                                                             \
     any_redo = FN_<DT, NC_, true, (SKIP && NC_ >= 4)>(rptr, cand_ptr_of_lane, walk, n_full, atol, rtol, \
-                                                      lane, second_round, n_real, rd, wp)
+                                                      lane, second_round, n_real, rd, wp, exact_acc[wave])
         // A segment that is a single group with stand-ins (so gpw == 1) skips them.  Beside
         // full groups the workgroup ends with its full groups anyway, and the stand-ins
         // are loaded (cache hits) and evaluated like candidates.

@@ -84,6 +84,41 @@ def test_degenerate_candidates_are_invalid(gu, dtype):
     chk.close()
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16],
+                         ids=lambda d: str(d).split(".")[-1])
+def test_nan_filled_tiles_next_to_everything_else(gu, dtype):
+    """Tiles that are NaN throughout are settled in the fast path by a closed form that only
+    holds over a finite reference tile: NaN-filled candidates beside reference tiles that hold
+    a NaN, an Inf or nothing special, NaN-filled except for one element, NaN in a single tile,
+    Inf-filled, and a mixture of NaN and Inf."""
+    _say("nan tiles %s" % dtype)
+    n = 40 * 1024 + 333
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    ref = (torch.randn(n, generator=g, device="cuda") + 2).to(dtype)
+    ref[3000] = float("nan")
+    ref[9000] = float("inf")
+    ref[9001] = float("-inf")
+    ref[20000:20050] = float("nan")
+    nan = torch.full_like(ref, float("nan"))
+    cands = [nan.clone()]
+    c = nan.clone(); c[12345] = 1.0; cands.append(c)                       # one number in one tile
+    c = nan.clone(); c[::1024] = ref[::1024]; cands.append(c)              # one right element per tile
+    c = ref.clone(); c[5 * 1024:6 * 1024] = float("nan"); cands.append(c)  # one tile (or two halves)
+    c = ref.clone(); c[7 * 512:8 * 512] = float("nan"); cands.append(c)
+    cands.append(torch.full_like(ref, float("inf")))
+    c = nan.clone(); c[1::2] = float("inf"); cands.append(c)               # NaN and Inf alternate
+    c = nan.clone(); c[9000] = float("inf"); c[9001] = float("inf"); cands.append(c)
+    cands.append(ref.clone())
+    P = len(cands)
+    seg = synth.Segment(ref.contiguous(), [x.contiguous() for x in cands], (n,), [True] * P)
+    w = synth.Workload("nan-tiles", [seg], 1e-2, 1e-2, torch.ones(P, 4, device="cuda"),
+                       torch.ones(4, device="cuda"))
+    chk, stats, want = gu.check_parity(w, label="nan tiles %s" % dtype)
+    assert want[0]["n_mismatch"] == n and want[0]["n_finite"] == 0
+    chk.close()
+
+
 def test_guard_rows_around_the_result_buffer(gu):
     """The calls write the rows they are given and not a byte more."""
     _say("guard rows")
