@@ -243,7 +243,9 @@ EVO_API int evo_fitness_ex(evo_check_t *c, const float *timings, const float *ba
  * The whole evaluation of a population in one call: evo_check_cases (K >= 1 test cases of the
  * same P candidates; K = 1 is evo_check_batch on cases[0]) followed by evo_fitness_ex, with
  * the same results as those two calls in that order.  When the K descriptors and K*P
- * candidate pointers fit the kernel argument block (K <= 8, K*P <= 384) it is ONE launch: the
+ * candidate pointers fit the kernel argument block (K <= 8, K*P' <= 384, P' being P rounded up
+ * to whole groups of 16 plus one power of two; for K = 1 a population such as 17 or 33 counts
+ * as two descriptors) it is ONE launch: the
  * timing rows are reduced by the first workgroups of the grid while the tensors stream, and
  * the last of them or of the check to finish computes speedup, fitness and the population
  * figures.  Larger tables run as two launches.

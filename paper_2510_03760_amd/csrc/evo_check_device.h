@@ -587,8 +587,10 @@ __device__ __forceinline__ void exact_candidate_pass(const char *rptr, const cha
 // t_fend) for a full group of NC candidates.  Straight-line code per candidate apart from the
 // commit test; loads run D candidates ahead of the arithmetic, across tile boundaries
 // too.  Candidates of a tile that the fast path must not settle (anything non-finite,
-// overflow) are recorded in redo[tile slot] for the exact path.  Ends with the
-// lanes -> wavefront reduction into wpart[0 .. NC).
+// overflow) are recorded in redo[tile slot] for the exact path -- except a candidate tile
+// that is NaN throughout over a finite reference tile, whose share is added on the spot
+// (counts in registers, exclusions and flags in xacc).  Ends with the lanes -> wavefront
+// reduction into wpart[0 .. NC).
 template <uint32_t DT, int NC, bool REF_STREAM, bool PADDED>
 __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_ptr_of_lane,
                                                const TileWalk walk, uint64_t t_fend,

@@ -45,8 +45,10 @@ namespace evo {
 // Each wavefront owns one group of candidates (a power of two, at most kG) and
 // keeps that group's running statistics in registers for the whole job; the
 // wavefronts of a workgroup either share a reference tile (different candidate
-// groups) or take different tiles (same group), so that a reference tile is never
-// fetched by more than one workgroup -- i.e. by more than one XCD's L2.
+// groups) or take different tiles (same group).  With more than four groups the
+// workgroups that take the same tiles for different groups have numbers that are
+// congruent modulo 8 whenever the chunk count is a multiple of 8, i.e. they run on one
+// XCD and meet the reference tile in one L2.
 constexpr int kLanes = 64;
 constexpr int kWaves = 4;
 constexpr int kThreads = kLanes * kWaves;
