@@ -588,7 +588,7 @@ __device__ __forceinline__ void exact_candidate_pass(const char *rptr, const cha
 // commit test; loads run D candidates ahead of the arithmetic, across tile boundaries
 // too.  Candidates of a tile that the fast path must not settle (anything non-finite,
 // overflow) are recorded in redo[tile slot] for the exact path -- except a candidate tile
-// that is NaN throughout over a finite reference tile, whose share is added on the spot
+// that is NaN or Inf throughout over a moderate reference tile, whose share is added on the spot
 // (counts in registers, exclusions and flags in xacc).  Ends with the lanes -> wavefront
 // reduction into wpart[0 .. NC).
 template <uint32_t DT, int NC, bool REF_STREAM, bool PADDED>
@@ -727,19 +727,28 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_p
                     acc[g].sum_rel = s_rel;
                     n_mismatch[g] += mism;
                 } else {
-                    // What a broken kernel tends to produce: a tile that is NaN throughout.
-                    // Over a finite reference tile that is the case iff every difference is
-                    // NaN, and then the tile's share is known without looking further:
-                    // every element mismatches and is excluded from the statistics.
-                    uint64_t other = 0;
+                    // What a broken kernel tends to produce: a tile without a single number in
+                    // it, NaN or +-Inf throughout.  Over reference elements below 2^102 in
+                    // magnitude a difference is NaN iff the candidate element is NaN and
+                    // infinite iff it is infinite (a finite one cannot carry the difference
+                    // past the largest binary32 number: 2^102 is a quarter of its last
+                    // place).  Then the tile's share is known without looking further: every
+                    // element mismatches and is excluded from the statistics.
+                    uint64_t number = 0, any_nan = 0, any_inf = 0;
 #pragma unroll
-                    for (int e = 0; e < kE; ++e)
-                        other |= ballot(!(d[e] != d[e]) || !(__builtin_fabsf(r[e]) < kInf));
-                    if (other == 0) {
+                    for (int e = 0; e < kE; ++e) {
+                        const uint64_t is_nan = ballot(d[e] != d[e]);
+                        const uint64_t is_inf = ballot(__builtin_fabsf(d[e]) == kInf);
+                        any_nan |= is_nan;
+                        any_inf |= is_inf;
+                        number |= ~(is_nan | is_inf) | ballot(!(__builtin_fabsf(r[e]) < 0x1p102f));
+                    }
+                    if (number == 0) {
                         n_mismatch[g] += (uint32_t)tile_elems(DT);
                         if (lane == 0) {
                             xacc[g].n_excluded += (uint32_t)tile_elems(DT);
-                            xacc[g].flags |= EVO_F_CAND_NAN | EVO_F_NAN_SITE_DIFF;
+                            xacc[g].flags |= (any_nan ? EVO_F_CAND_NAN | EVO_F_NAN_SITE_DIFF : 0u) |
+                                             (any_inf ? EVO_F_CAND_INF | EVO_F_INF_DIFF : 0u);
                         }
                     } else {
                         redo_mask |= 1u << g;
