@@ -6,7 +6,7 @@ batched (or segmented) tolerance check of every candidate against its reference,
 then the median-timing / speedup / fitness reduction.  Inputs are resident in HBM
 before the timed region starts.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c3h|c4|c5|cases|f64|i32|i64]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--spinup-ms MS] [--workload c2|c1|c3|c3h|c4|c5|cases|f64|i32|i64]
                     [--no-cpu-baseline] [--no-read-ceiling] [--copy-calibration]
 
 --copy-calibration runs only a plain device-to-device copy of known size (used to
@@ -159,6 +159,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2")
+    ap.add_argument("--spinup-ms", type=float, default=60.0,
+                    help="untimed load before the warm-up steps, in milliseconds")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget-elems", type=float, default=2.0e9,
                     help="candidate-elements the CPU oracle is timed on (about 160 M/s/core)")
@@ -250,6 +252,16 @@ def main() -> int:
                 mid.record(stream)
             chk.fitness(w.timings, w.baseline, stats, summary, stream=stream)
 
+    # Spin-up: the first tens of milliseconds of load in a process run at a varying clock (the
+    # same launch took 345-460 us over its first 60 repetitions and 345-355 us afterwards), so
+    # the device is kept busy with the step for a stated time before the W warm-up steps.
+    spun = 0
+    t_spin = time.perf_counter()
+    while (time.perf_counter() - t_spin) * 1e3 < args.spinup_ms:
+        for _ in range(4):
+            step()
+        torch.cuda.synchronize()
+        spun += 4
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -282,6 +294,7 @@ def main() -> int:
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "spinup": {"ms": args.spinup_ms, "steps": spun},
         "ms_per_step": ms_per_step,
         "higher_is_better": True,
         "scaling": "weak",
