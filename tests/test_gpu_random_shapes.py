@@ -24,7 +24,7 @@ def _say(msg):
     print(msg, flush=True)
 
 
-DTYPES = [torch.float32, torch.bfloat16, torch.float16]
+DTYPES = [torch.float32, torch.bfloat16, torch.float16, torch.float64]
 SPECIALS = [float("nan"), float("inf"), float("-inf"), 0.0, -0.0, 1e-41, 3e38, -3e38, 6e-5]
 
 
@@ -89,7 +89,7 @@ def _segment(rs, g, dtype, n, P, unaligned):
     return synth.Segment(ref, cands, (n,), [True] * P)
 
 
-@pytest.mark.parametrize("seed", list(range(80)))
+@pytest.mark.parametrize("seed", list(range(100)))
 def test_random_launch(gu, seed):
     rs = np.random.default_rng(1000 + seed)
     g = torch.Generator(device="cuda")
@@ -97,8 +97,8 @@ def test_random_launch(gu, seed):
     S = 1 if seed % 3 else int(rs.integers(2, 6))
     segs = []
     for s in range(S):
-        dtype = DTYPES[int(rs.integers(0, 3))]
-        tile = 512 if dtype == torch.float32 else 1024
+        dtype = DTYPES[int(rs.integers(0, 4)) if seed >= 60 else int(rs.integers(0, 3))]
+        tile = {torch.float32: 512, torch.float64: 256}.get(dtype, 1024)
         big = rs.random() < 0.35
         n = int(rs.integers(1, 40 * tile)) if not big else int(rs.integers(1024 * tile, 1400 * tile))
         P = int(rs.choice([1, 2, 3, 5, 6, 7, 9, 11, 12, 13, 15, 16, 17, 20, 27, 33, 37, 48, 65]))
