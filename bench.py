@@ -237,14 +237,17 @@ def main() -> int:
         else:
             chk.check_segmented(seg_descs, stats, P, stream=stream)
 
-    # One call (one launch) for the whole step where the population has one reference per
-    # test case; the ragged workload has a different population per segment and takes two.
-    fused = (seg_descs is None or is_cases) and not args.split
+    # One call (one launch) for the whole step: evo_evaluate where the population has one
+    # reference per test case, evo_evaluate_segmented for the ragged workload.
+    fused = not args.split
+    ragged = seg_descs is not None and not is_cases
     eval_cases = seg_descs if is_cases else [{"ref": segs[0].ref, "cand_ptrs": segs[0].cands,
                                               "n_elems": segs[0].n, "dtype": dcode(segs[0])}]
 
     def step(mid=None):
-        if fused:
+        if fused and ragged:
+            chk.evaluate_segmented(seg_descs, w.timings, w.baseline, stats, P, summary, stream=stream)
+        elif fused:
             chk.evaluate(eval_cases, w.timings, w.baseline, stats, summary, stream=stream)
         else:
             check()
@@ -253,17 +256,38 @@ def main() -> int:
             chk.fitness(w.timings, w.baseline, stats, summary, stream=stream)
 
     # Spin-up: the first tens of milliseconds of load in a process run at a varying clock (the
-    # same launch took 345-460 us over its first 60 repetitions and 345-355 us afterwards), so
-    # the device is kept busy with the step for a stated time before the W warm-up steps.
-    spun = 0
+    # same launch took 345-460 us over its first 60 repetitions and 345-355 us afterwards), and
+    # on a device that has been idle the first process can run at 0.6 of its later rate for
+    # longer than that.  The device is kept busy with the step for a stated time before the W
+    # warm-up steps, and beyond it (up to 2 s) until two consecutive batches of steps take the
+    # same time within 3 %.
+    spun, per_batch = 0, 4
     t_spin = time.perf_counter()
-    while (time.perf_counter() - t_spin) * 1e3 < args.spinup_ms:
-        for _ in range(4):
+    last = None
+    while args.spinup_ms > 0:
+        t_b = time.perf_counter()
+        for _ in range(per_batch):
             step()
         torch.cuda.synchronize()
-        spun += 4
+        now = time.perf_counter()
+        spun += per_batch
+        took = now - t_b
+        if took < 1e-3:                       # batches of at least a millisecond
+            per_batch *= 4
+            last = None
+            continue
+        elapsed_ms = (now - t_spin) * 1e3
+        settled = last is not None and abs(took - last) <= 0.03 * last
+        last = took
+        if elapsed_ms >= 2000.0 or (elapsed_ms >= args.spinup_ms and settled):
+            break
+    spin_ms = (time.perf_counter() - t_spin) * 1e3
+    # the warm-up steps record events the way the timed steps do, so that whatever the runtime
+    # sets up for the first events of a process is set up before the timed region
     for _ in range(args.warmup):
-        step()
+        torch.cuda.Event(enable_timing=True).record(stream)
+        step(None if fused else torch.cuda.Event(enable_timing=True))
+    torch.cuda.Event(enable_timing=True).record(stream)
     torch.cuda.synchronize()
 
     # One event between consecutive steps (plus one inside a step when it is two launches):
@@ -294,7 +318,7 @@ def main() -> int:
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "spinup": {"ms": args.spinup_ms, "steps": spun},
+        "spinup": {"min_ms": args.spinup_ms, "ms": spin_ms, "steps": spun},
         "ms_per_step": ms_per_step,
         "higher_is_better": True,
         "scaling": "weak",
@@ -305,7 +329,7 @@ def main() -> int:
         "config": {"workload": w.name, "P": P, "cand_elems": w.cand_elems,
                    "algorithmic_bytes": alg_bytes, "T": int(w.timings.shape[1]),
                    "atol": w.atol, "rtol": w.rtol,
-                   "entry": "evo_evaluate" if fused else
+                   "entry": ("evo_evaluate_segmented" if ragged else "evo_evaluate") if fused else
                             ("evo_check_batch" if seg_descs is None else
                              "evo_check_cases" if is_cases else "evo_check_segmented") + "+evo_fitness"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -257,6 +257,20 @@ EVO_API int evo_evaluate(evo_check_t *c, const evo_segment *cases, uint32_t K,
                          evo_pop_summary *summary);
 
 /*
+ * The ragged counterpart: evo_check_segmented followed by evo_fitness_ex over the same n_rows
+ * rows (timings holds one row of T samples per evo_stats row), with the same results as those
+ * two calls in that order.  The groups must cover the rows [0, n_rows) exactly, since a row
+ * without a group would have no valid flag.  One launch under the condition given for
+ * evo_evaluate (S descriptors), else two.
+ * Arguments and errors: as evo_check_segmented and evo_fitness_ex (P = n_rows), plus
+ * EVO_ERR_SIZE when some row belongs to no group.
+ */
+EVO_API int evo_evaluate_segmented(evo_check_t *c, const evo_segment *segs, uint32_t S,
+                           const float *timings, const float *baseline, uint32_t T, int reducer,
+                           void *stream, evo_stats *stats, uint32_t n_rows,
+                           evo_pop_summary *summary);
+
+/*
  * Population management of Sec. 3.2.2 (elite preservation): the indices of the k
  * candidates with the largest fitness, best first, equal fitness in index order.  Only
  * feasible candidates (fitness > 0: valid, with usable timings) qualify; slots beyond

@@ -99,13 +99,15 @@ def _load() -> ctypes.CDLL:
     h.evo_select_elite.argtypes = [vp, vp, u32, u32, vp, vp, vp]
     h.evo_select_elite_diverse.argtypes = [vp, vp, vp, u32, u32, vp, vp, vp]
     h.evo_evaluate.argtypes = [vp, ctypes.POINTER(EvoSegment), u32, vp, vp, u32, ctypes.c_int, vp, vp, vp]
+    h.evo_evaluate_segmented.argtypes = [vp, ctypes.POINTER(EvoSegment), u32, vp, vp, u32, ctypes.c_int, vp,
+                                         vp, u32, vp]
     h.evo_time_candidates.argtypes = [vp, ctypes.POINTER(LAUNCH_FN), ctypes.POINTER(vp), u32, u32,
                                       ctypes.POINTER(EvoTimingOpts), vp, vp, ctypes.POINTER(f32)]
     h.evo_check_destroy.argtypes = [vp]
     h.evo_strerror.argtypes = [ctypes.c_int]
     h.evo_strerror.restype = ctypes.c_char_p
     for name in ("evo_check_create", "evo_check_batch", "evo_check_segmented", "evo_check_cases",
-                 "evo_fitness", "evo_fitness_ex", "evo_select_elite", "evo_time_candidates", "evo_evaluate", "evo_select_elite_diverse",
+                 "evo_fitness", "evo_fitness_ex", "evo_select_elite", "evo_time_candidates", "evo_evaluate", "evo_evaluate_segmented", "evo_select_elite_diverse",
                  "evo_check_destroy"):
         getattr(h, name).restype = ctypes.c_int
     return h
@@ -223,6 +225,17 @@ def evo_evaluate(ctx: int, cases: Sequence[dict], K: int, timings, baseline, T: 
         raise EvoError(rc, "evo_evaluate")
 
 
+def evo_evaluate_segmented(ctx: int, segs: Sequence[dict], S: int, timings, baseline, T: int, reducer: int,
+                           stream, stats, n_rows: int, summary=None) -> None:
+    """``segs`` as for evo_check_segmented."""
+    c_segs, keep = _segment_array(segs)
+    rc = lib.evo_evaluate_segmented(ctx, c_segs, int(S), _ptr(timings), _ptr(baseline), int(T), int(reducer),
+                                    _stream(stream), _ptr(stats), int(n_rows), _ptr(summary))
+    del keep
+    if rc != 0:
+        raise EvoError(rc, "evo_evaluate_segmented")
+
+
 def evo_time_candidates(ctx: int, launches, T: int, stream, timings, warmup: int = 3,
                         flush_cache: bool = False, want_clock_ratio: bool = True):
     """``launches``: one Python callable per candidate, called as f(stream_pointer); each must
@@ -322,6 +335,13 @@ class Checker:
                  reducer: int = EVO_REDUCE_MEDIAN) -> None:
         evo_evaluate(self.ctx, cases, len(cases), timings, baseline, timings.shape[1], reducer,
                      stream if stream is not None else torch.cuda.current_stream(), stats, summary)
+
+    def evaluate_segmented(self, segs: Sequence[dict], timings: torch.Tensor, baseline: torch.Tensor,
+                           stats: torch.Tensor, n_rows: int, summary: Optional[torch.Tensor] = None,
+                           stream=None, reducer: int = EVO_REDUCE_MEDIAN) -> None:
+        evo_evaluate_segmented(self.ctx, segs, len(segs), timings, baseline, timings.shape[1], reducer,
+                               stream if stream is not None else torch.cuda.current_stream(), stats,
+                               n_rows, summary)
 
     def time_candidates(self, launches, T: int, timings: torch.Tensor, warmup: int = 3,
                         flush_cache: bool = False, stream=None):

@@ -432,6 +432,29 @@ int run_check(evo_check *c, const std::vector<HostSeg> &whole, hipStream_t strea
                                    fit->summary, fit->base, fit->ticket, stream));
 }
 
+// The groups of a segmented call: each valid on its own, rows inside [0, n_rows) and not
+// shared between groups.  covered: rows that belong to some group.
+int collect_segments(const evo_segment *segs, uint32_t S, uint32_t n_rows, std::vector<HostSeg> &hs,
+                     uint64_t &covered) {
+    hs.resize(S);
+    std::vector<std::pair<uint64_t, uint64_t>> ranges(S);
+    covered = 0;
+    for (uint32_t s = 0; s < S; ++s) {
+        hs[s] = HostSeg{segs[s].ref, segs[s].cand_ptrs, segs[s].n_elems, segs[s].P_s,
+                        segs[s].dtype, segs[s].stats_row0, 0u, 1u};
+        const int rc = validate_seg(hs[s]);
+        if (rc != EVO_OK) return rc;
+        const uint64_t lo = segs[s].stats_row0, hi = lo + segs[s].P_s;
+        if (hi > n_rows) return EVO_ERR_SIZE;
+        ranges[s] = {lo, hi};
+        covered += segs[s].P_s;
+    }
+    std::sort(ranges.begin(), ranges.end());
+    for (uint32_t s = 1; s < S; ++s)
+        if (ranges[s].first < ranges[s - 1].second) return EVO_ERR_SIZE;
+    return EVO_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -484,20 +507,10 @@ int evo_check_segmented(evo_check_t *c, const evo_segment *segs, uint32_t S, voi
     if (reinterpret_cast<uintptr_t>(stats) & 7u) return EVO_ERR_ALIGN;
     if (S == 0 || n_rows == 0) return EVO_ERR_SIZE;
     try {
-        std::vector<HostSeg> hs(S);
-        std::vector<std::pair<uint64_t, uint64_t>> ranges(S);
-        for (uint32_t s = 0; s < S; ++s) {
-            hs[s] = HostSeg{segs[s].ref, segs[s].cand_ptrs, segs[s].n_elems, segs[s].P_s,
-                            segs[s].dtype, segs[s].stats_row0, 0u, 1u};
-            const int rc = validate_seg(hs[s]);
-            if (rc != EVO_OK) return rc;
-            const uint64_t lo = segs[s].stats_row0, hi = lo + segs[s].P_s;
-            if (hi > n_rows) return EVO_ERR_SIZE;
-            ranges[s] = {lo, hi};
-        }
-        std::sort(ranges.begin(), ranges.end());
-        for (uint32_t s = 1; s < S; ++s)
-            if (ranges[s].first < ranges[s - 1].second) return EVO_ERR_SIZE;
+        std::vector<HostSeg> hs;
+        uint64_t covered = 0;
+        const int rc = collect_segments(segs, S, n_rows, hs, covered);
+        if (rc != EVO_OK) return rc;
         return run_check(c, hs, static_cast<hipStream_t>(stream), stats);
     } catch (const std::bad_alloc &) {
         return EVO_ERR_NOMEM;
@@ -609,6 +622,35 @@ int evo_evaluate(evo_check_t *c, const evo_segment *cases, uint32_t K, const flo
         if ((rc = ensure_fit_rows(c, cases[0].P_s)) != EVO_OK) return rc;
         const evo::FitLaunch fit{timings, baseline, summary, c->d_base_median, c->d_fit_rows,
                                  c->d_fit_ticket, cases[0].P_s, T, (uint32_t)reducer, 1u};
+        return run_check(c, hs, st, stats, &fit);
+    } catch (const std::bad_alloc &) {
+        return EVO_ERR_NOMEM;
+    }
+}
+
+int evo_evaluate_segmented(evo_check_t *c, const evo_segment *segs, uint32_t S, const float *timings,
+                           const float *baseline, uint32_t T, int reducer, void *stream,
+                           evo_stats *stats, uint32_t n_rows, evo_pop_summary *summary) {
+    if (!is_live(c)) return EVO_ERR_HANDLE;
+    if (!segs || !stats || !timings || !baseline) return EVO_ERR_NULL;
+    if (S == 0 || n_rows == 0 || n_rows > (1u << 20) || T == 0 || T > EVO_FITNESS_MAX_T)
+        return EVO_ERR_SIZE;
+    if (reducer != EVO_REDUCE_MEDIAN && reducer != EVO_REDUCE_MEAN) return EVO_ERR_SIZE;
+    if ((reinterpret_cast<uintptr_t>(timings) & 3u) || (reinterpret_cast<uintptr_t>(baseline) & 3u) ||
+        (reinterpret_cast<uintptr_t>(stats) & 7u) || (reinterpret_cast<uintptr_t>(summary) & 3u))
+        return EVO_ERR_ALIGN;
+    try {
+        std::vector<HostSeg> hs;
+        uint64_t covered = 0;
+        int rc = collect_segments(segs, S, n_rows, hs, covered);
+        if (rc != EVO_OK) return rc;
+        if (covered != n_rows) return EVO_ERR_SIZE;   // a row without a group has no valid flag
+        if ((rc = bind_device(c)) != EVO_OK) return rc;
+        hipStream_t st = static_cast<hipStream_t>(stream);
+        if ((rc = ensure_fitness_scratch(c, st)) != EVO_OK) return rc;
+        if ((rc = ensure_fit_rows(c, n_rows)) != EVO_OK) return rc;
+        const evo::FitLaunch fit{timings, baseline, summary, c->d_base_median, c->d_fit_rows,
+                                 c->d_fit_ticket, n_rows, T, (uint32_t)reducer, 1u};
         return run_check(c, hs, st, stats, &fit);
     } catch (const std::bad_alloc &) {
         return EVO_ERR_NOMEM;

@@ -372,6 +372,29 @@ static void validation_cases() {
     EXPECT(evo_evaluate(c, cs, 2, tim, base, 5, 0, nullptr, stats, pop) == EVO_ERR_SIZE);
     cs[1].P_s = 3;
 
+    {   // ragged evaluation in one call
+        evo_segment sg[2] = {{ref, cands, 100, 3, EVO_F32, 0, 0}, {ref, cands, 7, 2, EVO_BF16, 3, 0}};
+        EXPECT(evo_evaluate_segmented(nullptr, sg, 2, tim, base, 5, 0, nullptr, stats, 5, pop) == EVO_ERR_HANDLE);
+        EXPECT(evo_evaluate_segmented(c, nullptr, 2, tim, base, 5, 0, nullptr, stats, 5, pop) == EVO_ERR_NULL);
+        EXPECT(evo_evaluate_segmented(c, sg, 2, nullptr, base, 5, 0, nullptr, stats, 5, pop) == EVO_ERR_NULL);
+        EXPECT(evo_evaluate_segmented(c, sg, 2, tim, nullptr, 5, 0, nullptr, stats, 5, pop) == EVO_ERR_NULL);
+        EXPECT(evo_evaluate_segmented(c, sg, 2, tim, base, 5, 0, nullptr, nullptr, 5, pop) == EVO_ERR_NULL);
+        EXPECT(evo_evaluate_segmented(c, sg, 0, tim, base, 5, 0, nullptr, stats, 5, pop) == EVO_ERR_SIZE);
+        EXPECT(evo_evaluate_segmented(c, sg, 2, tim, base, 0, 0, nullptr, stats, 5, pop) == EVO_ERR_SIZE);
+        EXPECT(evo_evaluate_segmented(c, sg, 2, tim, base, 5, 3, nullptr, stats, 5, pop) == EVO_ERR_SIZE);
+        EXPECT(evo_evaluate_segmented(c, sg, 2, tim, base, 5, 0, nullptr, stats, 4, pop) == EVO_ERR_SIZE);
+        EXPECT(evo_evaluate_segmented(c, sg, 2, tim, base, 5, 0, nullptr, stats, 6, pop) ==
+               EVO_ERR_SIZE);   // row 5 belongs to no group
+        sg[1].stats_row0 = 2;   // overlap
+        EXPECT(evo_evaluate_segmented(c, sg, 2, tim, base, 5, 0, nullptr, stats, 5, pop) == EVO_ERR_SIZE);
+        sg[1].stats_row0 = 3;
+        EXPECT(evo_evaluate_segmented(c, sg, 2, reinterpret_cast<const float *>(arena + 2050), base, 5, 0,
+                                      nullptr, stats, 5, pop) == EVO_ERR_ALIGN);
+        // valid arguments reach the device layer (absent where this test runs)
+        const int rcv = evo_evaluate_segmented(c, sg, 2, tim, base, 5, 0, nullptr, stats, 5, pop);
+        EXPECT(rcv == EVO_OK || rcv == EVO_ERR_DEVICE);
+    }
+
     {   // timing stage
         static int calls = 0;
         const evo_launch_fn fns[2] = {[](void *, void *) { ++calls; }, [](void *, void *) { ++calls; }};

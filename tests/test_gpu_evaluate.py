@@ -105,3 +105,64 @@ def test_evaluate_equals_check_then_fitness(gu, K, n, P, dtype, T, reducer):
     assert np.float32(pop["best_speedup"]).tobytes() == np.float32(fit["best_speedup"]).tobytes()
     assert 0 < fit["n_valid"] < P or P < 4
     chk.close()
+
+
+@pytest.mark.parametrize("shapes,T,reducer", [
+    ([(4096, 4, torch.float32)], 5, 0),                                   # one group: as evo_check_batch
+    ([(700001, 16, torch.float32), (30001, 16, torch.float32)], 100, 0),
+    ([(300001, 32, torch.float32), (128, 32, torch.float32), (1000, 32, torch.float32),
+      (262144, 32, torch.float32)], 100, 1),                              # the ragged workload in small
+    ([(600001, 17, torch.float32), (90001, 5, torch.bfloat16), (200001, 33, torch.float16)], 64, 0),
+    ([(20001, 60, torch.float32)] * 9, 7, 0),                             # 9 groups, 540 pointers: two launches
+])
+def test_evaluate_segmented_equals_check_then_fitness(gu, shapes, T, reducer):
+    _say("evaluate_segmented %s T=%d reducer=%d" % ([(n, P, str(d)) for n, P, d in shapes], T, reducer))
+    import oracle
+    import paper_2510_03760_amd as evo
+    from paper_2510_03760_amd.binding import stats_to_numpy, summary_to_numpy
+    code = {torch.float32: evo.EVO_F32, torch.bfloat16: evo.EVO_BF16, torch.float16: evo.EVO_F16}
+    ocode = {torch.float32: oracle.F32, torch.bfloat16: oracle.BF16, torch.float16: oracle.F16}
+    segs, row0 = [], 0
+    data = []
+    for i, (n, P, dtype) in enumerate(shapes):
+        (ref, cands), = _cases(1, n, P, dtype, 3000 + 17 * i + P)
+        data.append((ref, cands, dtype))
+        segs.append({"ref": ref, "cand_ptrs": cands, "n_elems": n, "dtype": code[dtype], "stats_row0": row0})
+        row0 += P
+    rows = row0
+    g = torch.Generator(device="cuda")
+    g.manual_seed(T + rows)
+    tim = torch.exp(0.1 * torch.randn(rows, T, generator=g, device="cuda")).float()
+    base = torch.exp(0.1 * torch.randn(T, generator=g, device="cuda")).float()
+    chk = evo.Checker(evo.EVO_F32, shapes[0][0], 1e-2, 1e-2)
+
+    want_stats = chk.new_stats(rows)
+    want_sum = chk.new_summary()
+    chk.check_segmented(segs, want_stats, rows)
+    chk.fitness(tim, base, want_stats, want_sum, reducer=reducer)
+    torch.cuda.synchronize()
+
+    for rep in range(3):
+        stats = chk.new_stats(rows)
+        stats.fill_(0xAB)
+        summary = chk.new_summary()
+        summary.fill_(0xCD)
+        chk.evaluate_segmented(segs, tim, base, stats, rows, summary, reducer=reducer)
+        torch.cuda.synchronize()
+        assert torch.equal(stats, want_stats), rep
+        assert torch.equal(summary, want_sum), rep
+
+    got = stats_to_numpy(stats)
+    want_rows = []
+    for ref, cands, dtype in data:
+        want_rows += oracle.check_batch(synth.to_oracle_array(ref), [synth.to_oracle_array(c) for c in cands],
+                                        ocode[dtype], 1e-2, 1e-2, threads=16)
+    for p in range(rows):
+        gu.assert_rows_equal(got[p], want_rows[p], "evaluate_segmented row %d" % p)
+    valid = np.array([r["valid"] for r in want_rows], np.uint32)
+    fit = oracle.fitness(tim.cpu().numpy(), base.cpu().numpy(), valid, reducer=reducer)
+    for f in ("median_ms", "mean_ms", "speedup", "fitness"):
+        assert got[f].tobytes() == fit[f].tobytes(), f
+    pop = summary_to_numpy(summary)[0]
+    assert int(pop["best_idx"]) == fit["best_idx"] and int(pop["n_valid"]) == fit["n_valid"]
+    chk.close()
