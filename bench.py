@@ -19,6 +19,7 @@ machine streams at best; the JSON line carries it beside the vendor peak.
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -261,6 +262,10 @@ def main() -> int:
     # longer than that.  The device is kept busy with the step for a stated time before the W
     # warm-up steps, and beyond it (up to 2 s) until two consecutive batches of steps take the
     # same time within 3 %.
+    # no cyclic garbage collection between here and the end of the timed region: with torch
+    # imported a full collection takes 5-20 ms, during which nothing is launched (as timeit does)
+    gc.collect()
+    gc.disable()
     spun, per_batch = 0, 4
     t_spin = time.perf_counter()
     last = None
@@ -303,6 +308,7 @@ def main() -> int:
         bounds[k + 1].record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    gc.enable()
 
     ms_per_step = wall * 1e3 / args.steps
     check_ms = sorted(bounds[k].elapsed_time(bounds[k + 1] if fused else mids[k]) for k in range(args.steps))
