@@ -1548,8 +1548,10 @@ evo_check_kernel_inline(const InlineTable /*read via the segment pointer*/, uint
 }
 
 // The whole evaluation of a population in one launch: the check of evo_check_kernel_inline
-// and the timing reduction of evo_fitness_kernel.  The first P + 1 workgroups of the grid
-// reduce the timing rows (they take microseconds and free their slots for check jobs); the
+// and the timing reduction of evo_fitness_kernel.  The LAST P + 1 workgroups of the grid
+// reduce the timing rows: they are dispatched when the first check jobs end and run, a few
+// microseconds each, on compute units that would otherwise idle while the slowest check jobs
+// finish (in front of the check jobs, 257 of them delayed a 512-job launch by 10-15 us); the
 // others are check jobs.  Speedup, fitness and the population figures need every median and
 // every valid flag: each timing workgroup and every workgroup that writes evo_stats rows (one
 // per case group, else one per segment; `writers` in all) take a ticket, and whoever draws
@@ -1572,14 +1574,15 @@ evo_evaluate_kernel(const InlineTable /*read via the segment pointer*/, uint32_t
                     uint32_t *__restrict__ tickets, evo_stats *__restrict__ stats, const FitArgs fit) {
     const InlineTable *tab = (const InlineTable *)__builtin_amdgcn_kernarg_segment_ptr();
     const uint32_t n_rows = fit.P + 1;
+    const uint32_t n_jobs = gridDim.x - n_rows;
     bool last;
-    if (blockIdx.x < n_rows) {
+    if (blockIdx.x >= n_jobs) {
         // the pairs go to scratch: the evo_stats rows are written whole, later, by the check
-        last = fitness_row_and_ticket(fit.timings, fit.baseline, blockIdx.x, fit.P, fit.T, stats, fit.rows,
-                                      fit.base, fit.ticket, n_rows + fit.writers - 1u);
+        last = fitness_row_and_ticket(fit.timings, fit.baseline, blockIdx.x - n_jobs, fit.P, fit.T, stats,
+                                      fit.rows, fit.base, fit.ticket, n_rows + fit.writers - 1u);
     } else {
-        if (!check_body<DTS>(tab->descs, tab->ptrs, S, atol, rtol, n_first, blockIdx.x - n_rows,
-                             gridDim.x - n_rows, partials, tickets, stats))
+        if (!check_body<DTS>(tab->descs, tab->ptrs, S, atol, rtol, n_first, blockIdx.x, n_jobs, partials,
+                             tickets, stats))
             return;
         __shared__ uint32_t drew_last;
         __syncthreads();   // every row of this workgroup is written before thread 0's release
