@@ -43,6 +43,22 @@ def _full(gu, w, label):
         torch.cuda.synchronize()
         assert torch.equal(one, stats) and torch.equal(one_sum, two_sum), label
         _say("%s: evo_evaluate gives the same bytes" % label)
+    else:
+        # likewise for the ragged workload: evo_evaluate_segmented
+        row0, descs = 0, []
+        for seg in w.segments:
+            descs.append({"ref": seg.ref, "cand_ptrs": seg.cands, "n_elems": seg.n,
+                          "dtype": gu.dtype_code(seg), "stats_row0": row0})
+            row0 += len(seg.cands)
+        one = chk.new_stats(w.P)
+        one.fill_(0xAB)
+        one_sum = chk.new_summary()
+        chk.evaluate_segmented(descs, w.timings, w.baseline, one, w.P, one_sum)
+        two_sum = chk.new_summary()
+        chk.fitness(w.timings, w.baseline, stats, two_sum)
+        torch.cuda.synchronize()
+        assert torch.equal(one, stats) and torch.equal(one_sum, two_sum), label
+        _say("%s: evo_evaluate_segmented gives the same bytes" % label)
     chk.close()
     return want, pop
 
