@@ -19,6 +19,12 @@ using evo::Partial;
 using evo::SegDesc;
 
 constexpr uint32_t kJobsPerCu = EVO_JOBS_PER_CU;
+#ifndef EVO_MIN_JOB_COST
+#define EVO_MIN_JOB_COST 128   // tile loads a job should at least take ...
+#endif
+#ifndef EVO_MIN_JOBS
+#define EVO_MIN_JOBS 256       // ... while this many jobs remain (128: slower at 2^21 x 16)
+#endif
 constexpr uint32_t kMinTilesPerWave = 4;
 constexpr uint32_t kMaxP = 65535;
 constexpr int kStageSlots = 8;
@@ -288,6 +294,11 @@ void partition(const std::vector<HostSeg> &segs, uint32_t target_jobs, std::vect
     }
     // cost one job should take
     uint64_t per_job = (cost + target_jobs - 1) / target_jobs;
+    // A job should be worth its epilogue (reduction, rows, tickets, folds): in a launch too
+    // small to give every slot such a job, jobs are made that long anyway as long as about
+    // one per compute unit remains (fp32, one candidate of 2^22 elements: 40 -> 33 us; 16
+    // candidates: 78 -> 70 us; nothing changes from 2^23 x 16 upwards or below 2^21 x 16).
+    per_job = std::max<uint64_t>(per_job, std::min<uint64_t>(EVO_MIN_JOB_COST, cost / EVO_MIN_JOBS));
     if (per_job == 0) per_job = 1;
     // The rounding up per segment can push the total past the number of workgroups the
     // machine holds at once, and the surplus would run as a second round after everything
