@@ -24,7 +24,10 @@ SPECIAL = {
 
 
 def _num(x):
-    return float(x) if not isinstance(x, str) else float(x)
+    """A JSON number, "inf"/"nan", or a C99 hexadecimal literal ("0x1.8p-3": exact)."""
+    if isinstance(x, str) and "0x" in x:
+        return float.fromhex(x)
+    return float(x)
 
 
 def _arr(xs):
@@ -92,13 +95,22 @@ def _load_examples():
 
 def pin_worked_check_examples(orc):
     for ex in _load_examples()["check"]:
-        if ex["dtype"] == "bf16":
+        if ex["dtype"] in ("bf16", "f16"):
             r = np.array(ex["ref_bits"], dtype=np.uint16)
             c = np.array(ex["cand_bits"], dtype=np.uint16)
-            dt = orc.BF16
+            dt = orc.BF16 if ex["dtype"] == "bf16" else orc.F16
+        elif ex["dtype"] == "f64":
+            r = np.array([_num(x) for x in ex["ref"]], dtype=np.float64)
+            c = np.array([_num(x) for x in ex["cand"]], dtype=np.float64)
+            dt = orc.F64
         else:
             r, c, dt = _arr(ex["ref"]), _arr(ex["cand"]), orc.F32
-        got = orc.check_one(r, c, dt, ex["atol"], ex["rtol"])
+            if ex["name"].startswith("product_rounds"):   # these inputs must be exact in binary32
+                assert [float(v) for v in r] == [_num(x) for x in ex["ref"]], ex["name"]
+                assert [float(v) for v in c] == [_num(x) for x in ex["cand"]], ex["name"]
+        atol, rtol = _num(ex["atol"]), _num(ex["rtol"])
+        assert float(np.float32(atol)) == atol and float(np.float32(rtol)) == rtol, ex["name"]
+        got = orc.check_one(r, c, dt, atol, rtol)
         for key in ("n_mismatch", "n_finite", "valid", "flags"):
             assert got[key] == ex[key], (ex["name"], key, got)
         for key in ("max_abs_err", "max_rel_err"):

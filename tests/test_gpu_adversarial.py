@@ -143,3 +143,52 @@ def test_guard_rows_around_the_result_buffer(gu):
     assert bool((elite[:4] == -1).all()) and bool((elite[8:] == -1).all())
     assert bool((elite[4:8] >= 0).all())
     chk.close()
+
+
+def _golden_example(name):
+    import json
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "worked_examples.json")
+    with open(path) as fh:
+        for ex in json.load(fh)["check"]:
+            if ex["name"] == name:
+                return ex
+    raise KeyError(name)
+
+
+def _hexnum(x):
+    return float.fromhex(x) if isinstance(x, str) and "0x" in x else float(x)
+
+
+@pytest.mark.parametrize("kind", ["f32", "bf16", "f16", "f64"])
+def test_tolerance_product_is_rounded_before_the_sum(gu, kind):
+    """The hand-built inputs of tests/golden/worked_examples.json on which
+    atol + fl(rtol*|r|) and a fused multiply-add differ by one unit in the last place, with
+    |c - r| between the two: repeated over full tiles (fast path), over a ragged tail and on
+    an unaligned view (exact path).  The mismatch count is known in closed form."""
+    ex = _golden_example("product_rounds_before_sum_" + kind)
+    atol, rtol = _hexnum(ex["atol"]), _hexnum(ex["rtol"])
+    if kind in ("bf16", "f16"):
+        tdt = torch.bfloat16 if kind == "bf16" else torch.float16
+        r = torch.tensor(np.array(ex["ref_bits"], np.uint16).view(np.int16), device="cuda").view(tdt)
+        c = torch.tensor(np.array(ex["cand_bits"], np.uint16).view(np.int16), device="cuda").view(tdt)
+    else:
+        tdt = torch.float32 if kind == "f32" else torch.float64
+        r = torch.tensor([_hexnum(x) for x in ex["ref"]], dtype=torch.float64, device="cuda").to(tdt)
+        c = torch.tensor([_hexnum(x) for x in ex["cand"]], dtype=torch.float64, device="cuda").to(tdt)
+    k = r.numel()
+    for reps, offset in ((1, 0), (3001, 0), (40000, 0), (40000, 1)):
+        _say("fused-vs-unfused tolerance %s reps=%d offset=%d" % (kind, reps, offset))
+        n = k * reps
+        # offset 1: tensors that start one element past an aligned address (no 128-bit loads)
+        ref = torch.zeros(n + offset, dtype=tdt, device="cuda")[offset:]
+        cand = torch.zeros(n + offset, dtype=tdt, device="cuda")[offset:]
+        ref.copy_(r.repeat(reps))
+        cand.copy_(c.repeat(reps))
+        seg = synth.Segment(ref, [cand, ref.clone()], (n,), [True, False])
+        t = torch.ones(2, 4, device="cuda")
+        w = synth.Workload("fma-" + kind, [seg], atol, rtol, t, torch.ones(4, device="cuda"))
+        chk, stats, want = gu.check_parity(w, label="fma")
+        assert want[0]["n_mismatch"] == ex["n_mismatch"] * reps     # the hand-computed count
+        assert want[1]["n_mismatch"] == 0
+        chk.close()

@@ -13,6 +13,9 @@ SRC = os.path.join(os.path.dirname(oracle.__file__), "evo_oracle.c")
 # (name, text in evo_oracle.c, replacement)
 MUTANTS = [
     ("tolerance_scaled_by_candidate", "const float scaled = rtol * ar;", "const float scaled = rtol * fabsf(c);"),
+    ("tolerance_fused_multiply_add", "const float tol = atol + scaled;", "const float tol = fmaf(rtol, ar, atol);"),
+    ("tolerance_product_in_binary64", "const float tol = atol + scaled;", "const float tol = (float)((double)atol + (double)rtol * (double)ar);"),
+    ("f64_tolerance_fused_multiply_add", "const double tol_d = atol_d + scaled_d;", "const double tol_d = fma(rtol_d, ard, atol_d);"),
     ("tolerance_drops_atol", "const float tol = atol + scaled;", "const float tol = scaled;"),
     ("tolerance_drops_rtol", "const float tol = atol + scaled;", "const float tol = atol;"),
     ("strict_less_than", "match = (d <= tol);", "match = (d < tol);"),
