@@ -80,19 +80,41 @@ def is_stale() -> bool:
     return any(os.path.getmtime(d) > built for d in deps)
 
 
+CACHE_DIR = os.path.join(_ROOT, "_build")   # object cache of incremental builds (not tracked)
+
+
+def _cache_key(src, extra) -> str:
+    import hashlib
+    h = hashlib.sha256(" ".join([*HIPCC_FLAGS, *extra]).encode())
+    for dep in [src, os.path.join(INCLUDE, "evo.h")] + [os.path.join(CSRC, x) for x in HEADERS]:
+        with open(dep, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:24]
+
+
 def _compile(job):
-    src, obj, extra = job
+    import shutil
+    src, obj, extra, incremental = job
+    cached = os.path.join(CACHE_DIR, _cache_key(src, extra) + ".o") if incremental else None
+    if cached and os.path.exists(cached):
+        shutil.copyfile(cached, obj)
+        return 0, "(cached) " + src, ""
     cmd = [hipcc(), *HIPCC_FLAGS, *extra, "-I", INCLUDE, "-I", CSRC, "-DEVO_BUILDING=1", "-c", "-o", obj, src]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if cached and res.returncode == 0:
+        os.makedirs(CACHE_DIR, exist_ok=True)
+        shutil.copyfile(obj, cached + ".tmp.%d" % os.getpid())
+        os.replace(cached + ".tmp.%d" % os.getpid(), cached)
     # the host pass warns that it does not know the packed-fp32 feature: harmless
     out = "\n".join(l for l in res.stdout.splitlines()
                     if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)
     return res.returncode, " ".join(cmd), out
 
 
-def build(verbose: bool = False, extra_flags=(), jobs: int = 0) -> str:
+def build(verbose: bool = False, extra_flags=(), jobs: int = 0, incremental: bool = False) -> str:
     """Compiles every HIP source into paper_2510_03760_amd/libevo.so: one object per source
-    (and per element-type set of the check kernel), side by side, then one link."""
+    (and per element-type set of the check kernel), side by side, then one link.
+    incremental: objects whose source, headers and flags have not changed come from _build/."""
     import shutil
     import tempfile
     from concurrent.futures import ThreadPoolExecutor
@@ -100,8 +122,8 @@ def build(verbose: bool = False, extra_flags=(), jobs: int = 0) -> str:
     work = tempfile.mkdtemp(prefix="evo_build_")
     try:
         todo = [(os.path.join(CSRC, CHECK_INST), os.path.join(work, "check_%d.o" % m),
-                 extra + ["-DEVO_INST_DTS=%du" % m]) for m in reversed(CHECK_SETS)]   # longest first
-        todo += [(src, os.path.join(work, os.path.basename(src) + ".o"), extra) for src in sources()]
+                 extra + ["-DEVO_INST_DTS=%du" % m], incremental) for m in reversed(CHECK_SETS)]   # longest first
+        todo += [(src, os.path.join(work, os.path.basename(src) + ".o"), extra, incremental) for src in sources()]
         workers = jobs or max(1, min(len(todo), os.cpu_count() or 1, 16))
         with ThreadPoolExecutor(max_workers=workers) as ex:
             results = list(ex.map(_compile, todo))
@@ -127,4 +149,6 @@ def build(verbose: bool = False, extra_flags=(), jobs: int = 0) -> str:
 
 
 if __name__ == "__main__":
-    print(build(verbose=True, extra_flags=sys.argv[1:]))
+    args = sys.argv[1:]
+    print(build(verbose=True, extra_flags=[a for a in args if a != "--incremental"],
+                incremental="--incremental" in args))
