@@ -73,7 +73,8 @@ typedef enum {
                          /* an output pointer not to its record (stats: 8 bytes) */
     EVO_ERR_DEVICE = -6, /* a HIP call failed (no device, launch error, ...)    */
     EVO_ERR_NOMEM  = -7, /* host or device allocation failed                    */
-    EVO_ERR_HANDLE = -8  /* not a live context (never created, or destroyed)    */
+    EVO_ERR_HANDLE = -8, /* not a live context (never created, or destroyed)    */
+    EVO_ERR_LIMIT  = -9  /* beyond the fixed capacity of evo_check_batch_static */
 } evo_status;
 
 /* Bits of evo_stats.flags */
@@ -170,6 +171,29 @@ EVO_API int evo_check_create(evo_check_t **out, evo_dtype dtype, uint64_t n_elem
  */
 EVO_API int evo_check_batch(evo_check_t *c, const void *ref, const void *const *cand_ptrs,
                     uint32_t P, void *stream, evo_stats *stats);
+
+/*
+ * evo_check_batch for callers that cannot allocate device memory: code that runs under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same kernels and, for the same arguments, the same stats rows as evo_check_batch; but
+ * the partial rows and ticket counters live in a fixed array in the library's device image
+ * (EVO_STATIC_SCRATCH_BYTES, about 6 MiB, held by every GPU the library is loaded on until
+ * the process ends) instead of context-owned memory, and the call neither allocates nor
+ * frees anything, on the device or on the host.  Its first call on a device looks the
+ * array's address up (make that call outside a capture).
+ * Capacity: P <= 384 after rounding the candidates beyond the last full group of 16 up to a
+ * power of two, and at most EVO_STATIC_MAX_JOBS workgroups (a launch is planned for two
+ * per compute unit, so on an MI355X only tensors of several GiB each come near it); beyond
+ * it the call returns EVO_ERR_LIMIT and enqueues nothing.
+ * All calls on one GPU share the one array: calls that overlap in time on one GPU (two
+ * streams, two threads, two contexts) race, and the caller must serialise them.  The ticket
+ * counters are cleared by a small kernel in front of the check, so the call is two launches.
+ * Errors: as evo_check_batch, plus EVO_ERR_LIMIT.
+ */
+#define EVO_STATIC_MAX_JOBS 1024u
+#define EVO_STATIC_SCRATCH_BYTES 6314048u
+EVO_API int evo_check_batch_static(evo_check_t *c, const void *ref, const void *const *cand_ptrs,
+                                   uint32_t P, void *stream, evo_stats *stats);
 
 /*
  * The same check over S ragged groups in ONE launch (the test cases and output

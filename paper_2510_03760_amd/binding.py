@@ -92,6 +92,7 @@ def _load() -> ctypes.CDLL:
     vp, u32, u64, f32 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_float
     h.evo_check_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, u64, f32, f32]
     h.evo_check_batch.argtypes = [vp, vp, ctypes.POINTER(vp), u32, vp, vp]
+    h.evo_check_batch_static.argtypes = [vp, vp, ctypes.POINTER(vp), u32, vp, vp]
     h.evo_check_segmented.argtypes = [vp, ctypes.POINTER(EvoSegment), u32, vp, vp, u32]
     h.evo_check_cases.argtypes = [vp, ctypes.POINTER(EvoSegment), u32, vp, vp]
     h.evo_fitness.argtypes = [vp, vp, vp, u32, u32, vp, vp, vp]
@@ -106,7 +107,7 @@ def _load() -> ctypes.CDLL:
     h.evo_check_destroy.argtypes = [vp]
     h.evo_strerror.argtypes = [ctypes.c_int]
     h.evo_strerror.restype = ctypes.c_char_p
-    for name in ("evo_check_create", "evo_check_batch", "evo_check_segmented", "evo_check_cases",
+    for name in ("evo_check_create", "evo_check_batch", "evo_check_batch_static", "evo_check_segmented", "evo_check_cases",
                  "evo_fitness", "evo_fitness_ex", "evo_select_elite", "evo_time_candidates", "evo_evaluate", "evo_evaluate_segmented", "evo_select_elite_diverse",
                  "evo_check_destroy"):
         getattr(h, name).restype = ctypes.c_int
@@ -152,6 +153,13 @@ def evo_check_batch(ctx: int, ref, cand_ptrs: Sequence, P: int, stream, stats) -
                              _stream(stream), _ptr(stats))
     if rc != 0:
         raise EvoError(rc, "evo_check_batch")
+
+
+def evo_check_batch_static(ctx: int, ref, cand_ptrs: Sequence, P: int, stream, stats) -> None:
+    arr = (ctypes.c_void_p * max(1, len(cand_ptrs)))(*[_ptr(c) for c in cand_ptrs])
+    rc = lib.evo_check_batch_static(ctx, _ptr(ref), arr, int(P), _stream(stream), _ptr(stats))
+    if rc != 0:
+        raise EvoError(rc, "evo_check_batch_static")
 
 
 def _segment_array(segs: Sequence[dict]):
@@ -301,6 +309,11 @@ class Checker:
                     stream=None) -> None:
         evo_check_batch(self.ctx, ref, list(cands), len(cands),
                         stream if stream is not None else torch.cuda.current_stream(), stats)
+
+    def check_batch_static(self, ref: torch.Tensor, cands: Sequence[torch.Tensor], stats: torch.Tensor,
+                           stream=None) -> None:
+        evo_check_batch_static(self.ctx, ref, list(cands), len(cands),
+                               stream if stream is not None else torch.cuda.current_stream(), stats)
 
     def check_segmented(self, segs: Sequence[dict], stats: torch.Tensor, n_rows: int,
                         stream=None) -> None:

@@ -41,6 +41,21 @@ struct StageSlot {
 
 }  // namespace
 
+// Scratch of evo_check_batch_static, the one call that allocates nothing: partial rows of
+// at most kStaticMaxJobs jobs and of kInlinePtrs case rows, then the tickets.  Every device
+// the library's code is loaded on holds its own copy until the process ends.  In host code
+// the array's name is only a handle for hipGetSymbolAddress: kernels, copies and fills get
+// the address that call returns for the current device (static_scratch()).
+constexpr uint32_t kStaticMaxJobs = 1024;
+constexpr size_t kStaticPartialRows = 2 * (size_t)kStaticMaxJobs * evo::kRowsPerJob + evo::kInlinePtrs;
+constexpr size_t kStaticTicketWords = kStaticMaxJobs + 2 * evo::kInlineSegs;
+constexpr size_t kStaticPartialBytes = kStaticPartialRows * sizeof(evo::Partial);
+constexpr size_t kStaticScratchBytes = kStaticPartialBytes + kStaticTicketWords * sizeof(uint32_t);
+static_assert(kStaticPartialBytes % 256 == 0, "the tickets start on a 256-byte boundary");
+static_assert(kStaticMaxJobs == EVO_STATIC_MAX_JOBS && kStaticScratchBytes == EVO_STATIC_SCRATCH_BYTES,
+              "evo.h states the capacity");
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 struct evo_check {
     evo_dtype dtype;
     uint64_t n_elems;
@@ -74,6 +89,24 @@ namespace {
 
 std::mutex g_mu;
 std::set<evo_check *> g_live;
+
+// Device address of `scratch` on each device, looked up once per device.
+constexpr int kMaxDevices = 64;
+void *g_static_ptr[kMaxDevices];   // guarded by g_mu
+
+int static_scratch(int device, unsigned char **out) {
+    if (device < 0 || device >= kMaxDevices) return EVO_ERR_DEVICE;
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!g_static_ptr[device]) {
+        // `device` is the current device (bind_device): the address is this device's copy
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return EVO_ERR_DEVICE;
+        g_static_ptr[device] = p;
+    }
+    *out = static_cast<unsigned char *>(g_static_ptr[device]);
+    return EVO_OK;
+}
 
 bool is_live(evo_check *c) {
     std::lock_guard<std::mutex> lk(g_mu);
@@ -243,26 +276,31 @@ double heavy_share(uint32_t n_heavy, uint32_t n_groups) {
 // accumulator over several segments).
 constexpr uint64_t kSplitMinTiles = 1024;
 
-void split_remainders(const std::vector<HostSeg> &in, std::vector<HostSeg> &out) {
-    out.clear();
-    out.reserve(in.size() * 2);
-    for (const HostSeg &h : in) {
-        const uint32_t rem = h.P % (uint32_t)evo::kG, n_full = h.P / (uint32_t)evo::kG;
-        const uint64_t tiles = (h.n + evo::tile_elems(h.dtype) - 1) / evo::tile_elems(h.dtype);
-        const bool gains = n_full > 0 && rem != 0 && rem <= (uint32_t)evo::kG / 4 &&
-                           heavy_share(n_full, n_full) - heavy_share(n_full, n_full + 1) >= 0.25;
-        if (h.n_cases > 1 || !gains || tiles < kSplitMinTiles) {
-            out.push_back(h);
-            continue;
-        }
-        HostSeg full = h, rest = h;
-        full.P = h.P - rem;
-        rest.P = rem;
-        rest.cand_ptrs = h.cand_ptrs + full.P;
-        rest.row0 = h.row0 + full.P;
-        out.push_back(full);
-        out.push_back(rest);
+// out: room for two segments; returns how many were written (1 or 2).
+size_t split_remainder(const HostSeg &h, HostSeg *out) {
+    const uint32_t rem = h.P % (uint32_t)evo::kG, n_full = h.P / (uint32_t)evo::kG;
+    const uint64_t tiles = (h.n + evo::tile_elems(h.dtype) - 1) / evo::tile_elems(h.dtype);
+    const bool gains = n_full > 0 && rem != 0 && rem <= (uint32_t)evo::kG / 4 &&
+                       heavy_share(n_full, n_full) - heavy_share(n_full, n_full + 1) >= 0.25;
+    if (h.n_cases > 1 || !gains || tiles < kSplitMinTiles) {
+        out[0] = h;
+        return 1;
     }
+    HostSeg full = h, rest = h;
+    full.P = h.P - rem;
+    rest.P = rem;
+    rest.cand_ptrs = h.cand_ptrs + full.P;
+    rest.row0 = h.row0 + full.P;
+    out[0] = full;
+    out[1] = rest;
+    return 2;
+}
+
+void split_remainders(const std::vector<HostSeg> &in, std::vector<HostSeg> &out) {
+    out.resize(in.size() * 2);
+    size_t n = 0;
+    for (const HostSeg &h : in) n += split_remainder(h, out.data() + n);
+    out.resize(n);
 }
 
 // Splits every segment into jobs (workgroups) of similar cost.  Cost unit: one tile load
@@ -271,11 +309,11 @@ void split_remainders(const std::vector<HostSeg> &in, std::vector<HostSeg> &out)
 // compute unit, all resident at once), so that the per-job epilogue -- cross-lane
 // reduction, partial rows, ticket -- is paid once per wavefront slot and not once per few
 // tiles.
-void partition(const std::vector<HostSeg> &segs, uint32_t target_jobs, std::vector<SegDesc> &descs,
+// descs: room for n_segs descriptors.  Allocates nothing.
+void partition(const HostSeg *segs, size_t n_segs, uint32_t target_jobs, SegDesc *descs,
                uint32_t &total_jobs) {
-    descs.resize(segs.size());
     uint64_t cost = 0;   // summed over all jobs: steps x cost of a step
-    for (size_t s = 0; s < segs.size(); ++s) {
+    for (size_t s = 0; s < n_segs; ++s) {
         const HostSeg &h = segs[s];
         SegDesc &d = descs[s];
         d.n = h.n;
@@ -308,7 +346,7 @@ void partition(const std::vector<HostSeg> &segs, uint32_t target_jobs, std::vect
     for (int attempt = 0; attempt < 64; ++attempt) {
         job0 = 0;
         bool any_free = false;   // some segment could still take longer jobs
-        for (size_t s = 0; s < segs.size(); ++s) {
+        for (size_t s = 0; s < n_segs; ++s) {
             SegDesc &d = descs[s];
             const uint64_t tiles = (d.n + evo::tile_elems(d.dtype) - 1) / evo::tile_elems(d.dtype);
             const uint32_t tpw = evo::kWaves / d.gpw;
@@ -335,9 +373,10 @@ void partition(const std::vector<HostSeg> &segs, uint32_t target_jobs, std::vect
 
 // Upper bound on what partition() can produce for these segments (checked before any
 // allocation): every count must stay inside 32 bits.
-bool partition_fits(const std::vector<HostSeg> &segs) {
+bool partition_fits(const HostSeg *segs, size_t n_segs) {
     uint64_t jobs = 0;
-    for (const HostSeg &h : segs) {
+    for (size_t s = 0; s < n_segs; ++s) {
+        const HostSeg &h = segs[s];
         const uint64_t tiles = (h.n + evo::tile_elems(h.dtype) - 1) / evo::tile_elems(h.dtype);
         const uint64_t groups = evo::group_count(h.P);
         jobs += (tiles / kMinTilesPerWave + 1) * groups;
@@ -364,16 +403,17 @@ int run_check(evo_check *c, const std::vector<HostSeg> &whole, hipStream_t strea
         EVO_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device));
         c->n_cus = cus > 0 ? (uint32_t)cus : 1u;
     }
-    if (!partition_fits(segs)) return EVO_ERR_SIZE;
+    if (!partition_fits(segs.data(), segs.size())) return EVO_ERR_SIZE;
 
     std::vector<SegDesc> descs;
     uint32_t total_jobs = 0;
     size_t total_ptrs = 0;
     try {
-        partition(segs, c->n_cus * kJobsPerCu, descs, total_jobs);
+        descs.resize(segs.size());
     } catch (const std::bad_alloc &) {
         return EVO_ERR_NOMEM;
     }
+    partition(segs.data(), segs.size(), c->n_cus * kJobsPerCu, descs.data(), total_jobs);
     uint32_t dtype_set = 0;
     for (size_t s = 0; s < segs.size(); ++s) {
         total_ptrs += descs[s].P;
@@ -509,6 +549,60 @@ int evo_check_batch(evo_check_t *c, const void *ref, const void *const *cand_ptr
     } catch (const std::bad_alloc &) {
         return EVO_ERR_NOMEM;
     }
+}
+
+int evo_check_batch_static(evo_check_t *c, const void *ref, const void *const *cand_ptrs, uint32_t P,
+                           void *stream, evo_stats *stats) {
+    if (!is_live(c)) return EVO_ERR_HANDLE;
+    if (!stats) return EVO_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(stats) & 7u) return EVO_ERR_ALIGN;
+    const HostSeg h{ref, cand_ptrs, c->n_elems, P, (uint32_t)c->dtype, 0u, 0u, 1u};
+    int rc = validate_seg(h);
+    if (rc != EVO_OK) return rc;
+    if (P > evo::kInlinePtrs) return EVO_ERR_LIMIT;
+    if ((rc = bind_device(c)) != EVO_OK) return rc;
+    if (c->n_cus == 0) {
+        int cus = 0;
+        EVO_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device));
+        c->n_cus = cus > 0 ? (uint32_t)cus : 1u;
+    }
+    unsigned char *base = nullptr;
+    if ((rc = static_scratch(c->device, &base)) != EVO_OK) return rc;
+
+    // the same plan as evo_check_batch, on the stack
+    HostSeg segs[2];
+    const size_t S = split_remainder(h, segs);
+    if (!partition_fits(segs, S)) return EVO_ERR_SIZE;
+    SegDesc descs[2];
+    uint32_t total_jobs = 0;
+    partition(segs, S, c->n_cus * kJobsPerCu, descs, total_jobs);
+    size_t total_ptrs = 0;
+    for (size_t s = 0; s < S; ++s) {
+        descs[s].ref = segs[s].ref;
+        descs[s].ptr0 = total_ptrs;
+        total_ptrs += descs[s].P;
+    }
+    if (total_jobs > kStaticMaxJobs || total_ptrs > evo::kInlinePtrs) return EVO_ERR_LIMIT;
+
+    evo::InlineTable tab;
+    std::memset(&tab, 0, sizeof tab);
+    for (size_t s = 0; s < S; ++s) {
+        tab.descs[s] = descs[s];
+        for (uint32_t p = 0; p < descs[s].P; ++p)
+            tab.ptrs[descs[s].ptr0 + p] =
+                reinterpret_cast<uint64_t>(p < segs[s].P ? segs[s].cand_ptrs[p] : segs[s].ref);
+    }
+    uint32_t dtype_set = 1u << (uint32_t)c->dtype;
+    Partial *partials = reinterpret_cast<Partial *>(base);
+    uint32_t *tickets = reinterpret_cast<uint32_t *>(base + kStaticPartialBytes);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // The tickets must be zero when the kernel starts.  Every launch leaves them at zero, but
+    // the array is shared by all callers on this device and outlives a launch that failed: they
+    // are cleared by a small fill kernel in front (not a memset node, so that the pair of
+    // launches can be captured into a graph).
+    EVO_TRY(evo::launch_flush(tickets, ((size_t)total_jobs + 2 * S) * sizeof(uint32_t), 0u, st));
+    return dev(evo::launch_check_inline(dtype_set, tab, (uint32_t)S, total_jobs, c->atol, c->rtol, c->n_cus,
+                                        partials, tickets, stats, st));
 }
 
 int evo_check_segmented(evo_check_t *c, const evo_segment *segs, uint32_t S, void *stream,
@@ -792,6 +886,7 @@ const char *evo_strerror(int code) {
         case EVO_ERR_DEVICE: return "HIP call failed";
         case EVO_ERR_NOMEM: return "out of memory";
         case EVO_ERR_HANDLE: return "not a live context";
+        case EVO_ERR_LIMIT: return "beyond the fixed capacity of the call that allocates nothing";
         default: return "unknown status";
     }
 }

@@ -33,8 +33,10 @@ evo_probe_kernel(float *__restrict__ sink, uint32_t iterations, float seed) {
 }  // namespace
 
 hipError_t launch_flush(void *buf, size_t bytes, uint32_t value, hipStream_t stream) {
-    hipLaunchKernelGGL(evo_flush_kernel, dim3(2048), dim3(kThreads), 0, stream,
-                       static_cast<uint32_t *>(buf), bytes / sizeof(uint32_t), value);
+    const size_t n_words = bytes / sizeof(uint32_t);
+    const size_t blocks = (n_words + kThreads - 1) / kThreads;   // small fills: no idle workgroups
+    hipLaunchKernelGGL(evo_flush_kernel, dim3((unsigned)(blocks < 1 ? 1 : blocks > 2048 ? 2048 : blocks)),
+                       dim3(kThreads), 0, stream, static_cast<uint32_t *>(buf), n_words, value);
     return hipGetLastError();
 }
 

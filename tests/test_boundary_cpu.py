@@ -27,7 +27,7 @@ def declared_functions():
 
 
 def test_header_declares_the_documented_entry_points():
-    assert declared_functions() == ["evo_check_batch", "evo_check_cases", "evo_check_create",
+    assert declared_functions() == ["evo_check_batch", "evo_check_batch_static", "evo_check_cases", "evo_check_create",
                                     "evo_check_destroy", "evo_check_segmented", "evo_evaluate",
                                     "evo_evaluate_segmented",
                                     "evo_fitness",
