@@ -43,6 +43,8 @@ constexpr float kInf = __builtin_huge_valf();
 constexpr float kFltMin = 1.17549435e-38f;
 constexpr double kInfD = __builtin_huge_val();
 constexpr double kDblMin = 2.2250738585072014e-308;
+constexpr float kModerate = 0x1p102f;   // see fast_tiles
+static_assert(kModerate <= kRecipShortcutBelow, "the reciprocal shortcut must be exact below kModerate");
 constexpr int kDepth = EVO_DEPTH;
 constexpr uint32_t kRotate = EVO_ROTATE;   // slot rotation per step (odd)
 
@@ -400,6 +402,17 @@ __device__ __forceinline__ u32x4 load16(const char *base, uint32_t lane_off) {
     return *p;
 }
 
+// The same from a per-lane address.
+template <bool STREAM>
+__device__ __forceinline__ u32x4 load16_at(uint64_t addr) {
+    typedef __attribute__((address_space(1))) const u32x4 global_u32x4;
+    global_u32x4 *p = (global_u32x4 *)addr;
+#if EVO_NT_LOADS
+    if constexpr (STREAM) return __builtin_nontemporal_load(p);
+#endif
+    return *p;
+}
+
 // max(m, |a|, |b|) and max(m, a, b) in one instruction each.  Operands are finite
 // whenever the result is used (tiles holding anything else are redone exactly).
 __device__ __forceinline__ float max3_abs(float m, float a, float b) {
@@ -418,11 +431,19 @@ __device__ __forceinline__ float max3(float m, float a, float b) {
     return o;
 }
 
-// Pairwise sum of N values (of their magnitudes when ABS), N a power of two.
+// |a| + |b| in one instruction (the magnitudes as source modifiers; left to itself the
+// compiler first clears the sign bits with one v_and_b32 per operand).
+__device__ __forceinline__ float add_abs2(float a, float b) {
+    float o;
+    asm("v_add_f32_e64 %0, |%1|, |%2|" : "=v"(o) : "v"(a), "v"(b));
+    return o;
+}
+
+// Pairwise sum of N values (of their magnitudes when ABS), N a power of two >= 2.
 template <int N, bool ABS>
 __device__ __forceinline__ float tree_sum(const float *v) {
-    if constexpr (N == 1) {
-        return ABS ? __builtin_fabsf(v[0]) : v[0];
+    if constexpr (N == 2) {
+        return ABS ? add_abs2(v[0], v[1]) : v[0] + v[1];
     } else {
         return tree_sum<N / 2, ABS>(v) + tree_sum<N / 2, ABS>(v + N / 2);
     }
@@ -592,7 +613,7 @@ __device__ __forceinline__ void exact_candidate_pass(const char *rptr, const cha
 // (counts in registers, exclusions and flags in xacc).  Ends with the lanes -> wavefront
 // reduction into wpart[0 .. NC).
 template <uint32_t DT, int NC, bool REF_STREAM, bool PADDED>
-__device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_ptr_of_lane,
+__device__ __forceinline__ uint32_t fast_tiles(const char *rptr, const uint64_t *cptr_lds_generic,
                                                const TileWalk walk, uint64_t t_fend,
                                                float atol, float rtol, int lane, bool second_round,
                                                uint32_t n_real, uint16_t *redo, Partial *wpart,
@@ -606,16 +627,22 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_p
                   "pairwise fp32 trees: at most 4 roundings deep keeps the sums inside 1e-6");
     const uint32_t lane_off = (uint32_t)lane * 16u;
 
+    // The NC candidate pointers stay in LDS (cptr_lds[g], one broadcast read per use) and a
+    // candidate's address is formed per lane; as NC wave-uniform register pairs they -- and
+    // NC wave-uniform mismatch counters -- left no scalar registers for anything else, and
+    // the loop spent a sixth of its vector instructions moving scalars in and out of
+    // vector lanes.  Mismatches are counted in the wavefront's LDS record (xacc) instead:
+    // they are rare.
     Acc acc[NC];
-    uint32_t n_mismatch[NC];
-    const char *cptr[NC];
 #pragma unroll
-    for (int g = 0; g < NC; ++g) {
-        acc[g] = Acc{0.0f, 0.0f, 0.0, 0.0};
-        n_mismatch[g] = 0;
-        cptr[g] = lane_ptr(cand_ptr_of_lane, g);
-    }
+    for (int g = 0; g < NC; ++g) acc[g] = Acc{0.0f, 0.0f, 0.0, 0.0};
     uint32_t any_redo = 0;
+    // The table's LDS address is kept in a vector register (LDS reads take their address
+    // from one; as a wave-uniform value it would be moved there before every read).
+    typedef __attribute__((address_space(3))) const uint64_t lds_u64;
+    uint32_t table_addr = (uint32_t)(uintptr_t)(lds_u64 *)cptr_lds_generic;
+    asm volatile("" : "+v"(table_addr));
+    lds_u64 *cptr_lds = (lds_u64 *)(uintptr_t)table_addr;
 
     const uint32_t k_end = walk.steps_below(t_fend);
     if (k_end > 0) {
@@ -623,12 +650,13 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_p
         u32x4 buf[D][kNV];
         {
             const uint64_t off = walk.at(0) * kTileBytes;
+            const uint64_t voff = off + lane_off;
 #pragma unroll
             for (int j = 0; j < kNV; ++j) ref_raw[j] = load16<REF_STREAM>(rptr + off + j * 1024, lane_off);
 #pragma unroll
             for (int g = 0; g < D; ++g)
 #pragma unroll
-                for (int j = 0; j < kNV; ++j) buf[g][j] = load16<true>(cptr[g] + off + j * 1024, lane_off);
+                for (int j = 0; j < kNV; ++j) buf[g][j] = load16_at<true>(cptr_lds[g] + voff + j * 1024);
         }
         uint64_t t = walk.at(0);
         for (uint32_t slot = 0; slot < k_end; ++slot) {
@@ -643,20 +671,26 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_p
             // (a few redundant, in-bounds loads instead of a branch per load)
             const uint64_t t_next = (slot + 1 < k_end) ? walk.at(slot + 1) : t;
             const uint64_t off_next = t_next * kTileBytes;
+            const uint64_t voff = off + lane_off, voff_next = off_next + lane_off;   // per lane
 
             float r[kE], inv[kE];
 #pragma unroll
             for (int j = 0; j < kNV; ++j) widen<DT>(ref_raw[j], &r[j * TL::kVec]);
 #pragma unroll
             for (int j = 0; j < kNV; ++j) ref_raw[j] = load16<REF_STREAM>(rptr + off_next + j * 1024, lane_off);
+            // One test per reference element serves two shortcuts: below kModerate (2^102, far
+            // inside the range where the reciprocal shortcut is exact) the reciprocal needs no
+            // division, and a candidate tile without a single number in it can be settled on
+            // the spot (see below).  A NaN reference element fails the test too.
             bool huge = false;
 #pragma unroll
             for (int e = 0; e < kE; ++e) {
                 const float ar = __builtin_fabsf(r[e]);
                 inv[e] = ar >= kFltMin ? recip_shortcut(ar) : 0.0f;
-                huge = huge || !(ar < kRecipShortcutBelow);
+                huge = huge || !(ar < kModerate);
             }
-            if (ballot(huge) != 0) {   // |r| >= 2^126 somewhere in the tile: true division
+            const bool moderate_tile = ballot(huge) == 0;
+            if (!moderate_tile) {   // |r| >= 2^102 or NaN somewhere in the tile: true division
 #pragma unroll
                 for (int e = 0; e < kE; ++e) {
                     const float ar = __builtin_fabsf(r[e]);
@@ -683,8 +717,8 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_p
                 if (!PADDED || (uint32_t)((g + D) % NC) < n_real) {
 #pragma unroll
                     for (int j = 0; j < kNV; ++j)
-                        buf[g % D][j] = load16<true>(cptr[(g + D) % NC] + (g + D < NC ? off : off_next) + j * 1024,
-                                               lane_off);
+                        buf[g % D][j] = load16_at<true>(cptr_lds[(g + D) % NC] + (g + D < NC ? voff : voff_next) +
+                                                        j * 1024);
                 }
                 if (!real) continue;
 #pragma unroll
@@ -710,9 +744,14 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_p
                 // whole wavefront as soon as one lane cannot rule a mismatch out.
                 uint32_t mism = 0;
                 if (ballot(!(t_abs <= atol)) != 0) {
+                    // (rtol through an opaque copy: the tolerances are then worked out here,
+                    // where they are needed, and not once per tile for every candidate's sake,
+                    // which cost kE vector registers and 2 kE instructions per tile)
+                    float rtol_here = rtol;
+                    asm volatile("" : "+s"(rtol_here));
 #pragma unroll
                     for (int e = 0; e < kE; ++e) {
-                        const float scaled = rtol * __builtin_fabsf(r[e]);
+                        const float scaled = rtol_here * __builtin_fabsf(r[e]);
                         const float tol = atol + scaled;
                         mism += popc64(ballot(!(__builtin_fabsf(d[e]) <= tol)));
                     }
@@ -725,7 +764,7 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_p
                     acc[g].max_rel = m_rel;
                     acc[g].sum_abs = s_abs;
                     acc[g].sum_rel = s_rel;
-                    n_mismatch[g] += mism;
+                    if (mism != 0 && lane == 0) xacc[g].n_mismatch += mism;
                 } else {
                     // What a broken kernel tends to produce: a tile without a single number in
                     // it, NaN or +-Inf throughout.  Over reference elements below 2^102 in
@@ -741,11 +780,11 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_p
                         const uint64_t is_inf = ballot(__builtin_fabsf(d[e]) == kInf);
                         any_nan |= is_nan;
                         any_inf |= is_inf;
-                        number |= ~(is_nan | is_inf) | ballot(!(__builtin_fabsf(r[e]) < 0x1p102f));
+                        number |= ~(is_nan | is_inf);
                     }
-                    if (number == 0) {
-                        n_mismatch[g] += (uint32_t)tile_elems(DT);
+                    if (moderate_tile && number == 0) {
                         if (lane == 0) {
+                            xacc[g].n_mismatch += (uint32_t)tile_elems(DT);
                             xacc[g].n_excluded += (uint32_t)tile_elems(DT);
                             xacc[g].flags |= (any_nan ? EVO_F_CAND_NAN | EVO_F_NAN_SITE_DIFF : 0u) |
                                              (any_inf ? EVO_F_CAND_INF | EVO_F_INF_DIFF : 0u);
@@ -781,7 +820,7 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, uint64_t cand_p
 #pragma unroll
         for (int g = 0; g < NC; ++g) {
             Partial p;
-            p.n_mismatch = n_mismatch[g];
+            p.n_mismatch = 0;   // counted in xacc
             p.n_excluded = 0;
             p.sum_abs = last_lane_f64(acc[g].sum_abs);
             p.sum_rel = last_lane_f64(acc[g].sum_rel);
@@ -1049,7 +1088,8 @@ template <uint32_t DT, bool SKIP>
 __device__ __forceinline__ void run_job(const SegDesc &sd, const uint64_t *ptr_table, uint32_t job_local,
                         uint32_t job_global, float atol, float rtol, bool second_round,
                         Partial *partials, ExactAcc (*exact_acc)[kG],
-                        Partial (*wave_part)[kG], uint16_t (*redo)[kMaxTilesPerWave]) {
+                        Partial (*wave_part)[kG], uint16_t (*redo)[kMaxTilesPerWave],
+                        uint64_t (*cand_lds)[kG]) {
     constexpr uint32_t kTileElems = tile_elems(DT);
     const int lane = (int)(threadIdx.x & (kLanes - 1));
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -1099,6 +1139,8 @@ __device__ __forceinline__ void run_job(const SegDesc &sd, const uint64_t *ptr_t
         cand_ptr_of_lane = ((global_u64 *)(uintptr_t)ptr_table)[sd.ptr0 + grp.cand0 + lane];
     }
     const bool vec_ok = ((uintptr_t)rptr & 15u) == 0 && ballot((cand_ptr_of_lane & 15u) != 0) == 0;
+    // the same pointers in LDS, for fast_tiles (written and read by this wavefront only)
+    if (lane < kG) cand_lds[wave][lane] = cand_ptr_of_lane;
 
     // the segment's last group may end in stand-ins (SegDesc::n_pad)
     const uint32_t n_real = __builtin_amdgcn_readfirstlane(group + 1 == sd.n_groups ? nc - sd.n_pad : nc);
@@ -1116,6 +1158,15 @@ __device__ __forceinline__ void run_job(const SegDesc &sd, const uint64_t *ptr_t
 #define EVO_TILES_PADDED(FN_, NC_)                                                             \
     any_redo = FN_<DT, NC_, true, (SKIP && NC_ >= 4)>(rptr, cand_ptr_of_lane, walk, n_full, atol, rtol, \
                                                       lane, second_round, n_real, rd, wp, exact_acc[wave])
+#define EVO_TILES_LDS(FN_, NC_)                                                                \
+    any_redo = (gpw == 1)                                                                      \
+        ? FN_<DT, NC_, true, false>(rptr, cand_lds[wave], walk, n_full, atol, rtol, lane,       \
+                                    second_round, n_real, rd, wp, exact_acc[wave])              \
+        : FN_<DT, NC_, false, false>(rptr, cand_lds[wave], walk, n_full, atol, rtol, lane,      \
+                                     second_round, n_real, rd, wp, exact_acc[wave])
+#define EVO_TILES_PADDED_LDS(FN_, NC_)                                                         \
+    any_redo = FN_<DT, NC_, true, (SKIP && NC_ >= 4)>(rptr, cand_lds[wave], walk, n_full, atol, rtol, \
+                                                      lane, second_round, n_real, rd, wp, exact_acc[wave])
         // A segment that is a single group with stand-ins (so gpw == 1) skips them.  Beside
         // full groups the workgroup ends with its full groups anyway, and the stand-ins
         // are loaded (cache hits) and evaluated like candidates.
@@ -1125,8 +1176,8 @@ __device__ __forceinline__ void run_job(const SegDesc &sd, const uint64_t *ptr_t
         if (NC_ >= 4 && skip) { EVO_TILES_PADDED(fast_tiles_wide, NC_); }                      \
         else { EVO_TILES(fast_tiles_wide, NC_); }                                              \
     } else {                                                                                   \
-        if (NC_ >= 4 && skip) { EVO_TILES_PADDED(fast_tiles, NC_); }                           \
-        else { EVO_TILES(fast_tiles, NC_); }                                                   \
+        if (NC_ >= 4 && skip) { EVO_TILES_PADDED_LDS(fast_tiles, NC_); }                       \
+        else { EVO_TILES_LDS(fast_tiles, NC_); }                                               \
     }
         switch (nc) {
 #if EVO_KG > 8
@@ -1140,6 +1191,8 @@ __device__ __forceinline__ void run_job(const SegDesc &sd, const uint64_t *ptr_t
 #undef EVO_FAST
 #undef EVO_TILES
 #undef EVO_TILES_PADDED
+#undef EVO_TILES_LDS
+#undef EVO_TILES_PADDED_LDS
     }
 
     // Exact path over whatever is left: tiles the fast path flagged, the ragged last
@@ -1293,9 +1346,11 @@ __device__ __forceinline__ void fold_bundle(const SegDesc &sd, uint32_t gblock, 
     __syncthreads();
 }
 
-// Level 2.  Thread layout: R consecutive threads share a candidate and take R consecutive
-// ranges of the candidate's `units` second-level rows; their R results are then added in
-// range order.
+// Level 2.  Thread layout: the candidates of a pass are consecutive threads (their rows of one
+// unit are neighbours in memory, so a wavefront's load touches a contiguous run of rows
+// instead of 64 different cache lines: the level took 7 us before, with a candidate's R
+// ranges side by side), and thread group k of the R groups takes the k-th range of the
+// candidate's `units` second-level rows; the R results are then added in range order.
 // A segment that stands alone writes its evo_stats rows; one that is a case of a case
 // group leaves one row per candidate in case_rows for write_case_group.
 __device__ __forceinline__ void write_stats(evo_stats *dst, const Partial &a, uint64_t n_elems) {
@@ -1323,8 +1378,8 @@ __device__ __forceinline__ void finalize_segment(const SegDesc &sd, const Partia
     while (pc < sd.P && pc < (uint32_t)kThreads) pc <<= 1;   // candidates per pass (power of 2)
     const uint32_t R = kThreads / pc;                          // chunk ranges per candidate
     const uint32_t per = (units + R - 1) / R;
-    const uint32_t ci = threadIdx.x / R;
-    const uint32_t ri = threadIdx.x % R;
+    const uint32_t ci = threadIdx.x % pc;
+    const uint32_t ri = threadIdx.x / pc;
 
     for (uint32_t p0 = 0; p0 < sd.P; p0 += pc) {
         const uint32_t p = p0 + ci;
@@ -1355,7 +1410,7 @@ __device__ __forceinline__ void finalize_segment(const SegDesc &sd, const Partia
         fold[threadIdx.x] = a;
         __syncthreads();
         if (ri == 0 && p < sd.P - sd.n_pad) {
-            for (uint32_t k = 1; k < R; ++k) add_partial(a, fold[threadIdx.x + k]);
+            for (uint32_t k = 1; k < R; ++k) add_partial(a, fold[threadIdx.x + k * pc]);
             if (sd.n_cases <= 1) {
                 write_stats(&stats[sd.stats_row0 + p], a, sd.n);
             } else {
@@ -1392,7 +1447,7 @@ __device__ __forceinline__ void write_case_group(const SegDesc *descs, const Seg
 // workgroup that has just written evo_stats rows.
 template <uint32_t DTS>
 __device__ __forceinline__ bool check_body(const SegDesc *descs, const uint64_t *ptr_table,
-                                           uint32_t S, float atol, float rtol, uint32_t n_first,
+                                           uint32_t S, uint32_t n_first,
                                            uint32_t job, uint32_t total_jobs,
                                            Partial *partials, uint32_t *tickets, evo_stats *stats) {
     // Which segment does this workgroup belong to?  (job0 is ascending.)
@@ -1404,6 +1459,7 @@ __device__ __forceinline__ bool check_body(const SegDesc *descs, const uint64_t 
     const uint32_t s = lo;
     const SegDesc sd = descs[s];
     const uint32_t job_local = job - sd.job0;
+    const float atol = sd.atol, rtol = sd.rtol;   // the segment's tolerance (set by the host's policy)
 
     // Workgroups are placed one per compute unit first; those numbered n_first (the number
     // of compute units) and above then share a compute unit, SIMD by SIMD, with one of the
@@ -1417,36 +1473,37 @@ __device__ __forceinline__ bool check_body(const SegDesc *descs, const uint64_t 
     __shared__ ExactAcc exact_acc[kWaves][kG];
     __shared__ Partial wave_part[kWaves][kG];
     __shared__ uint16_t redo[kWaves][kMaxTilesPerWave];
+    __shared__ uint64_t cand_lds[kWaves][kG];
     constexpr bool kSkip = (DTS & (DTS - 1u)) == 0;   // one element type: see run_job
     if constexpr ((DTS & (1u << EVO_BF16)) != 0) {
         if (sd.dtype == EVO_BF16 || DTS == (1u << EVO_BF16))
             run_job<EVO_BF16, kSkip>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
-                             wave_part, redo);
+                             wave_part, redo, cand_lds);
     }
     if constexpr ((DTS & (1u << EVO_F16)) != 0) {
         if (sd.dtype == EVO_F16 || DTS == (1u << EVO_F16))
             run_job<EVO_F16, kSkip>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
-                             wave_part, redo);
+                             wave_part, redo, cand_lds);
     }
     if constexpr ((DTS & (1u << EVO_F32)) != 0) {
         if (sd.dtype == EVO_F32 || DTS == (1u << EVO_F32))
             run_job<EVO_F32, kSkip>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
-                             wave_part, redo);
+                             wave_part, redo, cand_lds);
     }
     if constexpr ((DTS & (1u << EVO_F64)) != 0) {
         if (sd.dtype == EVO_F64 || DTS == (1u << EVO_F64))
             run_job<EVO_F64, kSkip>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
-                             wave_part, redo);
+                             wave_part, redo, cand_lds);
     }
     if constexpr ((DTS & (1u << EVO_I32)) != 0) {
         if (sd.dtype == EVO_I32 || DTS == (1u << EVO_I32))
             run_job<EVO_I32, kSkip>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
-                             wave_part, redo);
+                             wave_part, redo, cand_lds);
     }
     if constexpr ((DTS & (1u << EVO_I64)) != 0) {
         if (sd.dtype == EVO_I64 || DTS == (1u << EVO_I64))
             run_job<EVO_I64, kSkip>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
-                             wave_part, redo);
+                             wave_part, redo, cand_lds);
     }
 
     // Two tickets: the bundle of kFold chunks this job belongs to, then the segment (see
@@ -1526,10 +1583,10 @@ __device__ __forceinline__ bool check_body(const SegDesc *descs, const uint64_t 
 template <uint32_t DTS>
 __global__ void __launch_bounds__(kThreads, EVO_WAVES_PER_EU)
 evo_check_kernel(const SegDesc *__restrict__ descs, const uint64_t *__restrict__ ptr_table,
-                 uint32_t S, float atol, float rtol, uint32_t n_first,
+                 uint32_t S, uint32_t n_first,
                  Partial *__restrict__ partials, uint32_t *__restrict__ tickets,
                  evo_stats *__restrict__ stats) {
-    (void)check_body<DTS>(descs, ptr_table, S, atol, rtol, n_first, blockIdx.x, gridDim.x, partials, tickets,
+    (void)check_body<DTS>(descs, ptr_table, S, n_first, blockIdx.x, gridDim.x, partials, tickets,
                           stats);
 }
 
@@ -1539,11 +1596,11 @@ evo_check_kernel(const SegDesc *__restrict__ descs, const uint64_t *__restrict__
 // into per-lane scratch memory.
 template <uint32_t DTS>
 __global__ void __launch_bounds__(kThreads, EVO_WAVES_PER_EU)
-evo_check_kernel_inline(const InlineTable /*read via the segment pointer*/, uint32_t S, float atol,
-                        float rtol, uint32_t n_first, Partial *__restrict__ partials,
+evo_check_kernel_inline(const InlineTable /*read via the segment pointer*/, uint32_t S,
+                        uint32_t n_first, Partial *__restrict__ partials,
                         uint32_t *__restrict__ tickets, evo_stats *__restrict__ stats) {
     const InlineTable *tab = (const InlineTable *)__builtin_amdgcn_kernarg_segment_ptr();
-    (void)check_body<DTS>(tab->descs, tab->ptrs, S, atol, rtol, n_first, blockIdx.x, gridDim.x, partials,
+    (void)check_body<DTS>(tab->descs, tab->ptrs, S, n_first, blockIdx.x, gridDim.x, partials,
                           tickets, stats);
 }
 
@@ -1569,8 +1626,8 @@ struct FitArgs {
 
 template <uint32_t DTS>
 __global__ void __launch_bounds__(kThreads, EVO_WAVES_PER_EU)
-evo_evaluate_kernel(const InlineTable /*read via the segment pointer*/, uint32_t S, float atol,
-                    float rtol, uint32_t n_first, Partial *__restrict__ partials,
+evo_evaluate_kernel(const InlineTable /*read via the segment pointer*/, uint32_t S,
+                    uint32_t n_first, Partial *__restrict__ partials,
                     uint32_t *__restrict__ tickets, evo_stats *__restrict__ stats, const FitArgs fit) {
     const InlineTable *tab = (const InlineTable *)__builtin_amdgcn_kernarg_segment_ptr();
     const uint32_t n_rows = fit.P + 1;
@@ -1581,7 +1638,7 @@ evo_evaluate_kernel(const InlineTable /*read via the segment pointer*/, uint32_t
         last = fitness_row_and_ticket(fit.timings, fit.baseline, blockIdx.x - n_jobs, fit.P, fit.T, stats,
                                       fit.rows, fit.base, fit.ticket, n_rows + fit.writers - 1u);
     } else {
-        if (!check_body<DTS>(tab->descs, tab->ptrs, S, atol, rtol, n_first, blockIdx.x, n_jobs, partials,
+        if (!check_body<DTS>(tab->descs, tab->ptrs, S, n_first, blockIdx.x, n_jobs, partials,
                              tickets, stats))
             return;
         __shared__ uint32_t drew_last;
@@ -1605,31 +1662,31 @@ evo_evaluate_kernel(const InlineTable /*read via the segment pointer*/, uint32_t
 // evo_internal.h; one translation unit per set, see evo_check_inst.hip).
 template <uint32_t DTS>
 hipError_t launch_check_for(const SegDesc *d_descs, const uint64_t *d_ptrs, uint32_t S,
-                            uint32_t total_jobs, float atol, float rtol, uint32_t n_first,
+                            uint32_t total_jobs, uint32_t n_first,
                             Partial *partials, uint32_t *tickets, evo_stats *stats,
                             hipStream_t stream) {
     hipLaunchKernelGGL(evo_check_kernel<DTS>, dim3(total_jobs), dim3(kThreads), 0, stream, d_descs,
-                       d_ptrs, S, atol, rtol, n_first, partials, tickets, stats);
+                       d_ptrs, S, n_first, partials, tickets, stats);
     return hipGetLastError();
 }
 
 template <uint32_t DTS>
 hipError_t launch_check_inline_for(const InlineTable &tab, uint32_t S, uint32_t total_jobs,
-                                   float atol, float rtol, uint32_t n_first, Partial *partials,
+                                   uint32_t n_first, Partial *partials,
                                    uint32_t *tickets, evo_stats *stats, hipStream_t stream) {
     hipLaunchKernelGGL(evo_check_kernel_inline<DTS>, dim3(total_jobs), dim3(kThreads), 0, stream,
-                       tab, S, atol, rtol, n_first, partials, tickets, stats);
+                       tab, S, n_first, partials, tickets, stats);
     return hipGetLastError();
 }
 
 template <uint32_t DTS>
-hipError_t launch_evaluate_for(const InlineTable &tab, uint32_t S, uint32_t total_jobs, float atol,
-                               float rtol, uint32_t n_first, Partial *partials, uint32_t *tickets,
+hipError_t launch_evaluate_for(const InlineTable &tab, uint32_t S, uint32_t total_jobs,
+                               uint32_t n_first, Partial *partials, uint32_t *tickets,
                                evo_stats *stats, const FitLaunch &f, hipStream_t stream) {
     const FitArgs fit{f.timings, f.baseline, f.summary, f.base, f.rows, f.ticket, f.P, f.T, f.reducer,
                       f.writers};
     hipLaunchKernelGGL(evo_evaluate_kernel<DTS>, dim3(total_jobs + f.P + 1), dim3(kThreads), 0, stream,
-                       tab, S, atol, rtol, n_first, partials, tickets, stats, fit);
+                       tab, S, n_first, partials, tickets, stats, fit);
     return hipGetLastError();
 }
 

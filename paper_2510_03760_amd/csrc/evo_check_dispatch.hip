@@ -4,10 +4,10 @@
 namespace evo {
 
 hipError_t launch_check(uint32_t dtype_set, const SegDesc *d_descs, const uint64_t *d_ptrs,
-                        uint32_t S, uint32_t total_jobs, float atol, float rtol, uint32_t n_first,
+                        uint32_t S, uint32_t total_jobs, uint32_t n_first,
                         Partial *partials, uint32_t *tickets, evo_stats *stats, hipStream_t stream) {
 #define EVO_LAUNCH(DTS_)                                                                          \
-    return launch_check_for<DTS_>(d_descs, d_ptrs, S, total_jobs, atol, rtol, n_first, partials,  \
+    return launch_check_for<DTS_>(d_descs, d_ptrs, S, total_jobs, n_first, partials,  \
                                   tickets, stats, stream)
     switch (dtype_set) {
         case 1u << EVO_F32: EVO_LAUNCH(1u << EVO_F32);
@@ -22,11 +22,11 @@ hipError_t launch_check(uint32_t dtype_set, const SegDesc *d_descs, const uint64
 }
 
 hipError_t launch_check_inline(uint32_t dtype_set, const InlineTable &tab, uint32_t S,
-                               uint32_t total_jobs, float atol, float rtol, uint32_t n_first,
+                               uint32_t total_jobs, uint32_t n_first,
                                Partial *partials, uint32_t *tickets, evo_stats *stats,
                                hipStream_t stream) {
 #define EVO_LAUNCH(DTS_)                                                                          \
-    return launch_check_inline_for<DTS_>(tab, S, total_jobs, atol, rtol, n_first, partials,       \
+    return launch_check_inline_for<DTS_>(tab, S, total_jobs, n_first, partials,       \
                                          tickets, stats, stream)
     switch (dtype_set) {
         case 1u << EVO_F32: EVO_LAUNCH(1u << EVO_F32);
@@ -41,11 +41,11 @@ hipError_t launch_check_inline(uint32_t dtype_set, const InlineTable &tab, uint3
 }
 
 hipError_t launch_evaluate(uint32_t dtype_set, const InlineTable &tab, uint32_t S, uint32_t total_jobs,
-                           float atol, float rtol, uint32_t n_first, Partial *partials,
+                           uint32_t n_first, Partial *partials,
                            uint32_t *tickets, evo_stats *stats, const FitLaunch &fit,
                            hipStream_t stream) {
 #define EVO_LAUNCH(DTS_)                                                                          \
-    return launch_evaluate_for<DTS_>(tab, S, total_jobs, atol, rtol, n_first, partials, tickets,  \
+    return launch_evaluate_for<DTS_>(tab, S, total_jobs, n_first, partials, tickets,  \
                                      stats, fit, stream)
     switch (dtype_set) {
         case 1u << EVO_F32: EVO_LAUNCH(1u << EVO_F32);

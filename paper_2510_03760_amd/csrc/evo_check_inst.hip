@@ -12,13 +12,13 @@
 namespace evo {
 
 template hipError_t launch_check_for<EVO_INST_DTS>(const SegDesc *, const uint64_t *, uint32_t, uint32_t,
-                                                   float, float, uint32_t, Partial *, uint32_t *,
+                                                   uint32_t, Partial *, uint32_t *,
                                                    evo_stats *, hipStream_t);
-template hipError_t launch_check_inline_for<EVO_INST_DTS>(const InlineTable &, uint32_t, uint32_t, float,
-                                                          float, uint32_t, Partial *, uint32_t *,
+template hipError_t launch_check_inline_for<EVO_INST_DTS>(const InlineTable &, uint32_t, uint32_t,
+                                                          uint32_t, Partial *, uint32_t *,
                                                           evo_stats *, hipStream_t);
 
-template hipError_t launch_evaluate_for<EVO_INST_DTS>(const InlineTable &, uint32_t, uint32_t, float, float,
+template hipError_t launch_evaluate_for<EVO_INST_DTS>(const InlineTable &, uint32_t, uint32_t,
                                                       uint32_t, Partial *, uint32_t *, evo_stats *,
                                                       const FitLaunch &, hipStream_t);
 

@@ -120,20 +120,21 @@ __host__ __device__ inline void locate(uint32_t P, uint32_t p, uint32_t *group, 
 // One ragged group as the kernel sees it (device memory, 64 bytes).
 struct SegDesc {
     const void *ref;
-    uint64_t ptr0;              // index of the segment's first candidate pointer in the table
     uint64_t n;                 // elements per tensor
+    uint32_t ptr0;              // index of the segment's first candidate pointer in the table
     uint32_t P;                 // candidates the kernel walks: the caller's plus n_pad
-    uint32_t dtype;
     uint32_t stats_row0;
     uint32_t job0;              // first workgroup index of this segment
     uint32_t n_jobs;            // n_gblocks * n_chunks
     uint32_t n_chunks;          // workgroups that share the tiles of one group block
     uint32_t case0;             // first segment of the case group this segment belongs to
     uint32_t n_groups;          // candidate groups
-    uint16_t gpw;               // groups per workgroup: 1, 2 or 4
-    uint16_t n_pad;             // trailing candidates that are stand-ins (their pointer is the
-                                // reference's); they get no evo_stats row
     uint32_t n_cases;           // segments in that case group (1: the segment stands alone)
+    float atol, rtol;           // the tolerance this segment is checked with
+    uint16_t dtype;
+    uint8_t gpw;                // groups per workgroup: 1, 2 or 4
+    uint8_t n_pad;              // trailing candidates that are stand-ins (their pointer is the
+                                // reference's); they get no evo_stats row
 };
 static_assert(sizeof(SegDesc) == 64, "SegDesc layout");
 
@@ -168,11 +169,11 @@ static_assert(sizeof(InlineTable) <= 3600, "kernel argument block must stay belo
 // n_first: compute units of the device (workgroups numbered below it get a compute unit
 // of their own when the launch starts).
 hipError_t launch_check(uint32_t dtype_set, const SegDesc *d_descs, const uint64_t *d_ptrs,
-                        uint32_t S, uint32_t total_jobs, float atol, float rtol, uint32_t n_first,
+                        uint32_t S, uint32_t total_jobs, uint32_t n_first,
                         Partial *partials, uint32_t *tickets, evo_stats *stats, hipStream_t stream);
 
 hipError_t launch_check_inline(uint32_t dtype_set, const InlineTable &tab, uint32_t S,
-                               uint32_t total_jobs, float atol, float rtol, uint32_t n_first,
+                               uint32_t total_jobs, uint32_t n_first,
                                Partial *partials, uint32_t *tickets, evo_stats *stats,
                                hipStream_t stream);
 
@@ -189,7 +190,7 @@ struct FitLaunch {
     uint32_t writers;     // workgroups that write evo_stats rows (one per segment or case group)
 };
 hipError_t launch_evaluate(uint32_t dtype_set, const InlineTable &tab, uint32_t S, uint32_t total_jobs,
-                           float atol, float rtol, uint32_t n_first, Partial *partials,
+                           uint32_t n_first, Partial *partials,
                            uint32_t *tickets, evo_stats *stats, const FitLaunch &fit,
                            hipStream_t stream);
 
@@ -199,16 +200,16 @@ constexpr uint32_t kAllTypes = (1u << EVO_F32) | (1u << EVO_BF16) | (1u << EVO_F
                                (1u << EVO_F64) | (1u << EVO_I32) | (1u << EVO_I64);
 template <uint32_t DTS>
 hipError_t launch_check_for(const SegDesc *d_descs, const uint64_t *d_ptrs, uint32_t S,
-                            uint32_t total_jobs, float atol, float rtol, uint32_t n_first,
+                            uint32_t total_jobs, uint32_t n_first,
                             Partial *partials, uint32_t *tickets, evo_stats *stats,
                             hipStream_t stream);
 template <uint32_t DTS>
 hipError_t launch_check_inline_for(const InlineTable &tab, uint32_t S, uint32_t total_jobs,
-                                   float atol, float rtol, uint32_t n_first, Partial *partials,
+                                   uint32_t n_first, Partial *partials,
                                    uint32_t *tickets, evo_stats *stats, hipStream_t stream);
 template <uint32_t DTS>
-hipError_t launch_evaluate_for(const InlineTable &tab, uint32_t S, uint32_t total_jobs, float atol,
-                               float rtol, uint32_t n_first, Partial *partials, uint32_t *tickets,
+hipError_t launch_evaluate_for(const InlineTable &tab, uint32_t S, uint32_t total_jobs,
+                               uint32_t n_first, Partial *partials, uint32_t *tickets,
                                evo_stats *stats, const FitLaunch &fit, hipStream_t stream);
 
 // base_median: two floats of device scratch (the baseline's median and mean).
