@@ -27,11 +27,24 @@
  *     IEEE-754 binary32 and EVO_F16 elements are IEEE-754 binary16, both little
  *     endian; they are widened exactly and every operation is done in binary32.
  *     The other element types are listed with evo_dtype and evo_stats.
- *   - Every call that takes a stream only enqueues work on it and returns; results
- *     are defined once the caller has synchronised that stream.  `stream` is a
- *     hipStream_t passed as void* (NULL = the null stream).
+ *   - Every call that takes a stream enqueues its work on it and returns (the one
+ *     exception is evo_time_candidates); results are defined once the caller has
+ *     synchronised that stream.  `stream` is a hipStream_t passed as void* (NULL = the
+ *     null stream).
+ *   - A context owns scratch memory (partial results, counters, tables) that grows on
+ *     demand: a call that needs more than the context holds frees and allocates device
+ *     memory (which waits for the device), clears new counters and waits for that.  A
+ *     call that repeats a shape the context has already run only enqueues kernels.
+ *   - Graph capture.  A call may be recorded into a HIP graph when (a) the context has
+ *     run the same call with the same shapes eagerly before, so that its scratch memory
+ *     exists, and (b) its descriptors and candidate pointers travel inside the kernel
+ *     arguments: at most 8 groups and 384 candidate pointers per call (after rounding
+ *     the candidates beyond the last full group of 16 up to a power of two).  While the
+ *     stream is capturing, a call that would have to allocate, free, clear or copy from
+ *     staging memory returns EVO_ERR_CAPTURE and enqueues nothing.  evo_time_candidates
+ *     cannot be captured.
  *   - A context must not be used from two streams or two host threads at once:
- *     it owns scratch memory that consecutive calls reuse in stream order.
+ *     consecutive calls reuse its scratch memory in stream order.
  *   - All functions return EVO_OK (0) or a negative evo_status.  Argument errors
  *     are detected on the host before anything is enqueued.  Nothing is printed,
  *     thrown or aborted.
@@ -68,13 +81,16 @@ typedef enum {
     EVO_ERR_NULL   = -1, /* a required pointer is NULL                          */
     EVO_ERR_DTYPE  = -2, /* unknown element type                                */
     EVO_ERR_SIZE   = -3, /* zero or out-of-range count (n, P, S, T, rows)       */
-    EVO_ERR_TOL    = -4, /* tolerance negative, NaN or infinite                 */
+    EVO_ERR_TOL    = -4, /* tolerance negative, NaN or infinite; tolerance class */
+                         /* out of range or never set                           */
     EVO_ERR_ALIGN  = -5, /* a tensor pointer is not aligned to its element size, or */
                          /* an output pointer not to its record (stats: 8 bytes) */
     EVO_ERR_DEVICE = -6, /* a HIP call failed (no device, launch error, ...)    */
     EVO_ERR_NOMEM  = -7, /* host or device allocation failed                    */
     EVO_ERR_HANDLE = -8, /* not a live context (never created, or destroyed)    */
-    EVO_ERR_LIMIT  = -9  /* beyond the fixed capacity of evo_check_batch_static */
+    EVO_ERR_LIMIT  = -9, /* beyond the fixed capacity of evo_check_batch_static */
+    EVO_ERR_CAPTURE = -10 /* the stream is capturing and the call would have to allocate, */
+                         /* free, clear or stage (see "Graph capture" above)             */
 } evo_status;
 
 /* Bits of evo_stats.flags */
@@ -132,7 +148,8 @@ typedef struct evo_segment {
     uint32_t           P_s;        /* > 0                                            */
     uint32_t           dtype;      /* evo_dtype                                      */
     uint32_t           stats_row0; /* first of the P_s rows this group writes        */
-    uint32_t           reserved;   /* set to 0                                       */
+    uint32_t           tol_class;  /* 0: the context's tolerance for `dtype`; 1 ..   */
+                                   /* EVO_TOL_CLASSES: that tolerance class          */
 } evo_segment;
 
 /* Population figures of Sec. 5.1, one per evo_fitness call, in device memory. */
@@ -156,6 +173,24 @@ EVO_API int evo_check_create(evo_check_t **out, evo_dtype dtype, uint64_t n_elem
                      float atol, float rtol);
 
 /*
+ * Tolerance policy.  The functional test of Sec. 4.3 compares outputs of operations of
+ * very different kinds and precisions (the kernel classification table of the appendix:
+ * matrix products, reductions, losses, ...; half-precision and single-precision outputs),
+ * and one absolute/relative pair does not fit them all.  A context therefore holds one
+ * pair per element type -- all equal to the pair given to evo_check_create until changed
+ * here -- and up to EVO_TOL_CLASSES caller-defined classes.  Every group of a call is
+ * checked with the pair of its element type, unless its descriptor names a class
+ * (evo_segment.tol_class; e.g. "loss outputs", "softmax rows").  The paper states no
+ * tolerance values; none is built in.  Integer element types ignore tolerances.
+ * Both calls are host-only and take effect for the calls made after them.
+ * Errors: EVO_ERR_HANDLE, EVO_ERR_DTYPE (set_tolerance), EVO_ERR_SIZE (class 0 or beyond
+ * EVO_TOL_CLASSES), EVO_ERR_TOL.
+ */
+#define EVO_TOL_CLASSES 15u
+EVO_API int evo_check_set_tolerance(evo_check_t *c, evo_dtype dtype, float atol, float rtol);
+EVO_API int evo_check_set_tolerance_class(evo_check_t *c, uint32_t tol_class, float atol, float rtol);
+
+/*
  * Functional testing of Sec. 4.3 for a population: checks P candidate tensors
  * against `ref` (each of the context's n_elems elements and dtype) and overwrites
  * stats[0..P) completely (timing fields are set to 0).
@@ -167,7 +202,8 @@ EVO_API int evo_check_create(evo_check_t **out, evo_dtype dtype, uint64_t n_elem
  * alignment gives the fast path.  `stats` must be 8-byte aligned (here and in
  * every other call that writes evo_stats rows).
  * Errors: EVO_ERR_HANDLE, EVO_ERR_NULL (ref, cand_ptrs, any cand_ptrs[i], stats),
- * EVO_ERR_SIZE (P == 0 or P > 65535), EVO_ERR_ALIGN, EVO_ERR_NOMEM, EVO_ERR_DEVICE.
+ * EVO_ERR_SIZE (P == 0 or P > 65535), EVO_ERR_ALIGN, EVO_ERR_NOMEM, EVO_ERR_DEVICE,
+ * EVO_ERR_CAPTURE.
  */
 EVO_API int evo_check_batch(evo_check_t *c, const void *ref, const void *const *cand_ptrs,
                     uint32_t P, void *stream, evo_stats *stats);
@@ -199,13 +235,15 @@ EVO_API int evo_check_batch_static(evo_check_t *c, const void *ref, const void *
  * The same check over S ragged groups in ONE launch (the test cases and output
  * shapes of an operation set differ in size, Sec. 4.3 / operation taxonomy in the
  * appendix).  Group s writes rows [stats_row0, stats_row0 + P_s); row ranges of
- * different groups must not overlap and must lie inside [0, n_rows).  The
- * context's tolerances apply; its n_elems and dtype are ignored.
+ * different groups must not overlap and must lie inside [0, n_rows).  Each group is
+ * checked with the tolerance of its element type or of its tolerance class (see
+ * evo_check_set_tolerance); the context's n_elems and dtype are ignored.
  *   segs   HOST array of S descriptors (and the host pointer arrays they name),
  *          read during the call only
  *   stats  device, n_rows rows; rows not named by any group are left untouched
  * Errors: as evo_check_batch, plus EVO_ERR_SIZE for S == 0, an empty group, a row
- * range outside n_rows or overlapping another, and EVO_ERR_DTYPE per group.
+ * range outside n_rows or overlapping another, EVO_ERR_DTYPE per group, EVO_ERR_TOL for
+ * a tolerance class that is out of range or was never set, EVO_ERR_CAPTURE.
  */
 EVO_API int evo_check_segmented(evo_check_t *c, const evo_segment *segs, uint32_t S,
                         void *stream, evo_stats *stats, uint32_t n_rows);
@@ -270,9 +308,9 @@ EVO_API int evo_fitness_ex(evo_check_t *c, const float *timings, const float *ba
  * candidate pointers fit the kernel argument block (K <= 8, K*P' <= 384, P' being P rounded up
  * to whole groups of 16 plus one power of two; for K = 1 a population such as 17 or 33 counts
  * as two descriptors) it is ONE launch: the
- * timing rows are reduced by the first workgroups of the grid while the tensors stream, and
- * the last of them or of the check to finish computes speedup, fitness and the population
- * figures.  Larger tables run as two launches.
+ * timing rows are reduced by the last workgroups of the grid, which start when the first
+ * check jobs end, and the last of them or of the check to finish computes speedup, fitness
+ * and the population figures.  Larger tables run as two launches.
  * Arguments and errors: as evo_check_cases and evo_fitness_ex; P is cases[0].P_s.
  */
 EVO_API int evo_evaluate(evo_check_t *c, const evo_segment *cases, uint32_t K,
@@ -342,7 +380,8 @@ EVO_API int evo_select_elite_diverse(evo_check_t *c, const evo_stats *stats, con
  * scratch buffer on first use.
  * Errors: EVO_ERR_HANDLE, EVO_ERR_NULL (launch, any launch[p], timings, opts),
  * EVO_ERR_SIZE (P == 0, T == 0, T > EVO_FITNESS_MAX_T, P > 65535, warmup > 1000000),
- * EVO_ERR_ALIGN (timings, clock_ratio), EVO_ERR_NOMEM, EVO_ERR_DEVICE.
+ * EVO_ERR_ALIGN (timings, clock_ratio), EVO_ERR_NOMEM, EVO_ERR_DEVICE, EVO_ERR_CAPTURE
+ * (the stream is capturing).
  */
 typedef void (*evo_launch_fn)(void *user, void *stream);
 typedef struct evo_timing_opts {

@@ -138,14 +138,19 @@ class CheckAccumulator:
         self._acc = _Acc()
         self._lib.oracle_check_init(ctypes.byref(self._acc))
 
-    def feed(self, ref_chunk, cand_chunk) -> None:
-        r = _as_elems(ref_chunk, self.dtype)
-        c = _as_elems(cand_chunk, self.dtype)
+    def feed(self, ref_chunk, cand_chunk, dtype: int = None, atol: float = None,
+             rtol: float = None) -> None:
+        """The next chunk; a chunk that is another test case of the same candidate may have
+        its own element type and tolerance."""
+        dt = self.dtype if dtype is None else dtype
+        a = self.atol if atol is None else float(np.float32(atol))
+        t = self.rtol if rtol is None else float(np.float32(rtol))
+        r = _as_elems(ref_chunk, dt)
+        c = _as_elems(cand_chunk, dt)
         if r.size != c.size:
             raise ValueError("chunk sizes differ")
         self._lib.oracle_check_chunk(
-            ctypes.byref(self._acc), r.ctypes.data, c.ctypes.data, r.size,
-            self.dtype, self.atol, self.rtol)
+            ctypes.byref(self._acc), r.ctypes.data, c.ctypes.data, r.size, dt, a, t)
 
     def result(self) -> dict:
         a = self._acc
@@ -179,6 +184,64 @@ def check_batch(ref, cands, dtype: int, atol: float, rtol: float, threads: int =
         return [check_one(ref, c, dtype, atol, rtol, lib_path) for c in cands]
     with ThreadPoolExecutor(max_workers=threads) as ex:
         return list(ex.map(lambda c: check_one(ref, c, dtype, atol, rtol, lib_path), cands))
+
+
+class TolerancePolicy:
+    """Which absolute/relative pair a group of tensors is checked with (functional testing
+    of Sec. 4.3 over outputs of different kinds and precisions, cf. the kernel
+    classification table of the appendix; the paper gives no values): one pair per element
+    type, all equal to the pair given here until set_dtype changes one, and caller-defined
+    classes 1..15; a group that names a class takes the class's pair, any other group the
+    pair of its element type."""
+
+    N_CLASSES = 15
+
+    def __init__(self, atol: float, rtol: float):
+        self.by_dtype = {d: (atol, rtol) for d in (F32, BF16, F16, F64, I32, I64)}
+        self.by_class = {}
+
+    def set_dtype(self, dtype: int, atol: float, rtol: float) -> None:
+        if dtype not in self.by_dtype:
+            raise ValueError("unknown element type")
+        self.by_dtype[dtype] = (atol, rtol)
+
+    def set_class(self, tol_class: int, atol: float, rtol: float) -> None:
+        if not 1 <= tol_class <= self.N_CLASSES:
+            raise ValueError("tolerance classes are 1..%d" % self.N_CLASSES)
+        self.by_class[tol_class] = (atol, rtol)
+
+    def lookup(self, dtype: int, tol_class: int = 0):
+        if tol_class == 0:
+            return self.by_dtype[dtype]
+        return self.by_class[tol_class]   # KeyError: the class was never set
+
+
+def check_segments(segments, policy: TolerancePolicy, threads: int = 1, lib_path: str = None) -> list:
+    """Rows of a ragged launch: ``segments`` is a list of (ref, cands, dtype, tol_class);
+    every group is checked on its own with the pair the policy gives it.  Returns the rows
+    of all groups, in group order."""
+    rows = []
+    for ref, cands, dtype, tol_class in segments:
+        atol, rtol = policy.lookup(dtype, tol_class)
+        rows += check_batch(ref, cands, dtype, atol, rtol, threads, lib_path)
+    return rows
+
+
+def check_cases(cases, policy: TolerancePolicy, lib_path: str = None) -> list:
+    """One row per candidate over K test cases: ``cases`` is a list of (ref, cands, dtype,
+    tol_class) with the same number of candidates each; candidate p's accumulator is fed
+    case after case, each case with its own element type and the pair the policy gives it."""
+    P = len(cases[0][1])
+    accs = None
+    for ref, cands, dtype, tol_class in cases:
+        if len(cands) != P:
+            raise ValueError("every case has the same candidates")
+        atol, rtol = policy.lookup(dtype, tol_class)
+        if accs is None:
+            accs = [CheckAccumulator(dtype, atol, rtol, lib_path) for _ in range(P)]
+        for acc, cand in zip(accs, cands):
+            acc.feed(ref, cand, dtype, atol, rtol)
+    return [a.result() for a in accs]
 
 
 def fitness(timings, baseline, valid, lib_path: str = None, reducer: int = REDUCE_MEDIAN) -> dict:
@@ -261,6 +324,14 @@ class Variant:
 
     def check_batch(self, ref, cands, dtype, atol, rtol, threads=1):
         return check_batch(ref, cands, dtype, atol, rtol, threads, self.lib_path)
+
+    TolerancePolicy = TolerancePolicy
+
+    def check_segments(self, segments, policy, threads=1):
+        return check_segments(segments, policy, threads, self.lib_path)
+
+    def check_cases(self, cases, policy):
+        return check_cases(cases, policy, self.lib_path)
 
     def fitness(self, timings, baseline, valid, reducer=REDUCE_MEDIAN):
         return fitness(timings, baseline, valid, self.lib_path, reducer)

@@ -51,7 +51,7 @@ class EvoSegment(ctypes.Structure):
     _fields_ = [
         ("ref", ctypes.c_void_p), ("cand_ptrs", ctypes.POINTER(ctypes.c_void_p)),
         ("n_elems", ctypes.c_uint64), ("P_s", ctypes.c_uint32), ("dtype", ctypes.c_uint32),
-        ("stats_row0", ctypes.c_uint32), ("reserved", ctypes.c_uint32),
+        ("stats_row0", ctypes.c_uint32), ("tol_class", ctypes.c_uint32),
     ]
 
 
@@ -91,6 +91,8 @@ def _load() -> ctypes.CDLL:
     h = ctypes.CDLL(lib_path)
     vp, u32, u64, f32 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_float
     h.evo_check_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, u64, f32, f32]
+    h.evo_check_set_tolerance.argtypes = [vp, ctypes.c_int, f32, f32]
+    h.evo_check_set_tolerance_class.argtypes = [vp, u32, f32, f32]
     h.evo_check_batch.argtypes = [vp, vp, ctypes.POINTER(vp), u32, vp, vp]
     h.evo_check_batch_static.argtypes = [vp, vp, ctypes.POINTER(vp), u32, vp, vp]
     h.evo_check_segmented.argtypes = [vp, ctypes.POINTER(EvoSegment), u32, vp, vp, u32]
@@ -107,7 +109,7 @@ def _load() -> ctypes.CDLL:
     h.evo_check_destroy.argtypes = [vp]
     h.evo_strerror.argtypes = [ctypes.c_int]
     h.evo_strerror.restype = ctypes.c_char_p
-    for name in ("evo_check_create", "evo_check_batch", "evo_check_batch_static", "evo_check_segmented", "evo_check_cases",
+    for name in ("evo_check_create", "evo_check_set_tolerance", "evo_check_set_tolerance_class", "evo_check_batch", "evo_check_batch_static", "evo_check_segmented", "evo_check_cases",
                  "evo_fitness", "evo_fitness_ex", "evo_select_elite", "evo_time_candidates", "evo_evaluate", "evo_evaluate_segmented", "evo_select_elite_diverse",
                  "evo_check_destroy"):
         getattr(h, name).restype = ctypes.c_int
@@ -147,6 +149,18 @@ def evo_check_create(dtype: int, n_elems: int, atol: float, rtol: float) -> int:
     return out.value
 
 
+def evo_check_set_tolerance(ctx: int, dtype: int, atol: float, rtol: float) -> None:
+    rc = lib.evo_check_set_tolerance(ctx, int(dtype), float(atol), float(rtol))
+    if rc != 0:
+        raise EvoError(rc, "evo_check_set_tolerance")
+
+
+def evo_check_set_tolerance_class(ctx: int, tol_class: int, atol: float, rtol: float) -> None:
+    rc = lib.evo_check_set_tolerance_class(ctx, int(tol_class), float(atol), float(rtol))
+    if rc != 0:
+        raise EvoError(rc, "evo_check_set_tolerance_class")
+
+
 def evo_check_batch(ctx: int, ref, cand_ptrs: Sequence, P: int, stream, stats) -> None:
     arr = (ctypes.c_void_p * max(1, len(cand_ptrs)))(*[_ptr(c) for c in cand_ptrs])
     rc = lib.evo_check_batch(ctx, _ptr(ref), arr if cand_ptrs is not None else None, int(P),
@@ -164,7 +178,7 @@ def evo_check_batch_static(ctx: int, ref, cand_ptrs: Sequence, P: int, stream, s
 
 def _segment_array(segs: Sequence[dict]):
     """ctypes evo_segment array for dicts with keys ref, cand_ptrs, n_elems, dtype and
-    (optionally) stats_row0, P_s; also returns the objects that must stay alive."""
+    (optionally) stats_row0, P_s, tol_class; also returns the objects that must stay alive."""
     keep: List[object] = []
     c_segs = (EvoSegment * max(1, len(segs)))()
     for i, sg in enumerate(segs):
@@ -177,7 +191,7 @@ def _segment_array(segs: Sequence[dict]):
         c_segs[i].P_s = int(sg.get("P_s", len(ptrs)))
         c_segs[i].dtype = int(sg["dtype"])
         c_segs[i].stats_row0 = int(sg.get("stats_row0", 0))
-        c_segs[i].reserved = 0
+        c_segs[i].tol_class = int(sg.get("tol_class", 0))
     return c_segs, keep
 
 
@@ -296,6 +310,12 @@ class Checker:
             self.close()
         except Exception:
             pass
+
+    def set_tolerance(self, dtype: int, atol: float, rtol: float) -> None:
+        evo_check_set_tolerance(self.ctx, dtype, atol, rtol)
+
+    def set_tolerance_class(self, tol_class: int, atol: float, rtol: float) -> None:
+        evo_check_set_tolerance_class(self.ctx, tol_class, atol, rtol)
 
     @staticmethod
     def new_stats(rows: int, device="cuda") -> torch.Tensor:

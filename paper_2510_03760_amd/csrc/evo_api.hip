@@ -56,10 +56,19 @@ static_assert(kStaticMaxJobs == EVO_STATIC_MAX_JOBS && kStaticScratchBytes == EV
               "evo.h states the capacity");
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
+constexpr uint32_t kDtypes = 6;              // EVO_F32 .. EVO_I64
+constexpr uint32_t kTolClasses = EVO_TOL_CLASSES;
+
+struct Tolerance {
+    float atol = 0.0f, rtol = 0.0f;
+    bool set = false;
+};
+
 struct evo_check {
     evo_dtype dtype;
     uint64_t n_elems;
-    float atol, rtol;
+    Tolerance by_dtype[kDtypes];            // all start as the pair given to evo_check_create
+    Tolerance by_class[kTolClasses + 1];    // [1 .. kTolClasses], set by the caller
     int device = -1;             // device the scratch lives on (-1: none yet)
     uint32_t n_cus = 0;          // compute units of that device
     // device scratch
@@ -125,6 +134,17 @@ int dev(hipError_t e) { return e == hipSuccess ? EVO_OK : (e == hipErrorOutOfMem
         if (rc_ != EVO_OK) return rc_;      \
     } while (0)
 
+// True while `stream` records into a graph: nothing may be allocated, freed, cleared with a
+// memset or copied from staging memory then (a replay would not repeat it).
+bool capturing(hipStream_t stream) {
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &st) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return st != hipStreamCaptureStatusNone;
+}
+
 // Scratch is tied to the device that is current when it is first needed.
 int bind_device(evo_check *c) {
     int cur = -1;
@@ -133,8 +153,14 @@ int bind_device(evo_check *c) {
     return c->device == cur ? EVO_OK : EVO_ERR_DEVICE;
 }
 
-int ensure_table(evo_check *c, size_t bytes) {
+// Scratch grows on demand.  Growing frees and allocates device memory and clears new
+// counters, none of which may happen while `stream` records into a graph: then the call is
+// refused (EVO_ERR_CAPTURE) before anything has been touched.  New counters are cleared and
+// the clearing has completed before the call goes on, so that a later call on another stream
+// is ordered after it.
+int ensure_table(evo_check *c, size_t bytes, hipStream_t stream) {
     if (bytes <= c->table_bytes) return EVO_OK;
+    if (capturing(stream)) return EVO_ERR_CAPTURE;
     if (c->d_table) EVO_TRY(hipFree(c->d_table));   // hipFree waits for the device
     c->d_table = nullptr;
     c->table_bytes = 0;
@@ -144,8 +170,9 @@ int ensure_table(evo_check *c, size_t bytes) {
     return EVO_OK;
 }
 
-int ensure_partials(evo_check *c, size_t rows) {
+int ensure_partials(evo_check *c, size_t rows, hipStream_t stream) {
     if (rows <= c->partial_rows) return EVO_OK;
+    if (capturing(stream)) return EVO_ERR_CAPTURE;
     if (c->d_partials) EVO_TRY(hipFree(c->d_partials));
     c->d_partials = nullptr;
     c->partial_rows = 0;
@@ -156,6 +183,7 @@ int ensure_partials(evo_check *c, size_t rows) {
 
 int ensure_tickets(evo_check *c, size_t n, hipStream_t stream) {
     if (n <= c->n_tickets) return EVO_OK;
+    if (capturing(stream)) return EVO_ERR_CAPTURE;
     if (c->d_tickets) EVO_TRY(hipFree(c->d_tickets));
     c->d_tickets = nullptr;
     c->n_tickets = 0;
@@ -163,22 +191,26 @@ int ensure_tickets(evo_check *c, size_t n, hipStream_t stream) {
     EVO_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_tickets), cap * sizeof(uint32_t)));
     // counters start at zero and every launch leaves them at zero again
     EVO_TRY(hipMemsetAsync(c->d_tickets, 0, cap * sizeof(uint32_t), stream));
+    EVO_TRY(hipStreamSynchronize(stream));
     c->n_tickets = cap;
     return EVO_OK;
 }
 
 int ensure_fitness_scratch(evo_check *c, hipStream_t stream) {
     if (c->d_base_median) return EVO_OK;
+    if (capturing(stream)) return EVO_ERR_CAPTURE;
     void *p = nullptr;
     EVO_TRY(hipMalloc(&p, 256));
     EVO_TRY(hipMemsetAsync(p, 0, 256, stream));
+    EVO_TRY(hipStreamSynchronize(stream));
     c->d_base_median = static_cast<float *>(p);
     c->d_fit_ticket = reinterpret_cast<uint32_t *>(static_cast<char *>(p) + 128);
     return EVO_OK;
 }
 
-int ensure_fit_rows(evo_check *c, size_t P) {
+int ensure_fit_rows(evo_check *c, size_t P, hipStream_t stream) {
     if (P <= c->fit_rows_count) return EVO_OK;
+    if (capturing(stream)) return EVO_ERR_CAPTURE;
     if (c->d_fit_rows) EVO_TRY(hipFree(c->d_fit_rows));
     c->d_fit_rows = nullptr;
     c->fit_rows_count = 0;
@@ -215,7 +247,24 @@ struct HostSeg {
     uint64_t n;
     uint32_t P, dtype, row0;
     uint32_t case0 = 0, n_cases = 1;   // case group (evo_check_cases), else the segment alone
+    float atol = 0.0f, rtol = 0.0f;    // filled in by resolve_tolerance
 };
+
+bool tolerance_ok(float atol, float rtol) {
+    return atol >= 0.0f && rtol >= 0.0f && !std::isinf(atol) && !std::isinf(rtol);
+}
+
+// The tolerance a group is checked with: its class when it names one (1 .. kTolClasses, set
+// beforehand), else the context's pair for its element type.
+int resolve_tolerance(const evo_check *c, uint32_t tol_class, HostSeg &h) {
+    if (tol_class > kTolClasses) return EVO_ERR_TOL;
+    const Tolerance &t = tol_class ? c->by_class[tol_class] : c->by_dtype[h.dtype];
+    if (!t.set) return EVO_ERR_TOL;
+    h.atol = t.atol;
+    h.rtol = t.rtol;
+    return EVO_OK;
+}
+
 
 // Pure host validation of one group (no device call).
 int validate_seg(const HostSeg &h) {
@@ -318,11 +367,13 @@ void partition(const HostSeg *segs, size_t n_segs, uint32_t target_jobs, SegDesc
         SegDesc &d = descs[s];
         d.n = h.n;
         d.P = padded_population(h.P);
-        d.n_pad = (uint16_t)(d.P - h.P);
-        d.dtype = h.dtype;
+        d.n_pad = (uint8_t)(d.P - h.P);
+        d.dtype = (uint16_t)h.dtype;
+        d.atol = h.atol;
+        d.rtol = h.rtol;
         d.stats_row0 = h.row0;
         d.n_groups = evo::group_count(d.P);
-        d.gpw = (uint16_t)std::min<uint32_t>(pow2_ceil(d.n_groups), EVO_GPW_MAX);
+        d.gpw = (uint8_t)std::min<uint32_t>(pow2_ceil(d.n_groups), EVO_GPW_MAX);
         d.case0 = h.n_cases > 1 ? h.case0 : (uint32_t)s;
         d.n_cases = h.n_cases;
         const uint64_t tiles = (h.n + evo::tile_elems(h.dtype) - 1) / evo::tile_elems(h.dtype);
@@ -424,7 +475,7 @@ int run_check(evo_check *c, const std::vector<HostSeg> &whole, hipStream_t strea
     // first-level rows (one set per job) and second-level rows (at most one set per job);
     // bundle tickets (indexed like jobs) and segment tickets
     // (layout: see evo_internal.h)
-    if ((rc = ensure_partials(c, 2 * (size_t)total_jobs * evo::kRowsPerJob + total_ptrs)) != EVO_OK)
+    if ((rc = ensure_partials(c, 2 * (size_t)total_jobs * evo::kRowsPerJob + total_ptrs, stream)) != EVO_OK)
         return rc;
     if ((rc = ensure_tickets(c, (size_t)total_jobs + 2 * S, stream)) != EVO_OK) return rc;
 
@@ -449,17 +500,19 @@ int run_check(evo_check *c, const std::vector<HostSeg> &whole, hipStream_t strea
             // one case group writes its rows once; independent segments write theirs each
             evo::FitLaunch f = *fit;
             f.writers = segs[0].n_cases > 1 ? 1u : (uint32_t)S;
-            return dev(evo::launch_evaluate(dtype_set, tab, (uint32_t)S, total_jobs, c->atol, c->rtol,
+            return dev(evo::launch_evaluate(dtype_set, tab, (uint32_t)S, total_jobs,
                                             c->n_cus, c->d_partials, c->d_tickets, stats, f, stream));
         }
-        return dev(evo::launch_check_inline(dtype_set, tab, (uint32_t)S, total_jobs, c->atol, c->rtol,
+        return dev(evo::launch_check_inline(dtype_set, tab, (uint32_t)S, total_jobs,
                                             c->n_cus, c->d_partials, c->d_tickets, stats, stream));
     }
 
     // blob = descriptors, then all candidate pointers, staged through pinned memory
     const size_t desc_bytes = S * sizeof(SegDesc);
     const size_t blob_bytes = desc_bytes + total_ptrs * sizeof(uint64_t);
-    if ((rc = ensure_table(c, blob_bytes)) != EVO_OK) return rc;
+    // a replay of a captured copy would read whatever the staging slot holds by then
+    if (capturing(stream)) return EVO_ERR_CAPTURE;
+    if ((rc = ensure_table(c, blob_bytes, stream)) != EVO_OK) return rc;
     StageSlot *slot = nullptr;
     if ((rc = acquire_slot(c, blob_bytes, &slot)) != EVO_OK) return rc;
     char *hb = static_cast<char *>(slot->host);
@@ -477,7 +530,7 @@ int run_check(evo_check *c, const std::vector<HostSeg> &whole, hipStream_t strea
     rc = dev(evo::launch_check(
         dtype_set, static_cast<const SegDesc *>(c->d_table),
         reinterpret_cast<const uint64_t *>(static_cast<char *>(c->d_table) + desc_bytes), (uint32_t)S,
-        total_jobs, c->atol, c->rtol, c->n_cus, c->d_partials, c->d_tickets, stats, stream));
+        total_jobs, c->n_cus, c->d_partials, c->d_tickets, stats, stream));
     if (rc != EVO_OK || !fit) return rc;
     return dev(evo::launch_fitness(fit->timings, fit->baseline, fit->P, fit->T, fit->reducer, stats,
                                    fit->summary, fit->base, fit->ticket, stream));
@@ -485,16 +538,17 @@ int run_check(evo_check *c, const std::vector<HostSeg> &whole, hipStream_t strea
 
 // The groups of a segmented call: each valid on its own, rows inside [0, n_rows) and not
 // shared between groups.  covered: rows that belong to some group.
-int collect_segments(const evo_segment *segs, uint32_t S, uint32_t n_rows, std::vector<HostSeg> &hs,
-                     uint64_t &covered) {
+int collect_segments(const evo_check *c, const evo_segment *segs, uint32_t S, uint32_t n_rows,
+                     std::vector<HostSeg> &hs, uint64_t &covered) {
     hs.resize(S);
     std::vector<std::pair<uint64_t, uint64_t>> ranges(S);
     covered = 0;
     for (uint32_t s = 0; s < S; ++s) {
         hs[s] = HostSeg{segs[s].ref, segs[s].cand_ptrs, segs[s].n_elems, segs[s].P_s,
                         segs[s].dtype, segs[s].stats_row0, 0u, 1u};
-        const int rc = validate_seg(hs[s]);
+        int rc = validate_seg(hs[s]);
         if (rc != EVO_OK) return rc;
+        if ((rc = resolve_tolerance(c, segs[s].tol_class, hs[s])) != EVO_OK) return rc;
         const uint64_t lo = segs[s].stats_row0, hi = lo + segs[s].P_s;
         if (hi > n_rows) return EVO_ERR_SIZE;
         ranges[s] = {lo, hi};
@@ -516,14 +570,12 @@ int evo_check_create(evo_check_t **out, evo_dtype dtype, uint64_t n_elems, float
     *out = nullptr;
     if (!dtype_ok((uint32_t)dtype)) return EVO_ERR_DTYPE;
     if (n_elems == 0) return EVO_ERR_SIZE;
-    if (!(atol >= 0.0f) || !(rtol >= 0.0f) || std::isinf(atol) || std::isinf(rtol))
-        return EVO_ERR_TOL;
+    if (!tolerance_ok(atol, rtol)) return EVO_ERR_TOL;
     evo_check *c = new (std::nothrow) evo_check();
     if (!c) return EVO_ERR_NOMEM;
     c->dtype = dtype;
     c->n_elems = n_elems;
-    c->atol = atol;
-    c->rtol = rtol;
+    for (Tolerance &t : c->by_dtype) t = Tolerance{atol, rtol, true};
     try {
         std::lock_guard<std::mutex> lk(g_mu);
         g_live.insert(c);
@@ -535,14 +587,31 @@ int evo_check_create(evo_check_t **out, evo_dtype dtype, uint64_t n_elems, float
     return EVO_OK;
 }
 
+int evo_check_set_tolerance(evo_check_t *c, evo_dtype dtype, float atol, float rtol) {
+    if (!is_live(c)) return EVO_ERR_HANDLE;
+    if (!dtype_ok((uint32_t)dtype)) return EVO_ERR_DTYPE;
+    if (!tolerance_ok(atol, rtol)) return EVO_ERR_TOL;
+    c->by_dtype[(uint32_t)dtype] = Tolerance{atol, rtol, true};
+    return EVO_OK;
+}
+
+int evo_check_set_tolerance_class(evo_check_t *c, uint32_t tol_class, float atol, float rtol) {
+    if (!is_live(c)) return EVO_ERR_HANDLE;
+    if (tol_class == 0 || tol_class > kTolClasses) return EVO_ERR_SIZE;
+    if (!tolerance_ok(atol, rtol)) return EVO_ERR_TOL;
+    c->by_class[tol_class] = Tolerance{atol, rtol, true};
+    return EVO_OK;
+}
+
 int evo_check_batch(evo_check_t *c, const void *ref, const void *const *cand_ptrs, uint32_t P,
                     void *stream, evo_stats *stats) {
     if (!is_live(c)) return EVO_ERR_HANDLE;
     if (!stats) return EVO_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(stats) & 7u) return EVO_ERR_ALIGN;
     HostSeg h{ref, cand_ptrs, c->n_elems, P, (uint32_t)c->dtype, 0u, 0u, 1u};
-    const int rc = validate_seg(h);
+    int rc = validate_seg(h);
     if (rc != EVO_OK) return rc;
+    if ((rc = resolve_tolerance(c, 0u, h)) != EVO_OK) return rc;
     try {
         std::vector<HostSeg> segs(1, h);
         return run_check(c, segs, static_cast<hipStream_t>(stream), stats);
@@ -556,9 +625,10 @@ int evo_check_batch_static(evo_check_t *c, const void *ref, const void *const *c
     if (!is_live(c)) return EVO_ERR_HANDLE;
     if (!stats) return EVO_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(stats) & 7u) return EVO_ERR_ALIGN;
-    const HostSeg h{ref, cand_ptrs, c->n_elems, P, (uint32_t)c->dtype, 0u, 0u, 1u};
+    HostSeg h{ref, cand_ptrs, c->n_elems, P, (uint32_t)c->dtype, 0u, 0u, 1u};
     int rc = validate_seg(h);
     if (rc != EVO_OK) return rc;
+    if ((rc = resolve_tolerance(c, 0u, h)) != EVO_OK) return rc;
     if (P > evo::kInlinePtrs) return EVO_ERR_LIMIT;
     if ((rc = bind_device(c)) != EVO_OK) return rc;
     if (c->n_cus == 0) {
@@ -601,7 +671,7 @@ int evo_check_batch_static(evo_check_t *c, const void *ref, const void *const *c
     // are cleared by a small fill kernel in front (not a memset node, so that the pair of
     // launches can be captured into a graph).
     EVO_TRY(evo::launch_flush(tickets, ((size_t)total_jobs + 2 * S) * sizeof(uint32_t), 0u, st));
-    return dev(evo::launch_check_inline(dtype_set, tab, (uint32_t)S, total_jobs, c->atol, c->rtol, c->n_cus,
+    return dev(evo::launch_check_inline(dtype_set, tab, (uint32_t)S, total_jobs, c->n_cus,
                                         partials, tickets, stats, st));
 }
 
@@ -614,7 +684,7 @@ int evo_check_segmented(evo_check_t *c, const evo_segment *segs, uint32_t S, voi
     try {
         std::vector<HostSeg> hs;
         uint64_t covered = 0;
-        const int rc = collect_segments(segs, S, n_rows, hs, covered);
+        const int rc = collect_segments(c, segs, S, n_rows, hs, covered);
         if (rc != EVO_OK) return rc;
         return run_check(c, hs, static_cast<hipStream_t>(stream), stats);
     } catch (const std::bad_alloc &) {
@@ -633,8 +703,9 @@ int evo_check_cases(evo_check_t *c, const evo_segment *cases, uint32_t K, void *
         for (uint32_t k = 0; k < K; ++k) {
             hs[k] = HostSeg{cases[k].ref, cases[k].cand_ptrs, cases[k].n_elems, cases[k].P_s,
                             cases[k].dtype, 0u, 0u, K};
-            const int rc = validate_seg(hs[k]);
+            int rc = validate_seg(hs[k]);
             if (rc != EVO_OK) return rc;
+            if ((rc = resolve_tolerance(c, cases[k].tol_class, hs[k])) != EVO_OK) return rc;
             if (cases[k].P_s != cases[0].P_s || cases[k].stats_row0 != 0) return EVO_ERR_SIZE;
         }
         return run_check(c, hs, static_cast<hipStream_t>(stream), stats);
@@ -690,6 +761,7 @@ int evo_select_elite_diverse(evo_check_t *c, const evo_stats *stats, const uint3
     const int rc = bind_device(c);
     if (rc != EVO_OK) return rc;
     if (P > c->rep_count) {
+        if (capturing(static_cast<hipStream_t>(stream))) return EVO_ERR_CAPTURE;
         if (c->d_rep) EVO_TRY(hipFree(c->d_rep));
         c->d_rep = nullptr;
         c->rep_count = 0;
@@ -716,15 +788,16 @@ int evo_evaluate(evo_check_t *c, const evo_segment *cases, uint32_t K, const flo
         for (uint32_t k = 0; k < K; ++k) {
             hs[k] = HostSeg{cases[k].ref, cases[k].cand_ptrs, cases[k].n_elems, cases[k].P_s,
                             cases[k].dtype, 0u, 0u, K};
-            const int rc = validate_seg(hs[k]);
+            int rc = validate_seg(hs[k]);
             if (rc != EVO_OK) return rc;
+            if ((rc = resolve_tolerance(c, cases[k].tol_class, hs[k])) != EVO_OK) return rc;
             if (cases[k].P_s != cases[0].P_s || cases[k].stats_row0 != 0) return EVO_ERR_SIZE;
         }
         int rc = bind_device(c);
         if (rc != EVO_OK) return rc;
         hipStream_t st = static_cast<hipStream_t>(stream);
         if ((rc = ensure_fitness_scratch(c, st)) != EVO_OK) return rc;
-        if ((rc = ensure_fit_rows(c, cases[0].P_s)) != EVO_OK) return rc;
+        if ((rc = ensure_fit_rows(c, cases[0].P_s, st)) != EVO_OK) return rc;
         const evo::FitLaunch fit{timings, baseline, summary, c->d_base_median, c->d_fit_rows,
                                  c->d_fit_ticket, cases[0].P_s, T, (uint32_t)reducer, 1u};
         return run_check(c, hs, st, stats, &fit);
@@ -747,13 +820,13 @@ int evo_evaluate_segmented(evo_check_t *c, const evo_segment *segs, uint32_t S, 
     try {
         std::vector<HostSeg> hs;
         uint64_t covered = 0;
-        int rc = collect_segments(segs, S, n_rows, hs, covered);
+        int rc = collect_segments(c, segs, S, n_rows, hs, covered);
         if (rc != EVO_OK) return rc;
         if (covered != n_rows) return EVO_ERR_SIZE;   // a row without a group has no valid flag
         if ((rc = bind_device(c)) != EVO_OK) return rc;
         hipStream_t st = static_cast<hipStream_t>(stream);
         if ((rc = ensure_fitness_scratch(c, st)) != EVO_OK) return rc;
-        if ((rc = ensure_fit_rows(c, n_rows)) != EVO_OK) return rc;
+        if ((rc = ensure_fit_rows(c, n_rows, st)) != EVO_OK) return rc;
         const evo::FitLaunch fit{timings, baseline, summary, c->d_base_median, c->d_fit_rows,
                                  c->d_fit_ticket, n_rows, T, (uint32_t)reducer, 1u};
         return run_check(c, hs, st, stats, &fit);
@@ -776,6 +849,7 @@ int evo_time_candidates(evo_check_t *c, const evo_launch_fn *launch, void *const
     int rc = bind_device(c);
     if (rc != EVO_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (capturing(st)) return EVO_ERR_CAPTURE;   // this call waits for its own runs
 
     // resources, on first use: two events per timed run plus two probe pairs, the pinned
     // staging table, the probe's sink, the flush buffer
@@ -881,12 +955,13 @@ const char *evo_strerror(int code) {
         case EVO_ERR_NULL: return "a required pointer is NULL";
         case EVO_ERR_DTYPE: return "unknown element type";
         case EVO_ERR_SIZE: return "zero or out-of-range count";
-        case EVO_ERR_TOL: return "tolerance is negative, NaN or infinite";
+        case EVO_ERR_TOL: return "tolerance is negative, NaN or infinite, or the tolerance class is not set";
         case EVO_ERR_ALIGN: return "pointer not aligned to its element size";
         case EVO_ERR_DEVICE: return "HIP call failed";
         case EVO_ERR_NOMEM: return "out of memory";
         case EVO_ERR_HANDLE: return "not a live context";
         case EVO_ERR_LIMIT: return "beyond the fixed capacity of the call that allocates nothing";
+        case EVO_ERR_CAPTURE: return "the stream is capturing and the call would have to allocate, clear or stage";
         default: return "unknown status";
     }
 }

@@ -18,10 +18,18 @@
 
 namespace evo {
 static int g_launches = 0;
-hipError_t launch_check(uint32_t, const SegDesc *, const uint64_t *, uint32_t, uint32_t, float, float,
+hipError_t launch_check(uint32_t, const SegDesc *, const uint64_t *, uint32_t, uint32_t,
                         uint32_t, Partial *, uint32_t *, evo_stats *, hipStream_t) { ++g_launches; return hipSuccess; }
-hipError_t launch_check_inline(uint32_t, const InlineTable &, uint32_t, uint32_t, float, float, uint32_t,
-                               Partial *, uint32_t *, evo_stats *, hipStream_t) { ++g_launches; return hipSuccess; }
+static float g_last_atol[8], g_last_rtol[8];   // tolerances of the last inline launch's descriptors
+hipError_t launch_check_inline(uint32_t, const InlineTable &tab, uint32_t S, uint32_t, uint32_t,
+                               Partial *, uint32_t *, evo_stats *, hipStream_t) {
+    for (uint32_t s = 0; s < S && s < 8; ++s) {
+        g_last_atol[s] = tab.descs[s].atol;
+        g_last_rtol[s] = tab.descs[s].rtol;
+    }
+    ++g_launches;
+    return hipSuccess;
+}
 hipError_t launch_fitness(const float *, const float *, uint32_t, uint32_t, uint32_t, evo_stats *,
                           evo_pop_summary *, float *, uint32_t *, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_select(const evo_stats *, uint32_t, uint32_t, uint32_t *, uint32_t *, hipStream_t) {
@@ -30,7 +38,7 @@ hipError_t launch_select(const evo_stats *, uint32_t, uint32_t, uint32_t *, uint
 }
 hipError_t launch_select_diverse(const evo_stats *, const uint32_t *, uint32_t *, uint32_t, uint32_t, uint32_t *,
                                  uint32_t *, hipStream_t) { ++g_launches; return hipSuccess; }
-hipError_t launch_evaluate(uint32_t, const InlineTable &, uint32_t, uint32_t, float, float, uint32_t, Partial *,
+hipError_t launch_evaluate(uint32_t, const InlineTable &, uint32_t, uint32_t, uint32_t, Partial *,
                            uint32_t *, evo_stats *, const FitLaunch &, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_flush(void *, size_t, uint32_t, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_probe(float *, uint32_t, hipStream_t) { ++g_launches; return hipSuccess; }
@@ -61,10 +69,9 @@ static uint64_t rng() {
 //  5. the launch fits the target when there is room for it (at most one job per segment
 //     is forced, and the cap on tiles per wavefront can force more).
 static void check_partition(const std::vector<HostSeg> &segs, uint32_t target) {
-    std::vector<SegDesc> d;
+    std::vector<SegDesc> d(segs.size());
     uint32_t total = 0;
-    partition(segs, target, d, total);
-    EXPECT(d.size() == segs.size());
+    partition(segs.data(), segs.size(), target, d.data(), total);
     uint64_t job = 0;
     bool capped = false;
     for (size_t s = 0; s < segs.size(); ++s) {
@@ -120,9 +127,9 @@ static void partition_cases() {
             h.cand_ptrs = nullptr;
             h.row0 = row0;
             row0 += h.P;
-            if (!partition_fits(std::vector<HostSeg>(1, h))) h.n = 1 + h.n % 4096;
+            if (!partition_fits(&h, 1)) h.n = 1 + h.n % 4096;
         }
-        if (!partition_fits(segs)) continue;
+        if (!partition_fits(segs.data(), segs.size())) continue;
         check_partition(segs, targets[it % 5]);
     }
     // the shapes the benchmark runs: one dense tensor, one 2^30 one
@@ -132,7 +139,7 @@ static void partition_cases() {
     h.n = 1ull << 30; h.P = 8;
     check_partition(std::vector<HostSeg>(1, h), 512);
     h.n = 1ull << 40; h.P = kMaxP;          // too large: refused before partitioning
-    EXPECT(!partition_fits(std::vector<HostSeg>(1, h)));
+    EXPECT(!partition_fits(&h, 1));
 }
 
 // split_remainders(): a segment stays whole or is cut in two; the parts cover its
@@ -205,9 +212,9 @@ static void split_cases() {
     b.P = 1;
     b.row0 = 16;
     std::vector<HostSeg> two{a, b};
-    std::vector<SegDesc> d;
+    std::vector<SegDesc> d(2);
     uint32_t total = 0;
-    partition(two, 512, d, total);
+    partition(two.data(), 2, 512, d.data(), total);
     EXPECT(total <= 512 && total >= 500);
     EXPECT(d[0].n_jobs > 5 * d[1].n_jobs && d[0].n_jobs < 6 * d[1].n_jobs);
 }
@@ -270,6 +277,34 @@ static void validation_cases() {
         EXPECT(evo_check_batch(c, ref, bad, 3, nullptr, stats) == EVO_ERR_NULL);
         bad[1] = arena + 33;
         EXPECT(evo_check_batch(c, ref, bad, 3, nullptr, stats) == EVO_ERR_ALIGN);
+    }
+
+    // the call that allocates nothing: the checks of evo_check_batch, plus its capacity
+    EXPECT(evo_check_batch_static(nullptr, ref, cands, 3, nullptr, stats) == EVO_ERR_HANDLE);
+    EXPECT(evo_check_batch_static(c, nullptr, cands, 3, nullptr, stats) == EVO_ERR_NULL);
+    EXPECT(evo_check_batch_static(c, ref, cands, 3, nullptr, nullptr) == EVO_ERR_NULL);
+    EXPECT(evo_check_batch_static(c, ref, cands, 0, nullptr, stats) == EVO_ERR_SIZE);
+    EXPECT(evo_check_batch_static(c, arena + 2, cands, 3, nullptr, stats) == EVO_ERR_ALIGN);
+    {
+        std::vector<const void *> many(385, arena + 64);
+        EXPECT(evo_check_batch_static(c, ref, many.data(), 385, nullptr, stats) == EVO_ERR_LIMIT);
+    }
+
+    // tolerance policy
+    EXPECT(evo_check_set_tolerance(nullptr, EVO_F32, 0.f, 0.f) == EVO_ERR_HANDLE);
+    EXPECT(evo_check_set_tolerance(c, (evo_dtype)6, 0.f, 0.f) == EVO_ERR_DTYPE);
+    EXPECT(evo_check_set_tolerance(c, EVO_BF16, -1.f, 0.f) == EVO_ERR_TOL);
+    EXPECT(evo_check_set_tolerance(c, EVO_BF16, 0.f, __builtin_huge_valf()) == EVO_ERR_TOL);
+    EXPECT(evo_check_set_tolerance_class(nullptr, 1, 0.f, 0.f) == EVO_ERR_HANDLE);
+    EXPECT(evo_check_set_tolerance_class(c, 0, 0.f, 0.f) == EVO_ERR_SIZE);
+    EXPECT(evo_check_set_tolerance_class(c, EVO_TOL_CLASSES + 1, 0.f, 0.f) == EVO_ERR_SIZE);
+    EXPECT(evo_check_set_tolerance_class(c, 2, __builtin_nanf(""), 0.f) == EVO_ERR_TOL);
+    {
+        evo_segment one = {ref, cands, 100, 3, EVO_F32, 0, 3};          // class 3 was never set
+        EXPECT(evo_check_segmented(c, &one, 1, nullptr, stats, 3) == EVO_ERR_TOL);
+        EXPECT(evo_check_cases(c, &one, 1, nullptr, stats) == EVO_ERR_TOL);
+        one.tol_class = EVO_TOL_CLASSES + 1;
+        EXPECT(evo_check_segmented(c, &one, 1, nullptr, stats, 3) == EVO_ERR_TOL);
     }
 
     evo_segment seg[2] = {{ref, cands, 100, 3, EVO_F32, 0, 0}, {ref, cands, 7, 2, EVO_BF16, 3, 0}};
@@ -428,6 +463,19 @@ static void validation_cases() {
     EXPECT(rc1 == EVO_OK || rc1 == EVO_ERR_DEVICE);
     const int rc2 = evo_check_segmented(c, seg, 2, nullptr, stats, 5);
     EXPECT(rc2 == rc1);
+    if (rc1 == EVO_OK) {
+        // every group is launched with the tolerance of its element type, or of its class
+        EXPECT(evo::g_last_atol[0] == 1e-2f && evo::g_last_rtol[1] == 1e-2f);
+        EXPECT(evo_check_set_tolerance(c, EVO_BF16, 0.5f, 0.25f) == EVO_OK);
+        EXPECT(evo_check_set_tolerance_class(c, 7, 3.0f, 0.0f) == EVO_OK);
+        EXPECT(evo_check_segmented(c, seg, 2, nullptr, stats, 5) == EVO_OK);
+        EXPECT(evo::g_last_atol[0] == 1e-2f && evo::g_last_rtol[0] == 1e-2f);
+        EXPECT(evo::g_last_atol[1] == 0.5f && evo::g_last_rtol[1] == 0.25f);
+        seg[0].tol_class = 7;
+        EXPECT(evo_check_segmented(c, seg, 2, nullptr, stats, 5) == EVO_OK);
+        EXPECT(evo::g_last_atol[0] == 3.0f && evo::g_last_rtol[0] == 0.0f && evo::g_last_atol[1] == 0.5f);
+        seg[0].tol_class = 0;
+    }
     const int rc3 = evo_check_cases(c, cs, 2, nullptr, stats);
     EXPECT(rc3 == rc1);
     if (rc1 == EVO_OK) {
@@ -453,7 +501,7 @@ static void validation_cases() {
     EXPECT(evo_check_destroy(nullptr) == EVO_ERR_HANDLE);
     EXPECT(evo_check_batch(c, ref, cands, 3, nullptr, stats) == EVO_ERR_HANDLE);
 
-    for (int code = 1; code >= -10; --code) EXPECT(evo_strerror(code) != nullptr && evo_strerror(code)[0]);
+    for (int code = 1; code >= -12; --code) EXPECT(evo_strerror(code) != nullptr && evo_strerror(code)[0]);
 }
 
 int main() {

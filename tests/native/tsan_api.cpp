@@ -10,11 +10,11 @@
 #include <thread>
 
 namespace evo {
-hipError_t launch_check(uint32_t, const SegDesc *, const uint64_t *, uint32_t, uint32_t, float, float,
+hipError_t launch_check(uint32_t, const SegDesc *, const uint64_t *, uint32_t, uint32_t,
                         uint32_t, Partial *, uint32_t *, evo_stats *, hipStream_t) { return hipSuccess; }
-hipError_t launch_check_inline(uint32_t, const InlineTable &, uint32_t, uint32_t, float, float, uint32_t,
+hipError_t launch_check_inline(uint32_t, const InlineTable &, uint32_t, uint32_t, uint32_t,
                                Partial *, uint32_t *, evo_stats *, hipStream_t) { return hipSuccess; }
-hipError_t launch_evaluate(uint32_t, const InlineTable &, uint32_t, uint32_t, float, float, uint32_t, Partial *,
+hipError_t launch_evaluate(uint32_t, const InlineTable &, uint32_t, uint32_t, uint32_t, Partial *,
                            uint32_t *, evo_stats *, const FitLaunch &, hipStream_t) { return hipSuccess; }
 hipError_t launch_fitness(const float *, const float *, uint32_t, uint32_t, uint32_t, evo_stats *,
                           evo_pop_summary *, float *, uint32_t *, hipStream_t) { return hipSuccess; }

@@ -601,10 +601,63 @@ def pin_select_elite_diverse(orc):
         assert got["elite"].tolist() == want + [P] * (k - len(want)), (P, k)
 
 
+def pin_tolerance_policy(orc):
+    """Every group of a launch is checked with the pair of its element type, or of the class it
+    names: the hand-built example, groups against single checks with the pair written out,
+    and an unset class is an error."""
+    dt = {"f32": (orc.F32, np.float32), "bf16": (orc.BF16, None)}
+    for ex in _load_examples()["policy"]:
+        pol = orc.TolerancePolicy(ex["default"]["atol"], ex["default"]["rtol"])
+        for name, pr in ex["by_dtype"].items():
+            pol.set_dtype(dt[name][0], pr["atol"], pr["rtol"])
+        for cls, pr in ex["by_class"].items():
+            pol.set_class(int(cls), pr["atol"], pr["rtol"])
+        r32, c32 = _arr(ex["ref"]), _arr(ex["cand"])
+        as_bf16 = lambda a: (a.view(np.uint32) >> 16).astype(np.uint16)   # exact for these values
+        assert np.array_equal((as_bf16(c32).astype(np.uint32) << 16).view(np.float32), c32)
+        segs = []
+        for g in ex["groups"]:
+            code = dt[g["dtype"]][0]
+            r, c = (r32, c32) if g["dtype"] == "f32" else (as_bf16(r32), as_bf16(c32))
+            segs.append((r, [c], code, g["tol_class"]))
+        rows = orc.check_segments(segs, pol)
+        assert len(rows) == len(ex["groups"])
+        for row, g in zip(rows, ex["groups"]):
+            assert row["n_mismatch"] == g["n_mismatch"] and row["valid"] == g["valid"], (ex["name"], g, row)
+            assert row["n_finite"] == len(ex["ref"]) and row["flags"] == 0
+            assert _same_f32(row["max_abs_err"], ex["max_abs_err"]) and _same_f32(row["max_rel_err"], ex["max_rel_err"])
+            assert row["sum_abs_err"] == ex["sum_abs_err"] and row["sum_rel_err"] == ex["sum_rel_err"]
+        one = orc.check_cases(segs, pol)
+        assert len(one) == 1
+        for key, want in ex["as_cases"].items():
+            assert one[0][key] == want, (ex["name"], key, one[0])
+        assert one[0]["n_elems"] == len(ex["ref"]) * len(ex["groups"])
+    # groups against single checks with the pair written out
+    rng = np.random.default_rng(77)
+    pol = orc.TolerancePolicy(1e-3, 1e-3)
+    pol.set_dtype(orc.F64, 1e-9, 1e-9)
+    pol.set_class(5, 0.5, 0.0)
+    r32 = rng.standard_normal(300).astype(np.float32)
+    c32 = (r32 * (1 + 2e-3 * rng.standard_normal(300))).astype(np.float32)
+    r64 = rng.standard_normal(200)
+    c64 = r64 * (1 + 2e-9 * rng.standard_normal(200))
+    rows = orc.check_segments([(r32, [c32], orc.F32, 0), (r64, [c64], orc.F64, 0), (r32, [c32], orc.F32, 5)], pol)
+    assert rows[0] == orc.check_one(r32, c32, orc.F32, 1e-3, 1e-3)
+    assert rows[1] == orc.check_one(r64, c64, orc.F64, 1e-9, 1e-9)
+    assert rows[2] == orc.check_one(r32, c32, orc.F32, 0.5, 0.0)
+    assert 0 < rows[0]["n_mismatch"] < 300 and 0 < rows[1]["n_mismatch"] < 200 and rows[2]["n_mismatch"] == 0
+    try:
+        orc.check_segments([(r32, [c32], orc.F32, 6)], pol)
+    except KeyError:
+        pass
+    else:
+        raise AssertionError("a tolerance class that was never set must be refused")
+
+
 ALL_PINS = [
     pin_truth_table, pin_flag_classes, pin_worked_check_examples, pin_worked_fitness_examples,
     pin_numpy_isclose, pin_sums_and_maxima, pin_invariants, pin_bf16_widening, pin_f16_widening,
     pin_median_and_speedup, pin_unusable_timing_rows, pin_select_elite,
     pin_f64_truth_table, pin_f64_numpy_isclose_sums_maxima, pin_f64_agrees_with_f32_where_both_are_exact,
-    pin_integer_equality, pin_mean_reducer, pin_select_elite_diverse,
+    pin_integer_equality, pin_mean_reducer, pin_select_elite_diverse, pin_tolerance_policy,
 ]

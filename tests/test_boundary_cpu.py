@@ -28,7 +28,8 @@ def declared_functions():
 
 def test_header_declares_the_documented_entry_points():
     assert declared_functions() == ["evo_check_batch", "evo_check_batch_static", "evo_check_cases", "evo_check_create",
-                                    "evo_check_destroy", "evo_check_segmented", "evo_evaluate",
+                                    "evo_check_destroy", "evo_check_segmented", "evo_check_set_tolerance",
+                                    "evo_check_set_tolerance_class", "evo_evaluate",
                                     "evo_evaluate_segmented",
                                     "evo_fitness",
                                     "evo_fitness_ex", "evo_select_elite", "evo_select_elite_diverse",

@@ -254,3 +254,95 @@ def test_fitness_ratio_of_means(gu, T):
         med_run = oracle.fitness(tim.cpu().numpy(), base.cpu().numpy(), valid)
         assert mean_run["speedup"][6] < 0.5 * med_run["speedup"][6]
     chk.close()
+
+
+def test_tolerance_policy_in_one_launch(gu):
+    """Groups of different element types and tolerance classes in ONE launch, each checked with
+    its own pair (functional testing over outputs of different precisions, Sec. 4.3): the
+    ragged call, the fused ragged call and the test-case call against the oracle's policy."""
+    _say("tolerance policy")
+    import oracle
+    import paper_2510_03760_amd as evo
+    from paper_2510_03760_amd.binding import stats_to_numpy, summary_to_numpy
+    g = torch.Generator(device="cuda")
+    g.manual_seed(91)
+
+    def group(n, P, dtype, noise):
+        r = torch.randn(n, generator=g, device="cuda", dtype=torch.float64)
+        cs = [(r * (1 + noise * torch.randn(n, generator=g, device="cuda", dtype=torch.float64))).to(dtype).contiguous()
+              for _ in range(P)]
+        return r.to(dtype).contiguous(), cs
+
+    P = 5
+    spec = [   # (tensors, element type codes, tolerance class)
+        (group(70001, P, torch.float32, 2e-4), evo.EVO_F32, oracle.F32, 0),
+        (group(33000, P, torch.bfloat16, 6e-3), evo.EVO_BF16, oracle.BF16, 0),
+        (group(12345, P, torch.float16, 8e-4), evo.EVO_F16, oracle.F16, 0),
+        (group(50000, P, torch.float64, 2e-9), evo.EVO_F64, oracle.F64, 0),
+        (group(4096, P, torch.float32, 2e-4), evo.EVO_F32, oracle.F32, 4),     # a stricter class
+        (group(300, P, torch.bfloat16, 6e-3), evo.EVO_BF16, oracle.BF16, 9),   # a looser class
+    ]
+    pol = oracle.TolerancePolicy(1e-4, 3e-4)
+    chk = evo.Checker(evo.EVO_F32, 1, 1e-4, 3e-4)
+    for code, ocode, atol, rtol in ((evo.EVO_BF16, oracle.BF16, 1e-2, 8e-3), (evo.EVO_F16, oracle.F16, 1e-3, 1e-3),
+                                    (evo.EVO_F64, oracle.F64, 1e-9, 3e-9)):
+        chk.set_tolerance(code, atol, rtol)
+        pol.set_dtype(ocode, atol, rtol)
+    for cls, atol, rtol in ((4, 0.0, 1e-4), (9, 0.25, 0.0)):
+        chk.set_tolerance_class(cls, atol, rtol)
+        pol.set_class(cls, atol, rtol)
+
+    descs, osegs, row0 = [], [], 0
+    for (r, cs), code, ocode, cls in spec:
+        descs.append({"ref": r, "cand_ptrs": cs, "n_elems": r.numel(), "dtype": code, "stats_row0": row0,
+                      "tol_class": cls})
+        osegs.append((synth.to_oracle_array(r), [synth.to_oracle_array(c) for c in cs], ocode, cls))
+        row0 += len(cs)
+    want = oracle.check_segments(osegs, pol, threads=8)
+    # the tolerances differ enough to matter: some groups reject elements, some accept all
+    per_group = [sum(w["n_mismatch"] for w in want[i * P:(i + 1) * P]) for i in range(len(spec))]
+    assert all(m > 0 for m in per_group[:5]) and per_group[5] == 0, per_group
+
+    stats = chk.new_stats(row0)
+    stats.fill_(0xAB)
+    chk.check_segmented(descs, stats, row0)
+    torch.cuda.synchronize()
+    got = stats_to_numpy(stats)
+    for i, (gr, w) in enumerate(zip(got, want)):
+        gu.assert_rows_equal(gr, w, "policy row %d" % i)
+
+    # the fused ragged call uses the same pairs
+    T = 6
+    tim = 1 + torch.rand(row0, T, generator=g, device="cuda")
+    base = 1 + torch.rand(T, generator=g, device="cuda")
+    stats2, summary = chk.new_stats(row0), chk.new_summary()
+    chk.evaluate_segmented(descs, tim, base, stats2, row0, summary)
+    torch.cuda.synchronize()
+    got2 = stats_to_numpy(stats2)
+    for i, (gr, w) in enumerate(zip(got2, want)):
+        gu.assert_rows_equal(gr, w, "policy (fused) row %d" % i)
+    fit = oracle.fitness(tim.cpu().numpy(), base.cpu().numpy(), np.array([w["valid"] for w in want], np.uint32))
+    for f in ("median_ms", "mean_ms", "speedup", "fitness"):
+        assert got2[f].tobytes() == fit[f].tobytes(), f
+    assert int(summary_to_numpy(summary)[0]["n_valid"]) == fit["n_valid"]
+
+    # as test cases of the same P candidates: one row per candidate, each case with its pair
+    cases = [{k: v for k, v in d.items() if k != "stats_row0"} for d in descs]
+    stats3 = chk.new_stats(P)
+    stats3.fill_(0xAB)
+    chk.check_cases(cases, stats3)
+    torch.cuda.synchronize()
+    got3 = stats_to_numpy(stats3)
+    want3 = oracle.check_cases(osegs, pol)
+    for p in range(P):
+        gu.assert_rows_equal(got3[p], want3[p], "policy case row %d" % p)
+
+    # a class that was never set is refused before anything is enqueued
+    bad = dict(descs[0], tol_class=7)
+    stats.fill_(0x5A)
+    with pytest.raises(evo.EvoError) as err:
+        chk.check_segmented([bad], stats, row0)
+    assert err.value.code == -4
+    torch.cuda.synchronize()
+    assert int(stats.min()) == 0x5A and int(stats.max()) == 0x5A
+    chk.close()

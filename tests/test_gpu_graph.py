@@ -62,3 +62,77 @@ def test_evaluate_and_select_in_a_graph(gu):
             eager()                      # eager work between replays
     assert int(want[3][0]) == 4
     chk.close()
+
+
+def test_capture_is_refused_when_the_call_would_allocate_or_stage(gu):
+    """Under stream capture a call may only enqueue kernels.  A context that has never run the
+    shape (its scratch memory would have to be allocated and cleared) and a launch whose
+    table does not fit the kernel arguments (it would be copied from a staging buffer that
+    later calls overwrite) are refused with EVO_ERR_CAPTURE before anything is enqueued; the
+    same calls work eagerly, and after the eager run the first one can be captured."""
+    print("graph capture: refused cases", flush=True)
+    import paper_2510_03760_amd as evo
+    from paper_2510_03760_amd.binding import stats_to_numpy
+    n, T = 50000, 8
+    g = torch.Generator(device="cuda")
+    g.manual_seed(12)
+    ref = torch.randn(n, generator=g, device="cuda")
+    cands = [ref + 1e-3 * torch.randn(n, generator=g, device="cuda") for _ in range(6)]
+    cands[2][17] = 5.0
+    tim = 1 + torch.rand(6, T, generator=g, device="cuda")
+    base = 1 + torch.rand(T, generator=g, device="cuda")
+    cases = [{"ref": ref, "cand_ptrs": cands, "n_elems": n, "dtype": evo.EVO_F32}]
+    scratch = torch.zeros(16, device="cuda")
+
+    fresh = evo.Checker(evo.EVO_F32, n, 1e-2, 1e-2)
+    stats, summary = fresh.new_stats(6), fresh.new_summary()
+    stats.fill_(0x33)
+    codes = []
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        scratch.add_(1.0)                     # the graph is not empty
+        for call in (lambda: fresh.check_batch(ref, cands, stats),
+                     lambda: fresh.evaluate(cases, tim, base, stats, summary),
+                     lambda: fresh.fitness(tim, base, stats, summary)):
+            try:
+                call()
+                codes.append(0)
+            except evo.EvoError as e:
+                codes.append(e.code)
+    assert codes == [-10, -10, -10], codes
+    graph.replay()
+    torch.cuda.synchronize()
+    assert int(stats.min()) == 0x33 and int(stats.max()) == 0x33    # nothing was recorded
+
+    # eager run of the same shape, then the capture goes through and replays give its result
+    want_stats, want_summary = fresh.new_stats(6), fresh.new_summary()
+    fresh.evaluate(cases, tim, base, want_stats, want_summary)
+    torch.cuda.synchronize()
+    graph2 = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph2):
+        fresh.evaluate(cases, tim, base, stats, summary)
+    for rep in range(3):
+        stats.fill_(0x44)
+        graph2.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(stats, want_stats) and torch.equal(summary, want_summary), rep
+        fresh.check_batch(ref, cands, fresh.new_stats(6))          # eager work between replays
+        torch.cuda.synchronize()
+
+    # 400 candidate pointers do not fit the kernel arguments: staged path, eager only
+    many = [ref] * 399 + [cands[2]]
+    big = fresh.new_stats(400)
+    fresh.check_batch(ref, many, big)                               # eager: allocates, stages, runs
+    torch.cuda.synchronize()
+    rows = stats_to_numpy(big)
+    assert int(rows["valid"][:399].sum()) == 399 and int(rows["n_mismatch"][399]) == 1
+    graph3 = torch.cuda.CUDAGraph()
+    code = 0
+    with torch.cuda.graph(graph3):
+        scratch.add_(1.0)
+        try:
+            fresh.check_batch(ref, many, big)
+        except evo.EvoError as e:
+            code = e.code
+    assert code == -10
+    fresh.close()
