@@ -7,7 +7,13 @@ then the median-timing / speedup / fitness reduction.  Inputs are resident in HB
 before the timed region starts.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--spinup-ms MS] [--workload c2|c1|c3|c3h|c4|c5|cases|f64|i32|i64]
-                    [--no-cpu-baseline] [--no-read-ceiling] [--copy-calibration]
+                    [--no-cpu-baseline] [--no-read-ceiling] [--copy-calibration] [--no-extra-workloads]
+
+The JSON line is about --workload (default c2, the configuration the metric is quoted on).  With
+the default workload it also carries "workloads": the same measurement of the other large
+single-GPU workloads (c3, c4, c5; 20 steps each, after a spin-up of their own, the previous
+workload's tensors released first) with their roofline fractions and an agreement check of a
+stated pick of their rows against the CPU oracle on the whole tensors.
 
 --copy-calibration runs only a plain device-to-device copy of known size (used to
 scale the rocprofv3 FETCH_SIZE / WRITE_SIZE counters) and prints its own JSON line.
@@ -154,6 +160,183 @@ def cpu_baseline(w, budget_elems: int):
     return one, rows, frac
 
 
+def oracle_agreement(w, got, cand_pick, threads: int, chunk: int = 1 << 24):
+    """The GPU rows of the picked candidates of every group against the oracle on the WHOLE
+    tensors (copied to the host chunk by chunk; whole candidates side by side on `threads`
+    threads, each still reduced sequentially): integers, flags and maxima byte for byte,
+    the two error sums to 1e-6.  Part of the cpu_baseline leg."""
+    import numpy as np
+    import oracle
+    import synth
+    from concurrent.futures import ThreadPoolExecutor
+    t0 = time.perf_counter()
+    same, n_rows, row0 = True, 0, 0
+    for seg in w.segments:
+        dt = {"bf16": oracle.BF16, "f16": oracle.F16, "f64": oracle.F64, "i32": oracle.I32,
+              "i64": oracle.I64}.get(seg.dtype_name, oracle.F32)
+        picked = [p for p in range(len(seg.cands)) if cand_pick(p)]
+        accs = [oracle.CheckAccumulator(dt, w.atol, w.rtol) for _ in picked]
+        with ThreadPoolExecutor(max_workers=max(1, threads)) as ex:
+            for lo in range(0, seg.n, chunk):
+                hi = min(seg.n, lo + chunk)
+                r = synth.to_oracle_array(seg.ref[lo:hi])
+                list(ex.map(lambda ap: ap[0].feed(r, synth.to_oracle_array(seg.cands[ap[1]][lo:hi])),
+                            zip(accs, picked)))
+        for acc, p in zip(accs, picked):
+            o, g = acc.result(), got[row0 + p]
+            ok = (int(g["n_mismatch"]) == o["n_mismatch"] and int(g["n_finite"]) == o["n_finite"] and
+                  int(g["flags"]) == o["flags"] and int(g["valid"]) == o["valid"] and
+                  g["max_abs_err"].tobytes() == o["max_abs_err"].tobytes() and
+                  g["max_rel_err"].tobytes() == o["max_rel_err"].tobytes())
+            for f in ("sum_abs_err", "sum_rel_err"):
+                a, b = float(g[f]), float(o[f])
+                ok = ok and (a == b or abs(a - b) <= 1e-6 * abs(b))
+            same = same and ok
+            n_rows += 1
+        row0 += len(seg.cands)
+    return same, n_rows, time.perf_counter() - t0
+
+
+def measure(name: str, steps: int, warmup: int, spinup_ms: float, split: bool):
+    """Builds workload `name`, spins the device up, runs `warmup` untimed and `steps` timed steps
+    and returns (result fields, workload, checker, stats, summary).  One event per launch
+    boundary on the launch stream times every launch of the dominant kernel."""
+    import torch
+    import paper_2510_03760_amd as evo
+    from paper_2510_03760_amd.binding import stats_to_numpy, summary_to_numpy
+
+    w = build_workload(name)
+    torch.cuda.synchronize()
+    segs = w.segments
+    dcode = lambda s: {"bf16": evo.EVO_BF16, "f16": evo.EVO_F16, "f64": evo.EVO_F64,  # noqa: E731
+                       "i32": evo.EVO_I32, "i64": evo.EVO_I64}.get(s.dtype_name, evo.EVO_F32)
+    chk = evo.Checker(dcode(segs[0]), segs[0].n, w.atol, w.rtol)
+    P = w.P
+    stats = chk.new_stats(P)
+    summary = chk.new_summary()
+    stream = torch.cuda.current_stream()
+    seg_descs = None
+    is_cases = bool(w.notes.get("cases"))
+    if is_cases:
+        seg_descs = [{"ref": s.ref, "cand_ptrs": s.cands, "n_elems": s.n, "dtype": dcode(s)}
+                     for s in segs]
+    elif len(segs) > 1:
+        row0, seg_descs = 0, []
+        for s in segs:
+            seg_descs.append({"ref": s.ref, "cand_ptrs": s.cands, "n_elems": s.n,
+                              "dtype": dcode(s), "stats_row0": row0})
+            row0 += len(s.cands)
+
+    def check():
+        if seg_descs is None:
+            chk.check_batch(segs[0].ref, segs[0].cands, stats, stream=stream)
+        elif is_cases:
+            chk.check_cases(seg_descs, stats, stream=stream)
+        else:
+            chk.check_segmented(seg_descs, stats, P, stream=stream)
+
+    # One call (one launch) for the whole step: evo_evaluate where the population has one
+    # reference per test case, evo_evaluate_segmented for the ragged workload.
+    fused = not split
+    ragged = seg_descs is not None and not is_cases
+    eval_cases = seg_descs if is_cases else [{"ref": segs[0].ref, "cand_ptrs": segs[0].cands,
+                                              "n_elems": segs[0].n, "dtype": dcode(segs[0])}]
+
+    def step(mid=None):
+        if fused and ragged:
+            chk.evaluate_segmented(seg_descs, w.timings, w.baseline, stats, P, summary, stream=stream)
+        elif fused:
+            chk.evaluate(eval_cases, w.timings, w.baseline, stats, summary, stream=stream)
+        else:
+            check()
+            if mid is not None:
+                mid.record(stream)
+            chk.fitness(w.timings, w.baseline, stats, summary, stream=stream)
+
+    # Spin-up: the first tens of milliseconds of load in a process run at a varying clock (the
+    # same launch took 345-460 us over its first 60 repetitions and 345-355 us afterwards), and
+    # on a device that has been idle the first process can run at 0.6 of its later rate for
+    # longer than that.  The device is kept busy with the step for a stated time before the W
+    # warm-up steps, and beyond it (up to 2 s) until two consecutive batches of steps take the
+    # same time within 3 %.
+    # no cyclic garbage collection between here and the end of the timed region: with torch
+    # imported a full collection takes 5-20 ms, during which nothing is launched (as timeit does)
+    gc.collect()
+    gc.disable()
+    spun, per_batch = 0, 4
+    t_spin = time.perf_counter()
+    last = None
+    while spinup_ms > 0:
+        t_b = time.perf_counter()
+        for _ in range(per_batch):
+            step()
+        torch.cuda.synchronize()
+        now = time.perf_counter()
+        spun += per_batch
+        took = now - t_b
+        if took < 1e-3:                       # batches of at least a millisecond
+            per_batch *= 4
+            last = None
+            continue
+        elapsed_ms = (now - t_spin) * 1e3
+        settled = last is not None and abs(took - last) <= 0.03 * last
+        last = took
+        if elapsed_ms >= 2000.0 or (elapsed_ms >= spinup_ms and settled):
+            break
+    spin_ms = (time.perf_counter() - t_spin) * 1e3
+    # the warm-up steps record events the way the timed steps do, so that whatever the runtime
+    # sets up for the first events of a process is set up before the timed region
+    for _ in range(warmup):
+        torch.cuda.Event(enable_timing=True).record(stream)
+        step(None if fused else torch.cuda.Event(enable_timing=True))
+    torch.cuda.Event(enable_timing=True).record(stream)
+    torch.cuda.synchronize()
+
+    # One event between consecutive steps (plus one inside a step when it is two launches):
+    # enough to time every launch of the dominant kernel on its stream, and no more than
+    # that inside the timed region.
+    bounds = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    mids = [None if fused else torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    bounds[0].record(stream)
+    for k in range(steps):
+        step(mids[k])
+        bounds[k + 1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    gc.enable()
+
+    ms_per_step = wall * 1e3 / steps
+    check_ms = sorted(bounds[k].elapsed_time(bounds[k + 1] if fused else mids[k]) for k in range(steps))
+    fit_ms = [0.0] if fused else sorted(mids[k].elapsed_time(bounds[k + 1]) for k in range(steps))
+    check_avg = sum(check_ms) / len(check_ms)
+    alg_bytes = w.algorithmic_bytes
+    achieved = alg_bytes / (check_avg * 1e-3) / 1e9
+
+    fields = {
+        "ms_per_step": ms_per_step,
+        "cand_elems_per_s": w.cand_elems / (wall / steps),
+        "spinup": {"min_ms": spinup_ms, "ms": spin_ms, "steps": spun},
+        "dtype": {"bf16": "bf16->f32", "f16": "f16->f32", "f64": "f64", "i32": "i32",
+                  "i64": "i64"}.get(segs[0].dtype_name, "f32"),
+        "config": {"workload": w.name, "P": P, "cand_elems": w.cand_elems,
+                   "algorithmic_bytes": alg_bytes, "T": int(w.timings.shape[1]),
+                   "atol": w.atol, "rtol": w.rtol,
+                   "entry": ("evo_evaluate_segmented" if ragged else "evo_evaluate") if fused else
+                            ("evo_check_batch" if seg_descs is None else
+                             "evo_check_cases" if is_cases else "evo_check_segmented") + "+evo_fitness"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
+                     "kernel": "evo_evaluate_kernel" if fused else "evo_check_kernel", "avg_ms": check_avg,
+                     "median_ms": check_ms[len(check_ms) // 2], "min_ms": check_ms[0]},
+        "fitness_kernel_us": None if fused else {"avg": 1e3 * sum(fit_ms) / len(fit_ms),
+                                                 "median": 1e3 * fit_ms[len(fit_ms) // 2]},
+        "hbm_gbps_whole_step": alg_bytes / (wall / steps) / 1e9,
+    }
+    return fields, w, chk, stats, summary, stream, is_cases
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -169,6 +352,8 @@ def main() -> int:
     ap.add_argument("--no-read-ceiling", action="store_true")
     ap.add_argument("--split", action="store_true",
                     help="two calls per step (check, then fitness) also where evo_evaluate applies")
+    ap.add_argument("--no-extra-workloads", action="store_true",
+                    help="with the default workload: do not measure the other large workloads afterwards")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -208,144 +393,29 @@ def main() -> int:
     import paper_2510_03760_amd as evo
     from paper_2510_03760_amd.binding import stats_to_numpy, summary_to_numpy
 
-    w = build_workload(args.workload)
-    torch.cuda.synchronize()
-    segs = w.segments
-    dcode = lambda s: {"bf16": evo.EVO_BF16, "f16": evo.EVO_F16, "f64": evo.EVO_F64,  # noqa: E731
-                       "i32": evo.EVO_I32, "i64": evo.EVO_I64}.get(s.dtype_name, evo.EVO_F32)
-    chk = evo.Checker(dcode(segs[0]), segs[0].n, w.atol, w.rtol)
+    fields, w, chk, stats, summary, stream, is_cases = measure(args.workload, args.steps, args.warmup,
+                                                               args.spinup_ms, args.split)
     P = w.P
-    stats = chk.new_stats(P)
-    summary = chk.new_summary()
-    stream = torch.cuda.current_stream()
-    seg_descs = None
-    is_cases = bool(w.notes.get("cases"))
-    if is_cases:
-        seg_descs = [{"ref": s.ref, "cand_ptrs": s.cands, "n_elems": s.n, "dtype": dcode(s)}
-                     for s in segs]
-    elif len(segs) > 1:
-        row0, seg_descs = 0, []
-        for s in segs:
-            seg_descs.append({"ref": s.ref, "cand_ptrs": s.cands, "n_elems": s.n,
-                              "dtype": dcode(s), "stats_row0": row0})
-            row0 += len(s.cands)
-
-    def check():
-        if seg_descs is None:
-            chk.check_batch(segs[0].ref, segs[0].cands, stats, stream=stream)
-        elif is_cases:
-            chk.check_cases(seg_descs, stats, stream=stream)
-        else:
-            chk.check_segmented(seg_descs, stats, P, stream=stream)
-
-    # One call (one launch) for the whole step: evo_evaluate where the population has one
-    # reference per test case, evo_evaluate_segmented for the ragged workload.
-    fused = not args.split
-    ragged = seg_descs is not None and not is_cases
-    eval_cases = seg_descs if is_cases else [{"ref": segs[0].ref, "cand_ptrs": segs[0].cands,
-                                              "n_elems": segs[0].n, "dtype": dcode(segs[0])}]
-
-    def step(mid=None):
-        if fused and ragged:
-            chk.evaluate_segmented(seg_descs, w.timings, w.baseline, stats, P, summary, stream=stream)
-        elif fused:
-            chk.evaluate(eval_cases, w.timings, w.baseline, stats, summary, stream=stream)
-        else:
-            check()
-            if mid is not None:
-                mid.record(stream)
-            chk.fitness(w.timings, w.baseline, stats, summary, stream=stream)
-
-    # Spin-up: the first tens of milliseconds of load in a process run at a varying clock (the
-    # same launch took 345-460 us over its first 60 repetitions and 345-355 us afterwards), and
-    # on a device that has been idle the first process can run at 0.6 of its later rate for
-    # longer than that.  The device is kept busy with the step for a stated time before the W
-    # warm-up steps, and beyond it (up to 2 s) until two consecutive batches of steps take the
-    # same time within 3 %.
-    # no cyclic garbage collection between here and the end of the timed region: with torch
-    # imported a full collection takes 5-20 ms, during which nothing is launched (as timeit does)
-    gc.collect()
-    gc.disable()
-    spun, per_batch = 0, 4
-    t_spin = time.perf_counter()
-    last = None
-    while args.spinup_ms > 0:
-        t_b = time.perf_counter()
-        for _ in range(per_batch):
-            step()
-        torch.cuda.synchronize()
-        now = time.perf_counter()
-        spun += per_batch
-        took = now - t_b
-        if took < 1e-3:                       # batches of at least a millisecond
-            per_batch *= 4
-            last = None
-            continue
-        elapsed_ms = (now - t_spin) * 1e3
-        settled = last is not None and abs(took - last) <= 0.03 * last
-        last = took
-        if elapsed_ms >= 2000.0 or (elapsed_ms >= args.spinup_ms and settled):
-            break
-    spin_ms = (time.perf_counter() - t_spin) * 1e3
-    # the warm-up steps record events the way the timed steps do, so that whatever the runtime
-    # sets up for the first events of a process is set up before the timed region
-    for _ in range(args.warmup):
-        torch.cuda.Event(enable_timing=True).record(stream)
-        step(None if fused else torch.cuda.Event(enable_timing=True))
-    torch.cuda.Event(enable_timing=True).record(stream)
-    torch.cuda.synchronize()
-
-    # One event between consecutive steps (plus one inside a step when it is two launches):
-    # enough to time every launch of the dominant kernel on its stream, and no more than
-    # that inside the timed region.
-    bounds = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    mids = [None if fused else torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    bounds[0].record(stream)
-    for k in range(args.steps):
-        step(mids[k])
-        bounds[k + 1].record(stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    gc.enable()
-
-    ms_per_step = wall * 1e3 / args.steps
-    check_ms = sorted(bounds[k].elapsed_time(bounds[k + 1] if fused else mids[k]) for k in range(args.steps))
-    fit_ms = [0.0] if fused else sorted(mids[k].elapsed_time(bounds[k + 1]) for k in range(args.steps))
-    check_avg = sum(check_ms) / len(check_ms)
-    alg_bytes = w.algorithmic_bytes
-    achieved = alg_bytes / (check_avg * 1e-3) / 1e9
-
     out = {
         "metric": METRIC,
-        "value": w.cand_elems / (wall / args.steps),
+        "value": fields["cand_elems_per_s"],
         "unit": "cand-elem/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "spinup": {"min_ms": args.spinup_ms, "ms": spin_ms, "steps": spun},
-        "ms_per_step": ms_per_step,
+        "spinup": fields["spinup"],
+        "ms_per_step": fields["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": {"bf16": "bf16->f32", "f16": "f16->f32", "f64": "f64", "i32": "i32",
-                  "i64": "i64"}.get(segs[0].dtype_name, "f32"),
+        "dtype": fields["dtype"],
         "data": "synthetic",
-        "config": {"workload": w.name, "P": P, "cand_elems": w.cand_elems,
-                   "algorithmic_bytes": alg_bytes, "T": int(w.timings.shape[1]),
-                   "atol": w.atol, "rtol": w.rtol,
-                   "entry": ("evo_evaluate_segmented" if ragged else "evo_evaluate") if fused else
-                            ("evo_check_batch" if seg_descs is None else
-                             "evo_check_cases" if is_cases else "evo_check_segmented") + "+evo_fitness"},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
-                     "kernel": "evo_evaluate_kernel" if fused else "evo_check_kernel", "avg_ms": check_avg,
-                     "median_ms": check_ms[len(check_ms) // 2], "min_ms": check_ms[0]},
-        "fitness_kernel_us": None if fused else {"avg": 1e3 * sum(fit_ms) / len(fit_ms),
-                                                 "median": 1e3 * fit_ms[len(fit_ms) // 2]},
-        "hbm_gbps_whole_step": alg_bytes / (wall / args.steps) / 1e9,
+        "config": fields["config"],
+        "roofline": fields["roofline"],
+        "fitness_kernel_us": fields["fitness_kernel_us"],
+        "hbm_gbps_whole_step": fields["hbm_gbps_whole_step"],
     }
+    achieved = fields["roofline"]["achieved"]
     if ceiling is not None:
         best = max(ceiling["nontemporal_GBps"], ceiling["plain_GBps"])
         out["read_ceiling"] = {"GBps": best, "plain_loads_GBps": ceiling["plain_GBps"],
@@ -374,9 +444,12 @@ def main() -> int:
                      "best_speedup": float(pop["best_speedup"]),
                      "n_mismatch_total": int(got["n_mismatch"].sum())}
 
+    host_cores = os.cpu_count() or 1
+    oracle_threads = max(1, min(16, host_cores))
     if not args.no_cpu_baseline:
         base, rows, frac = cpu_baseline(w, int(args.cpu_budget_elems))
         out["cpu_baseline"] = base
+        out["cpu_baseline"]["host_cores"] = host_cores
         if frac >= 1.0 and not is_cases:   # the sample was the whole population: report agreement too
             same = all(int(g["n_mismatch"]) == r["n_mismatch"] and
                        g["max_abs_err"].tobytes() == r["max_abs_err"].tobytes() and
@@ -384,6 +457,40 @@ def main() -> int:
                        for g, r in zip(got, rows))
             out["cpu_baseline"]["agrees_with_gpu"] = bool(same)
     chk.close()
+
+    # The other large single-GPU workloads, each after its own spin-up, with the tensors of the
+    # previous one released first: the same measurement, a compact record each.  Agreement with
+    # the oracle is checked on the whole tensors of a stated pick of candidates.
+    if args.workload == "c2" and not args.no_extra_workloads:
+        del w, chk, stats, summary, got
+        gc.collect()
+        torch.cuda.empty_cache()
+        picks = {"c3": ("every 4th candidate and the 8 with permuted rows", lambda p: p % 4 == 0 or p % 8 == 7),
+                 "c4": ("every 4th candidate of every group and every corrupted one",
+                        lambda p: p % 4 == 0 or p % 4 == 3),
+                 "c5": ("candidates 0, 2 (extra NaN sites) and 6 (Inf signs flipped)", lambda p: p in (0, 2, 6))}
+        out["workloads"] = {}
+        for name in ("c3", "c4", "c5"):
+            f2, w2, chk2, stats2, summary2, _, _ = measure(name, min(args.steps, 20), min(args.warmup, 10),
+                                                         args.spinup_ms, args.split)
+            r2 = f2["roofline"]
+            rec = {"ms_per_step": f2["ms_per_step"], "kernel_avg_ms": r2["avg_ms"], "kernel_min_ms": r2["min_ms"],
+                   "achieved": r2["achieved"], "frac": r2["frac"], "traffic": r2["traffic"],
+                   "cand_elems_per_s": f2["cand_elems_per_s"], "dtype": f2["dtype"],
+                   "entry": f2["config"]["entry"], "algorithmic_bytes": f2["config"]["algorithmic_bytes"],
+                   "steps": min(args.steps, 20)}
+            if not args.no_cpu_baseline:
+                torch.cuda.synchronize()
+                got2 = stats_to_numpy(stats2)
+                same, n_rows, secs = oracle_agreement(w2, got2, picks[name][1], oracle_threads)
+                rec["agrees_with_gpu"] = {"value": bool(same), "rows": n_rows, "sample": picks[name][0] +
+                                          ", whole tensors", "oracle_threads": oracle_threads,
+                                          "seconds": round(secs, 2)}
+            out["workloads"][f2["config"]["workload"]] = rec
+            chk2.close()
+            del w2, chk2, stats2, summary2
+            gc.collect()
+            torch.cuda.empty_cache()
     print(json.dumps(out))
     return 0
 
