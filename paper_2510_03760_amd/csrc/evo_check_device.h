@@ -645,39 +645,53 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, const uint64_t 
     lds_u64 *cptr_lds = (lds_u64 *)(uintptr_t)table_addr;
 
     const uint32_t k_end = walk.steps_below(t_fend);
+    // A single candidate leaves the pipeline above with two tiles in flight (the next
+    // tile's reference and candidate), where a group of two or more has three: its loop
+    // takes TWO tiles per iteration instead, each in registers of its own, and requests
+    // tile k + 2 of both tensors when tile k has been consumed -- three to four tiles in
+    // flight.  kTPI = 1 is the plain loop.
+    constexpr int kTPI = NC == 1 ? 2 : 1;
     if (k_end > 0) {
-        u32x4 ref_raw[kNV];
-        u32x4 buf[D][kNV];
-        {
-            const uint64_t off = walk.at(0) * kTileBytes;
+        u32x4 ref_raw[kTPI][kNV];
+        u32x4 buf[kTPI][D][kNV];
+        uint64_t tile_of[kTPI];   // the tile whose data ref_raw[u] / buf[u] hold or await
+#pragma unroll
+        for (int u = 0; u < kTPI; ++u) {
+            tile_of[u] = walk.at((uint32_t)u < k_end ? (uint32_t)u : k_end - 1u);
+            const uint64_t off = tile_of[u] * kTileBytes;
             const uint64_t voff = off + lane_off;
 #pragma unroll
-            for (int j = 0; j < kNV; ++j) ref_raw[j] = load16<REF_STREAM>(rptr + off + j * 1024, lane_off);
+            for (int j = 0; j < kNV; ++j) ref_raw[u][j] = load16<REF_STREAM>(rptr + off + j * 1024, lane_off);
 #pragma unroll
             for (int g = 0; g < D; ++g)
 #pragma unroll
-                for (int j = 0; j < kNV; ++j) buf[g][j] = load16_at<true>(cptr_lds[g] + voff + j * 1024);
+                for (int j = 0; j < kNV; ++j) buf[u][g][j] = load16_at<true>(cptr_lds[g] + voff + j * 1024);
         }
-        uint64_t t = walk.at(0);
-        for (uint32_t slot = 0; slot < k_end; ++slot) {
+        for (uint32_t slot0 = 0; slot0 < k_end; slot0 += (uint32_t)kTPI) {
+#pragma unroll
+          for (int u = 0; u < kTPI; ++u) {
+            const uint32_t slot = slot0 + (uint32_t)u;
+            if (kTPI > 1 && slot >= k_end) break;
             // Issue priority, see `second_round` in check_body: raised for two steps,
             // normal for two steps.
             if (second_round) {
                 if (slot & 2u) __builtin_amdgcn_s_setprio(1);
                 else __builtin_amdgcn_s_setprio(0);
             }
+            const uint64_t t = tile_of[u];
             const uint64_t off = t * kTileBytes;
-            // the wavefront's next tile; at the end of the job the current one again
+            // the tile these registers take next; at the end of the job the current one again
             // (a few redundant, in-bounds loads instead of a branch per load)
-            const uint64_t t_next = (slot + 1 < k_end) ? walk.at(slot + 1) : t;
+            const uint64_t t_next = (slot + (uint32_t)kTPI < k_end) ? walk.at(slot + (uint32_t)kTPI) : t;
             const uint64_t off_next = t_next * kTileBytes;
             const uint64_t voff = off + lane_off, voff_next = off_next + lane_off;   // per lane
+            tile_of[u] = t_next;
 
             float r[kE], inv[kE];
 #pragma unroll
-            for (int j = 0; j < kNV; ++j) widen<DT>(ref_raw[j], &r[j * TL::kVec]);
+            for (int j = 0; j < kNV; ++j) widen<DT>(ref_raw[u][j], &r[j * TL::kVec]);
 #pragma unroll
-            for (int j = 0; j < kNV; ++j) ref_raw[j] = load16<REF_STREAM>(rptr + off_next + j * 1024, lane_off);
+            for (int j = 0; j < kNV; ++j) ref_raw[u][j] = load16<REF_STREAM>(rptr + off_next + j * 1024, lane_off);
             // One test per reference element serves two shortcuts: below kModerate (2^102, far
             // inside the range where the reciprocal shortcut is exact) the reciprocal needs no
             // division, and a candidate tile without a single number in it can be settled on
@@ -709,16 +723,28 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, const uint64_t 
                 if (real) {
                     float c[kE];
 #pragma unroll
-                    for (int j = 0; j < kNV; ++j) widen<DT>(buf[g % D][j], &c[j * TL::kVec]);
+                    for (int j = 0; j < kNV; ++j) widen<DT>(buf[u][g % D][j], &c[j * TL::kVec]);
 #pragma unroll
                     for (int e = 0; e < kE; ++e) d[e] = c[e] - r[e];
                 }
                 // refill the slot: candidate g+D of this tile, or g+D-NC of the next
-                if (!PADDED || (uint32_t)((g + D) % NC) < n_real) {
+                if constexpr (!PADDED) {
 #pragma unroll
                     for (int j = 0; j < kNV; ++j)
-                        buf[g % D][j] = load16_at<true>(cptr_lds[(g + D) % NC] + (g + D < NC ? voff : voff_next) +
+                        buf[u][g % D][j] = load16_at<true>(cptr_lds[(g + D) % NC] + (g + D < NC ? voff : voff_next) +
                                                         j * 1024);
+                } else if (real) {
+                    // With n_real candidates the slot of the last D of them is free for the
+                    // next tile's first D candidates (candidate k uses slot k % D in every
+                    // tile): requested here, D real candidates ahead like every other load,
+                    // and not when the loop reaches the stand-ins' positions -- which left
+                    // each tile's first candidates a full memory latency away (5 candidates
+                    // ran at 0.68-0.72 of peak where 4 and 8 reach 0.79).
+                    const bool same_tile = (uint32_t)(g + D) < n_real;
+                    const uint64_t base = cptr_lds[same_tile ? (uint32_t)(g + D) : (uint32_t)(g % D)] +
+                                          (same_tile ? voff : voff_next);
+#pragma unroll
+                    for (int j = 0; j < kNV; ++j) buf[u][g % D][j] = load16_at<true>(base + j * 1024);
                 }
                 if (!real) continue;
 #pragma unroll
@@ -796,7 +822,7 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, const uint64_t 
             }
             if (lane == 0) redo[slot] = (uint16_t)redo_mask;
             any_redo |= redo_mask;
-            t = t_next;
+          }
         }
     }
 
