@@ -92,19 +92,48 @@ def _cache_key(src, extra) -> str:
     return h.hexdigest()[:24]
 
 
+RESOURCES_PATH = os.path.join(_PKG, "kernel_resources.json")   # written by build(), not tracked
+
+
+def _parse_resources(text: str) -> dict:
+    """Register, scratch and LDS use per kernel from the compiler's resource-usage remarks."""
+    import re
+    out, name = {}, None
+    for line in text.splitlines():
+        m = re.search(r"remark: Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+            out[name] = {}
+            continue
+        m = re.search(r"remark:\s+([A-Za-z ]+?)(?: \[[^\]]*\])?: (\d+)", line)
+        if m and name:
+            out[name][m.group(1).strip()] = int(m.group(2))
+    return out
+
+
 def _compile(job):
+    import json
     import shutil
     src, obj, extra, incremental = job
     cached = os.path.join(CACHE_DIR, _cache_key(src, extra) + ".o") if incremental else None
-    if cached and os.path.exists(cached):
+    if cached and os.path.exists(cached) and os.path.exists(cached + ".json"):
         shutil.copyfile(cached, obj)
+        shutil.copyfile(cached + ".json", obj + ".json")
         return 0, "(cached) " + src, ""
-    cmd = [hipcc(), *HIPCC_FLAGS, *extra, "-I", INCLUDE, "-I", CSRC, "-DEVO_BUILDING=1", "-c", "-o", obj, src]
+    cmd = [hipcc(), *HIPCC_FLAGS, *extra, "-Rpass-analysis=kernel-resource-usage", "-I", INCLUDE, "-I", CSRC,
+           "-DEVO_BUILDING=1", "-c", "-o", obj, src]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode == 0:
+        with open(obj + ".json", "w") as fh:
+            json.dump(_parse_resources(res.stdout), fh)
+        import re
+        res.stdout = "\n".join(l for l in res.stdout.splitlines() if "kernel-resource-usage" not in l
+                               and not re.match(r"^\s*(\d+\s*)?\|", l) and "In file included" not in l)
     if cached and res.returncode == 0:
         os.makedirs(CACHE_DIR, exist_ok=True)
-        shutil.copyfile(obj, cached + ".tmp.%d" % os.getpid())
-        os.replace(cached + ".tmp.%d" % os.getpid(), cached)
+        for suffix in ("", ".json"):
+            shutil.copyfile(obj + suffix, cached + suffix + ".tmp.%d" % os.getpid())
+            os.replace(cached + suffix + ".tmp.%d" % os.getpid(), cached + suffix)
     # the host pass warns that it does not know the packed-fp32 feature: harmless
     out = "\n".join(l for l in res.stdout.splitlines()
                     if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)
@@ -140,6 +169,15 @@ def build(verbose: bool = False, extra_flags=(), jobs: int = 0, incremental: boo
         if res.returncode != 0:
             raise RuntimeError("link failed:\n" + res.stdout)
         os.replace(tmp, LIB_PATH)
+        # what every kernel of the library uses, for tests/test_kernel_resources.py
+        import json
+        table = {}
+        for t in todo:
+            with open(t[1] + ".json") as fh:
+                table.update(json.load(fh))
+        with open(RESOURCES_PATH + ".tmp.%d" % os.getpid(), "w") as fh:
+            json.dump(table, fh, indent=1, sort_keys=True)
+        os.replace(RESOURCES_PATH + ".tmp.%d" % os.getpid(), RESOURCES_PATH)
     finally:
         shutil.rmtree(work, ignore_errors=True)
     if not extra_flags:

@@ -44,6 +44,7 @@ constexpr float kFltMin = 1.17549435e-38f;
 constexpr double kInfD = __builtin_huge_val();
 constexpr double kDblMin = 2.2250738585072014e-308;
 constexpr float kModerate = 0x1p102f;   // see fast_tiles
+constexpr double kModerateD = 0x1p969;   // the binary64 counterpart, see fast_tiles_wide
 static_assert(kModerate <= kRecipShortcutBelow, "the reciprocal shortcut must be exact below kModerate");
 constexpr int kDepth = EVO_DEPTH;
 constexpr uint32_t kRotate = EVO_ROTATE;   // slot rotation per step (odd)
@@ -142,13 +143,15 @@ struct ExactAcc {
 
 // Wavefront-wide reductions with data-parallel-primitive (DPP) moves: four shifts inside
 // each row of 16 lanes (a running combination ends up in the row's last lane), then the
-// last lane of rows 0 and 2 is broadcast into rows 1 and 3, then that of row 1 into rows
-// 2 and 3, so that lane 63 holds the combination of all 64 lanes.  Lanes without a source
-// lane receive 0, the neutral element of both uses below.  No LDS traffic, one vector
-// instruction per step and 32-bit word; the order of the additions is fixed.
+// last lane of every row is broadcast into the next row, then lane 31 into rows 2 and 3, so
+// that lane 63 holds the combination of all 64 lanes in a fixed order (the other lanes hold
+// partial combinations that nobody reads).  Lanes without a source lane receive 0, the
+// neutral element of both uses below (bound_ctrl; every row enabled, so no lane keeps an
+// old value and none has to be prepared: that cost one move per step and word before).
+// No LDS traffic, one vector instruction per step and 32-bit word.
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ uint32_t dpp_word(uint32_t v) {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
 }
 constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0x118;
 constexpr int kRowBcast15 = 0x142, kRowBcast31 = 0x143;
@@ -479,7 +482,10 @@ struct TileWalk {
     }
     // number of steps k = 0, 1, ... whose tile lies below `limit`
     __device__ __forceinline__ uint32_t steps_below(uint64_t limit) const {
-        const uint32_t full = (uint32_t)(limit / window());
+        // (a 64-bit division is a few hundred instructions; both operands almost always fit
+        // 32 bits, and this is on every job's path before its first load and after its last)
+        const uint64_t w = window();
+        const uint32_t full = ((limit | w) >> 32) == 0 ? (uint32_t)limit / (uint32_t)w : (uint32_t)(limit / w);
         return full + (at(full) < limit ? 1u : 0u);
     }
 };
@@ -640,8 +646,8 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, const uint64_t 
     // The table's LDS address is kept in a vector register (LDS reads take their address
     // from one; as a wave-uniform value it would be moved there before every read).
     typedef __attribute__((address_space(3))) const uint64_t lds_u64;
-    uint32_t table_addr = (uint32_t)(uintptr_t)(lds_u64 *)cptr_lds_generic;
-    asm volatile("" : "+v"(table_addr));
+    // (plus a per-lane zero that the compiler does not see through: 0 lanes counted below each)
+    const uint32_t table_addr = (uint32_t)(uintptr_t)(lds_u64 *)cptr_lds_generic + __builtin_amdgcn_mbcnt_lo(0u, 0u);
     lds_u64 *cptr_lds = (lds_u64 *)(uintptr_t)table_addr;
 
     const uint32_t k_end = walk.steps_below(t_fend);
@@ -680,9 +686,11 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, const uint64_t 
             }
             const uint64_t t = tile_of[u];
             const uint64_t off = t * kTileBytes;
-            // the tile these registers take next; at the end of the job the current one again
-            // (a few redundant, in-bounds loads instead of a branch per load)
-            const uint64_t t_next = (slot + (uint32_t)kTPI < k_end) ? walk.at(slot + (uint32_t)kTPI) : t;
+            // the tile these registers take next; at the end of the job tile 0 (a few redundant,
+            // in-bounds loads instead of a branch per load: tile 0 of every tensor is what all
+            // wavefronts ask for at their end, so it comes from a cache -- the registers are
+            // reused right after the loop and must wait for these loads)
+            const uint64_t t_next = (slot + (uint32_t)kTPI < k_end) ? walk.at(slot + (uint32_t)kTPI) : 0;
             const uint64_t off_next = t_next * kTileBytes;
             const uint64_t voff = off + lane_off, voff_next = off_next + lane_off;   // per lane
             tile_of[u] = t_next;
@@ -886,7 +894,7 @@ __device__ __forceinline__ uint32_t fast_tiles_wide(const char *rptr, uint64_t c
                                                     const TileWalk walk, uint64_t t_fend,
                                                     float atol, float rtol, int lane,
                                                     bool second_round, uint32_t n_real,
-                                                    uint16_t *redo, Partial *wpart, ExactAcc * /*xacc*/) {
+                                                    uint16_t *redo, Partial *wpart, ExactAcc *xacc) {
     using TL = Tile<DT>;
     constexpr bool kInt = kIsInt<DT>;
     constexpr int kE = TL::kE;
@@ -937,17 +945,21 @@ __device__ __forceinline__ uint32_t fast_tiles_wide(const char *rptr, uint64_t c
 #pragma unroll
             for (int j = 0; j < kNV; ++j) ref_raw[j] = load16<REF_STREAM>(rptr + off_next + j * 1024, lane_off);
             double r[kInt ? 1 : kE], inv[kInt ? 1 : kE];
+            bool moderate_tile = false;   // every |r| of the tile below kModerateD (and none NaN)
             if constexpr (!kInt) {
 #pragma unroll
                 for (int j = 0; j < kNV; ++j) {
                     r[2 * j] = __builtin_bit_cast(double, u64_of(rw[j].x, rw[j].y));
                     r[2 * j + 1] = __builtin_bit_cast(double, u64_of(rw[j].z, rw[j].w));
                 }
+                bool huge = false;
 #pragma unroll
                 for (int e = 0; e < kE; ++e) {
                     const double ar = __builtin_fabs(r[e]);
                     inv[e] = ar >= kDblMin ? 1.0 / ar : 0.0;
+                    huge = huge || !(ar < kModerateD);
                 }
+                moderate_tile = ballot(huge) == 0;
             }
 
             uint32_t redo_mask = 0;
@@ -1000,7 +1012,30 @@ __device__ __forceinline__ uint32_t fast_tiles_wide(const char *rptr, uint64_t c
                         acc[g].sum_rel += sr;
                         n_mismatch[g] += mism;
                     } else {
-                        redo_mask |= 1u << g;
+                        // As in fast_tiles: a candidate tile without a single number in it, NaN
+                        // or +-Inf throughout, over a moderate reference tile (below 2^969 a
+                        // finite candidate element cannot carry the difference past the largest
+                        // binary64 number: that is a quarter of its last place) is settled on
+                        // the spot -- every element mismatches and is excluded.
+                        uint64_t number = 0, any_nan = 0, any_inf = 0;
+#pragma unroll
+                        for (int e = 0; e < kE; ++e) {
+                            const uint64_t is_nan = ballot(d[e] != d[e]);
+                            const uint64_t is_inf = ballot(__builtin_fabs(d[e]) == kInfD);
+                            any_nan |= is_nan;
+                            any_inf |= is_inf;
+                            number |= ~(is_nan | is_inf);
+                        }
+                        if (moderate_tile && number == 0) {
+                            n_mismatch[g] += (uint32_t)tile_elems(DT);
+                            if (lane == 0) {
+                                xacc[g].n_excluded += (uint32_t)tile_elems(DT);
+                                xacc[g].flags |= (any_nan ? EVO_F_CAND_NAN | EVO_F_NAN_SITE_DIFF : 0u) |
+                                                 (any_inf ? EVO_F_CAND_INF | EVO_F_INF_DIFF : 0u);
+                            }
+                        } else {
+                            redo_mask |= 1u << g;
+                        }
                     }
                 } else if constexpr (DT == EVO_I32) {
                     const uint32_t rr[kE] = {rw[0].x, rw[0].y, rw[0].z, rw[0].w, rw[1].x, rw[1].y, rw[1].z, rw[1].w};
@@ -1313,6 +1348,10 @@ __device__ __forceinline__ void run_job(const SegDesc &sd, const uint64_t *ptr_t
 // geometry only, so the sums are reproducible; and no workgroup ever has to read more
 // than a few dozen rows per candidate after the last tile has been streamed.
 constexpr uint32_t kFold = 16;
+#ifndef EVO_ONE_LEVEL_ROWS
+#define EVO_ONE_LEVEL_ROWS 8
+#endif
+constexpr uint32_t kOneLevelRows = EVO_ONE_LEVEL_ROWS;   // see check_body
 
 __device__ __forceinline__ void add_row(Partial &a, const uint64_t (&w)[6]) {
     a.n_mismatch += w[0];
@@ -1567,25 +1606,46 @@ __device__ __forceinline__ bool check_body(const SegDesc *descs, const uint64_t 
         }
         return true;
     }
-    if (threadIdx.x == 0) {
-        const uint32_t prev = __hip_atomic_fetch_add(&tickets[bundle], 1u, __ATOMIC_ACQ_REL,
-                                                     __HIP_MEMORY_SCOPE_AGENT);
-        is_last = (prev == count - 1) ? 1u : 0u;
-    }
-    __syncthreads();
-    if (!is_last) return false;
-    fold_bundle(sd, gblock, first, count, partials, rows1 + (uint64_t)bundle * kRowsPerJob, fold);
-    if (threadIdx.x == 0) {
-        __hip_atomic_store(&tickets[bundle], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const uint32_t n_bundles = units * ((sd.n_groups + sd.gpw - 1) / sd.gpw);
-        const uint32_t prev = __hip_atomic_fetch_add(&seg_tickets[s], 1u, __ATOMIC_ACQ_REL,
-                                                     __HIP_MEMORY_SCOPE_AGENT);
-        is_last = (prev == n_bundles - 1) ? 1u : 0u;
-    }
-    __syncthreads();
-    if (!is_last) return false;
     Partial *case_rows = rows1 + (uint64_t)total_jobs * kRowsPerJob;
-    finalize_segment(sd, rows1, units, stats, case_rows, fold);
+    // A segment whose jobs' rows one workgroup can add in a few batches per thread (at most
+    // kOneLevelRows per thread in finalize_segment's layout, i.e. one batch of loads: up to 128
+    // jobs of 16 candidates, 512 of 4, any number of a single one) skips the first level: every job takes the segment's ticket, and the last one
+    // adds the jobs' rows directly, in job order.  That is one ticket round trip and one fold
+    // less on the path that nothing overlaps (2-3 us of a 25-45 us launch).  With more rows per
+    // thread the single fold takes longer than the two levels it replaces (measured with 32:
+    // the ragged eight-shape mix 0.71 -> 0.72 ms, 2^23 x 16 114 -> 117 us).
+    uint32_t pc = 1;
+    while (pc < sd.P && pc < (uint32_t)kThreads) pc <<= 1;
+    const bool one_level = (uint64_t)sd.n_chunks * pc <= (uint64_t)kOneLevelRows * kThreads;
+    if (one_level) {
+        if (threadIdx.x == 0) {
+            const uint32_t prev = __hip_atomic_fetch_add(&seg_tickets[s], 1u, __ATOMIC_ACQ_REL,
+                                                         __HIP_MEMORY_SCOPE_AGENT);
+            is_last = (prev == sd.n_jobs - 1) ? 1u : 0u;
+        }
+        __syncthreads();
+        if (!is_last) return false;
+        finalize_segment(sd, partials, sd.n_chunks, stats, case_rows, fold);
+    } else {
+        if (threadIdx.x == 0) {
+            const uint32_t prev = __hip_atomic_fetch_add(&tickets[bundle], 1u, __ATOMIC_ACQ_REL,
+                                                         __HIP_MEMORY_SCOPE_AGENT);
+            is_last = (prev == count - 1) ? 1u : 0u;
+        }
+        __syncthreads();
+        if (!is_last) return false;
+        fold_bundle(sd, gblock, first, count, partials, rows1 + (uint64_t)bundle * kRowsPerJob, fold);
+        if (threadIdx.x == 0) {
+            __hip_atomic_store(&tickets[bundle], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint32_t n_bundles = units * ((sd.n_groups + sd.gpw - 1) / sd.gpw);
+            const uint32_t prev = __hip_atomic_fetch_add(&seg_tickets[s], 1u, __ATOMIC_ACQ_REL,
+                                                         __HIP_MEMORY_SCOPE_AGENT);
+            is_last = (prev == n_bundles - 1) ? 1u : 0u;
+        }
+        __syncthreads();
+        if (!is_last) return false;
+        finalize_segment(sd, rows1, units, stats, case_rows, fold);
+    }
     if (threadIdx.x == 0)
         __hip_atomic_store(&seg_tickets[s], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (sd.n_cases <= 1) return true;

@@ -84,7 +84,7 @@ def test_degenerate_candidates_are_invalid(gu, dtype):
     chk.close()
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16],
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16, torch.float64],
                          ids=lambda d: str(d).split(".")[-1])
 def test_nan_filled_tiles_next_to_everything_else(gu, dtype):
     """Tiles that are NaN throughout are settled in the fast path by a closed form that only
@@ -116,6 +116,47 @@ def test_nan_filled_tiles_next_to_everything_else(gu, dtype):
                        torch.ones(4, device="cuda"))
     chk, stats, want = gu.check_parity(w, label="nan tiles %s" % dtype)
     assert want[0]["n_mismatch"] == n and want[0]["n_finite"] == 0
+    chk.close()
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float64],
+                         ids=lambda d: str(d).split(".")[-1])
+def test_no_number_shortcut_stops_where_a_difference_can_overflow(gu, dtype):
+    """A candidate tile whose differences are all NaN or Inf is settled without looking further
+    only over reference elements small enough that a FINITE candidate element cannot overflow
+    the difference (below 2^102 in binary32, 2^969 in binary64).  Here one difference per tile
+    is infinite although both sides are finite: that element belongs to the statistics
+    (n_finite, max and sum of the errors become Inf) and the shortcut must not take the tile.
+    Beside it: the same tiles over a reference just below the bound, where the element's
+    difference stays finite."""
+    _say("overflowing difference in a NaN tile %s" % dtype)
+    n = 12 * 4096 + 77
+    big = {torch.float32: 2.0 ** 120, torch.bfloat16: 2.0 ** 120, torch.float64: 2.0 ** 970}[dtype]
+    below = {torch.float32: 2.0 ** 101, torch.bfloat16: 2.0 ** 101, torch.float64: 2.0 ** 968}[dtype]
+    lowest = torch.finfo(dtype).min
+    g = torch.Generator(device="cuda")
+    g.manual_seed(8)
+    cands = []
+    ref = (torch.randn(n, generator=g, device="cuda", dtype=torch.float64) + 2).to(dtype)
+    sites = torch.arange(100, n, 1000, device="cuda")
+    ref[sites[0::2]] = big                      # these can overflow against a finite candidate
+    ref[sites[1::2]] = below                    # these cannot
+    c = torch.full_like(ref, float("nan"))
+    c[sites] = lowest                           # finite: |c - r| = Inf over `big`, finite over `below`
+    cands.append(c)
+    c = torch.full_like(ref, float("inf"))
+    c[sites] = lowest
+    cands.append(c)
+    cands.append(torch.full_like(ref, float("nan")))
+    cands.append(ref.clone())
+    P = len(cands)
+    seg = synth.Segment(ref.contiguous(), [x.contiguous() for x in cands], (n,), [True] * P)
+    w = synth.Workload("overflow-tiles", [seg], 1e-2, 1e-2, torch.ones(P, 4, device="cuda"),
+                       torch.ones(4, device="cuda"))
+    chk, stats, want = gu.check_parity(w, label="overflow tiles %s" % dtype)
+    assert want[0]["n_finite"] == sites.numel() and want[0]["n_mismatch"] == n
+    assert np.isinf(want[0]["max_abs_err"]) and np.isinf(want[0]["sum_abs_err"])
+    assert want[2]["n_finite"] == 0 and want[3]["valid"] == 1
     chk.close()
 
 
