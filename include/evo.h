@@ -89,8 +89,10 @@ typedef enum {
     EVO_ERR_NOMEM  = -7, /* host or device allocation failed                    */
     EVO_ERR_HANDLE = -8, /* not a live context (never created, or destroyed)    */
     EVO_ERR_LIMIT  = -9, /* beyond the fixed capacity of evo_check_batch_static */
-    EVO_ERR_CAPTURE = -10 /* the stream is capturing and the call would have to allocate, */
+    EVO_ERR_CAPTURE = -10, /* the stream is capturing and the call would have to allocate, */
                          /* free, clear or stage (see "Graph capture" above)             */
+    EVO_ERR_INTERNAL = -11 /* evo_check_destroy: a guard behind the library's scratch      */
+                         /* memory was overwritten (a defect of the library, not a usage error) */
 } evo_status;
 
 /* Bits of evo_stats.flags */
@@ -394,9 +396,11 @@ EVO_API int evo_time_candidates(evo_check_t *c, const evo_launch_fn *launch, voi
                                 void *stream, float *timings, float *clock_ratio);
 
 /*
- * Destroys a context: waits for the device to go idle, frees the library's scratch
- * memory.  NULL, unknown and already destroyed handles are ignored
- * (evo_check_destroy returns EVO_ERR_HANDLE for them and does nothing else).
+ * Destroys a context: waits for the device to go idle, checks the guard bytes behind the
+ * scratch buffers its kernels wrote (EVO_ERR_INTERNAL if one was overwritten; the context is
+ * destroyed all the same) and frees the library's scratch memory.  NULL, unknown and
+ * already destroyed handles are ignored (evo_check_destroy returns EVO_ERR_HANDLE for them
+ * and does nothing else).
  */
 EVO_API int evo_check_destroy(evo_check_t *c);
 

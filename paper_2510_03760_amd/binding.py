@@ -83,12 +83,16 @@ assert STATS_DTYPE.itemsize == ctypes.sizeof(EvoStats) == 72
 assert SUMMARY_DTYPE.itemsize == ctypes.sizeof(EvoPopSummary) == 16
 
 
-def _load() -> ctypes.CDLL:
-    if not os.path.exists(lib_path):
+def load_library(path: str = None) -> ctypes.CDLL:
+    """The C ABI of the library at `path` (default: the package's libevo.so) with its argument
+    types declared.  The package itself binds the default; tests use this for other builds of
+    the same sources."""
+    path = path or lib_path
+    if not os.path.exists(path):
         raise ImportError(
-            "%s is missing: build it with `python -m paper_2510_03760_amd.build` "
-            "(there is no fallback implementation)" % lib_path)
-    h = ctypes.CDLL(lib_path)
+            "%s is missing: build it with `python paper_2510_03760_amd/build.py` "
+            "(there is no fallback implementation)" % path)
+    h = ctypes.CDLL(path)
     vp, u32, u64, f32 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_float
     h.evo_check_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, u64, f32, f32]
     h.evo_check_set_tolerance.argtypes = [vp, ctypes.c_int, f32, f32]
@@ -116,7 +120,7 @@ def _load() -> ctypes.CDLL:
     return h
 
 
-lib = _load()
+lib = load_library()
 
 
 def evo_strerror(code: int) -> str:
@@ -296,8 +300,10 @@ class Checker:
 
     def close(self) -> None:
         if self.ctx:
-            evo_check_destroy(self.ctx)
-            self.ctx = None
+            ctx, self.ctx = self.ctx, None
+            rc = evo_check_destroy(ctx)
+            if rc != 0:
+                raise EvoError(rc, "evo_check_destroy")
 
     def __enter__(self):
         return self

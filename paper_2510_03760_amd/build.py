@@ -10,6 +10,11 @@ _ROOT = os.path.dirname(_PKG)
 CSRC = os.path.join(_PKG, "csrc")
 INCLUDE = os.path.join(_ROOT, "include")
 LIB_PATH = os.path.join(_PKG, "libevo.so")
+# The same library with three workgroups per compute unit instead of two (host code only: the
+# kernels are the same objects): the parity tests run on it as well, since no result may depend
+# on how a launch is cut into jobs.
+GRID_VARIANT_PATH = os.path.join(_PKG, "libevo_grid3.so")
+GRID_VARIANT_FLAGS = ["-DEVO_JOBS_PER_CU=3"]
 
 SOURCES = ["evo_api.hip", "evo_check_dispatch.hip", "evo_fitness_kernel.hip", "evo_select_kernel.hip",
            "evo_timing_kernel.hip"]
@@ -72,7 +77,7 @@ def build_read_ceiling() -> str:
 
 
 def is_stale() -> bool:
-    if not os.path.exists(LIB_PATH):
+    if not os.path.exists(LIB_PATH) or not os.path.exists(GRID_VARIANT_PATH):
         return True
     built = os.path.getmtime(LIB_PATH)
     deps = sources() + [os.path.join(CSRC, CHECK_INST)] + [os.path.join(CSRC, h) for h in HEADERS] + [
@@ -169,6 +174,19 @@ def build(verbose: bool = False, extra_flags=(), jobs: int = 0, incremental: boo
         if res.returncode != 0:
             raise RuntimeError("link failed:\n" + res.stdout)
         os.replace(tmp, LIB_PATH)
+        if not extra_flags:
+            api_src = os.path.join(CSRC, "evo_api.hip")
+            api_obj = os.path.join(work, "evo_api_grid.o")
+            rc, cmd, out = _compile((api_src, api_obj, GRID_VARIANT_FLAGS, incremental))
+            if rc != 0:
+                raise RuntimeError("hipcc failed:\n" + cmd + "\n" + out)
+            objs = [api_obj if t[0] == api_src else t[1] for t in todo]
+            tmp = GRID_VARIANT_PATH + ".tmp.%d" % os.getpid()
+            res = subprocess.run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs,
+                                 stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+            if res.returncode != 0:
+                raise RuntimeError("link failed:\n" + res.stdout)
+            os.replace(tmp, GRID_VARIANT_PATH)
         # what every kernel of the library uses, for tests/test_kernel_resources.py
         import json
         table = {}

@@ -28,6 +28,10 @@ constexpr uint32_t kJobsPerCu = EVO_JOBS_PER_CU;
 constexpr uint32_t kMinTilesPerWave = 4;
 constexpr uint32_t kMaxP = 65535;
 constexpr int kStageSlots = 8;
+// Every scratch buffer the kernels write ends in a guard of this many bytes holding
+// kGuardByte; evo_check_destroy checks that they still do.
+constexpr size_t kGuardBytes = 256;
+constexpr int kGuardByte = 0xC5;
 constexpr size_t kFlushBytes = 512u << 20;      // twice the last-level cache of MI355X
 constexpr uint32_t kProbeIterations = 20000;    // about 35 us at 2.4 GHz
 constexpr int kProbeSpinUp = 100;
@@ -176,7 +180,10 @@ int ensure_partials(evo_check *c, size_t rows, hipStream_t stream) {
     if (c->d_partials) EVO_TRY(hipFree(c->d_partials));
     c->d_partials = nullptr;
     c->partial_rows = 0;
-    EVO_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_partials), rows * sizeof(Partial)));
+    EVO_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_partials), rows * sizeof(Partial) + kGuardBytes));
+    EVO_TRY(hipMemsetAsync(reinterpret_cast<char *>(c->d_partials) + rows * sizeof(Partial), kGuardByte,
+                           kGuardBytes, stream));
+    EVO_TRY(hipStreamSynchronize(stream));
     c->partial_rows = rows;
     return EVO_OK;
 }
@@ -188,9 +195,10 @@ int ensure_tickets(evo_check *c, size_t n, hipStream_t stream) {
     c->d_tickets = nullptr;
     c->n_tickets = 0;
     const size_t cap = std::max<size_t>(n * 2, 64);
-    EVO_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_tickets), cap * sizeof(uint32_t)));
+    EVO_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_tickets), cap * sizeof(uint32_t) + kGuardBytes));
     // counters start at zero and every launch leaves them at zero again
     EVO_TRY(hipMemsetAsync(c->d_tickets, 0, cap * sizeof(uint32_t), stream));
+    EVO_TRY(hipMemsetAsync(c->d_tickets + cap, kGuardByte, kGuardBytes, stream));
     EVO_TRY(hipStreamSynchronize(stream));
     c->n_tickets = cap;
     return EVO_OK;
@@ -215,7 +223,9 @@ int ensure_fit_rows(evo_check *c, size_t P, hipStream_t stream) {
     c->d_fit_rows = nullptr;
     c->fit_rows_count = 0;
     const size_t cap = std::max<size_t>(2 * P, 256);
-    EVO_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_fit_rows), cap * 2 * sizeof(float)));
+    EVO_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_fit_rows), cap * 2 * sizeof(float) + kGuardBytes));
+    EVO_TRY(hipMemsetAsync(c->d_fit_rows + cap * 2, kGuardByte, kGuardBytes, stream));
+    EVO_TRY(hipStreamSynchronize(stream));
     c->fit_rows_count = cap;
     return EVO_OK;
 }
@@ -929,6 +939,21 @@ int evo_check_destroy(evo_check_t *c) {
         int cur = -1;
         if (hipGetDevice(&cur) == hipSuccess && cur != c->device) (void)hipSetDevice(c->device);
         if (hipDeviceSynchronize() != hipSuccess) rc = EVO_ERR_DEVICE;
+        // the guards behind the buffers the kernels write must be untouched
+        const void *guards[3] = {
+            c->d_partials ? reinterpret_cast<const char *>(c->d_partials) + c->partial_rows * sizeof(Partial) : nullptr,
+            c->d_tickets ? reinterpret_cast<const char *>(c->d_tickets + c->n_tickets) : nullptr,
+            c->d_fit_rows ? reinterpret_cast<const char *>(c->d_fit_rows + c->fit_rows_count * 2) : nullptr};
+        for (const void *g : guards) {
+            unsigned char host[kGuardBytes];
+            if (!g || rc != EVO_OK) continue;
+            if (hipMemcpy(host, g, kGuardBytes, hipMemcpyDeviceToHost) != hipSuccess) {
+                rc = EVO_ERR_DEVICE;
+                continue;
+            }
+            for (size_t i = 0; i < kGuardBytes; ++i)
+                if (host[i] != kGuardByte) rc = EVO_ERR_INTERNAL;
+        }
         if (c->d_table) (void)hipFree(c->d_table);
         if (c->d_partials) (void)hipFree(c->d_partials);
         if (c->d_tickets) (void)hipFree(c->d_tickets);
@@ -961,6 +986,7 @@ const char *evo_strerror(int code) {
         case EVO_ERR_NOMEM: return "out of memory";
         case EVO_ERR_HANDLE: return "not a live context";
         case EVO_ERR_LIMIT: return "beyond the fixed capacity of the call that allocates nothing";
+        case EVO_ERR_INTERNAL: return "a guard behind the library's scratch memory was overwritten";
         case EVO_ERR_CAPTURE: return "the stream is capturing and the call would have to allocate, clear or stage";
         default: return "unknown status";
     }
