@@ -1415,7 +1415,7 @@ __device__ __forceinline__ void fold_bundle(const SegDesc &sd, uint32_t gblock, 
 // unit are neighbours in memory, so a wavefront's load touches a contiguous run of rows
 // instead of 64 different cache lines: the level took 7 us before, with a candidate's R
 // ranges side by side), and thread group k of the R groups takes the k-th range of the
-// candidate's `units` second-level rows; the R results are then added in range order.
+// candidate's `units` second-level rows; the R results are then added by a fixed tree.
 // A segment that stands alone writes its evo_stats rows; one that is a case of a case
 // group leaves one row per candidate in case_rows for write_case_group.
 __device__ __forceinline__ void write_stats(evo_stats *dst, const Partial &a, uint64_t n_elems) {
@@ -1474,8 +1474,17 @@ __device__ __forceinline__ void finalize_segment(const SegDesc &sd, const Partia
         }
         fold[threadIdx.x] = a;
         __syncthreads();
+        // The R ranges of a candidate are added pairwise (range k with range k + stride, a fixed
+        // tree): one thread adding them one after the other took 4 us per segment with few
+        // candidates, where R is 64 to 256.
+        for (uint32_t stride = R >> 1; stride >= 1; stride >>= 1) {
+            if (ri < stride) {
+                add_partial(a, fold[threadIdx.x + stride * pc]);
+                fold[threadIdx.x] = a;
+            }
+            __syncthreads();
+        }
         if (ri == 0 && p < sd.P - sd.n_pad) {
-            for (uint32_t k = 1; k < R; ++k) add_partial(a, fold[threadIdx.x + k * pc]);
             if (sd.n_cases <= 1) {
                 write_stats(&stats[sd.stats_row0 + p], a, sd.n);
             } else {
