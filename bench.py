@@ -8,6 +8,7 @@ before the timed region starts.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--spinup-ms MS] [--workload c2|c1|c3|c3h|c4|c5|cases|f64|i32|i64]
                     [--no-cpu-baseline] [--no-read-ceiling] [--copy-calibration] [--no-extra-workloads]
+                    [--sweep populations|small|cases]
 
 The JSON line is about --workload (default c2, the configuration the metric is quoted on).  With
 the default workload it also carries "workloads": the same measurement of the other large
@@ -197,6 +198,67 @@ def oracle_agreement(w, got, cand_pick, threads: int, chunk: int = 1 << 24):
     return same, n_rows, time.perf_counter() - t0
 
 
+def sweep(mode: str, steps: int) -> int:
+    """Other shapes than the five workloads, evo_check_batch / evo_check_cases alone (no timing
+    reduction), one JSON line per shape: median time between HIP events around each call and the
+    algorithmic bytes over it as a fraction of the HBM peak.
+      populations  P = 1..33 candidates at 2.4-4.6 GB per launch, fp32 and bf16
+      small        fp32 launches of 8 MB to 1.1 GB
+      cases        K = 5 test cases of P = 1..8 candidates (the shape of one evaluation in the
+                   paper's loop), fp32, 2^20 / 2^24 / 2^26 elements per tensor"""
+    import torch
+    import paper_2510_03760_amd as evo
+
+    def run(dt, n, P, K=1):
+        tdt = {"f32": torch.float32, "bf16": torch.bfloat16}[dt]
+        code = {"f32": evo.EVO_F32, "bf16": evo.EVO_BF16}[dt]
+        g = torch.Generator(device="cuda")
+        g.manual_seed(1)
+        refs = [torch.rand(n, device="cuda", generator=g).to(tdt) for _ in range(K)]
+        cands = [[(r.float() * 1.0001).to(tdt) for _ in range(P)] for r in refs]
+        chk = evo.Checker(code, n, 1e-2, 1e-2)
+        stats = chk.new_stats(P)
+        cases = [{"ref": r, "cand_ptrs": c, "n_elems": n, "dtype": code} for r, c in zip(refs, cands)]
+        call = ((lambda: chk.check_batch(refs[0], cands[0], stats)) if K == 1 else
+                (lambda: chk.check_cases(cases, stats)))
+        for _ in range(25):
+            call()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        ev[0].record()
+        for i in range(steps):
+            call()
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        ms = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
+        med = ms[len(ms) // 2]
+        byt = K * (P + 1) * n * refs[0].element_size()
+        print(json.dumps({"sweep": mode, "dtype": dt, "n_elems": n, "P": P, "K": K, "algorithmic_bytes": byt,
+                          "median_us": round(med * 1e3, 1), "GBps": round(byt / med / 1e6, 0),
+                          "frac_of_peak": round(byt / med / 1e6 / HBM_PEAK_GBS, 3),
+                          "entry": "evo_check_batch" if K == 1 else "evo_check_cases"}), flush=True)
+        chk.close()
+
+    if mode == "populations":
+        for dt, es in (("f32", 4), ("bf16", 2)):
+            for P in (1, 2, 3, 4, 5, 7, 8, 9, 11, 12, 13, 15, 16, 17, 24, 33):
+                n = (1 << 29) if dt == "f32" else (1 << 30)
+                while (P + 1) * n * es > 4.7e9:
+                    n >>= 1
+                run(dt, n, P)
+    elif mode == "small":
+        for P, lg in ((1, 20), (1, 22), (1, 24), (4, 22), (16, 20), (16, 21), (16, 22), (16, 23), (16, 24), (64, 20)):
+            run("f32", 1 << lg, P)
+    elif mode == "cases":
+        for P in (1, 2, 4, 8):
+            for lg in (20, 24, 26):
+                run("f32", 1 << lg, P, K=5)
+    else:
+        print("bench.py: unknown sweep %r (populations, small, cases)" % mode, file=sys.stderr)
+        return 2
+    return 0
+
+
 def measure(name: str, steps: int, warmup: int, spinup_ms: float, split: bool):
     """Builds workload `name`, spins the device up, runs `warmup` untimed and `steps` timed steps
     and returns (result fields, workload, checker, stats, summary).  One event per launch
@@ -352,6 +414,7 @@ def main() -> int:
     ap.add_argument("--no-read-ceiling", action="store_true")
     ap.add_argument("--split", action="store_true",
                     help="two calls per step (check, then fitness) also where evo_evaluate applies")
+    ap.add_argument("--sweep", default=None, help="populations | small | cases: other shapes, one JSON line each")
     ap.add_argument("--no-extra-workloads", action="store_true",
                     help="with the default workload: do not measure the other large workloads afterwards")
     args = ap.parse_args()
@@ -364,13 +427,16 @@ def main() -> int:
         return 2
 
     # child process, finished before this process touches the GPU
-    ceiling = None if (args.no_read_ceiling or args.copy_calibration) else read_ceiling()
+    ceiling = None if (args.no_read_ceiling or args.copy_calibration or args.sweep) else read_ceiling()
 
     import torch
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
     torch.cuda.set_device(0)
+
+    if args.sweep:
+        return sweep(args.sweep, min(args.steps, 40))
 
     if args.copy_calibration:
         n = 1 << 30   # bytes

@@ -616,7 +616,7 @@ __device__ __forceinline__ void exact_candidate_pass(const char *rptr, const cha
 // too.  Candidates of a tile that the fast path must not settle (anything non-finite,
 // overflow) are recorded in redo[tile slot] for the exact path -- except a candidate tile
 // that is NaN or Inf throughout over a moderate reference tile, whose share is added on the spot
-// (counts in registers, exclusions and flags in xacc).  Ends with the lanes -> wavefront
+// (counts, exclusions and flags in xacc).  Ends with the lanes -> wavefront
 // reduction into wpart[0 .. NC).
 template <uint32_t DT, int NC, bool REF_STREAM, bool PADDED>
 __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, const uint64_t *cptr_lds_generic,
