@@ -1140,6 +1140,8 @@ __device__ __forceinline__ uint32_t fast_tiles_wide(const char *rptr, uint64_t c
     return any_redo;
 }
 
+__device__ __forceinline__ void write_stats(evo_stats *dst, const Partial &a, uint64_t n_elems);
+
 // One job: a chunk of tiles of one segment for up to kWaves candidate groups.
 // SKIP: instantiate the fast path a second time for groups that end in stand-ins, without
 // their loads and arithmetic (off in the all-types kernel, where the stand-ins are loaded --
@@ -1150,7 +1152,7 @@ __device__ __forceinline__ void run_job(const SegDesc &sd, const uint64_t *ptr_t
                         uint32_t job_global, float atol, float rtol, bool second_round,
                         Partial *partials, ExactAcc (*exact_acc)[kG],
                         Partial (*wave_part)[kG], uint16_t (*redo)[kMaxTilesPerWave],
-                        uint64_t (*cand_lds)[kG]) {
+                        uint64_t (*cand_lds)[kG], evo_stats *stats) {
     constexpr uint32_t kTileElems = tile_elems(DT);
     const int lane = (int)(threadIdx.x & (kLanes - 1));
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -1334,8 +1336,17 @@ __device__ __forceinline__ void run_job(const SegDesc &sd, const uint64_t *ptr_t
                 out.max_rel = __builtin_fmaxf(out.max_rel, o.max_rel);
                 out.flags |= o.flags;
             }
-            // published by the release of the ticket this workgroup takes next
-            partials[(uint64_t)job_global * kRowsPerJob + slot * kG + gi] = out;
+            if (sd.n_jobs == 1 && sd.n_cases <= 1) {
+                // The segment was this one job (small tensors: the call is bound by latency,
+                // and tickets with their folds would double it): the row is final and goes
+                // straight into the caller's evo_stats.  One group block: the group is the slot.
+                const Group gr = group_of(sd.P, slot);
+                const uint32_t p = gr.cand0 + gi;
+                if (gi < gr.nc && p < sd.P - sd.n_pad) write_stats(&stats[sd.stats_row0 + p], out, sd.n);
+            } else {
+                // published by the release of the ticket this workgroup takes next
+                partials[(uint64_t)job_global * kRowsPerJob + slot * kG + gi] = out;
+            }
         }
     }
 }
@@ -1552,32 +1563,32 @@ __device__ __forceinline__ bool check_body(const SegDesc *descs, const uint64_t 
     if constexpr ((DTS & (1u << EVO_BF16)) != 0) {
         if (sd.dtype == EVO_BF16 || DTS == (1u << EVO_BF16))
             run_job<EVO_BF16, kSkip>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
-                             wave_part, redo, cand_lds);
+                             wave_part, redo, cand_lds, stats);
     }
     if constexpr ((DTS & (1u << EVO_F16)) != 0) {
         if (sd.dtype == EVO_F16 || DTS == (1u << EVO_F16))
             run_job<EVO_F16, kSkip>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
-                             wave_part, redo, cand_lds);
+                             wave_part, redo, cand_lds, stats);
     }
     if constexpr ((DTS & (1u << EVO_F32)) != 0) {
         if (sd.dtype == EVO_F32 || DTS == (1u << EVO_F32))
             run_job<EVO_F32, kSkip>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
-                             wave_part, redo, cand_lds);
+                             wave_part, redo, cand_lds, stats);
     }
     if constexpr ((DTS & (1u << EVO_F64)) != 0) {
         if (sd.dtype == EVO_F64 || DTS == (1u << EVO_F64))
             run_job<EVO_F64, kSkip>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
-                             wave_part, redo, cand_lds);
+                             wave_part, redo, cand_lds, stats);
     }
     if constexpr ((DTS & (1u << EVO_I32)) != 0) {
         if (sd.dtype == EVO_I32 || DTS == (1u << EVO_I32))
             run_job<EVO_I32, kSkip>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
-                             wave_part, redo, cand_lds);
+                             wave_part, redo, cand_lds, stats);
     }
     if constexpr ((DTS & (1u << EVO_I64)) != 0) {
         if (sd.dtype == EVO_I64 || DTS == (1u << EVO_I64))
             run_job<EVO_I64, kSkip>(sd, ptr_table, job_local, job, atol, rtol, second_round, partials, exact_acc,
-                             wave_part, redo, cand_lds);
+                             wave_part, redo, cand_lds, stats);
     }
 
     // Two tickets: the bundle of kFold chunks this job belongs to, then the segment (see
@@ -1603,18 +1614,7 @@ __device__ __forceinline__ bool check_body(const SegDesc *descs, const uint64_t 
     const uint32_t first = (chunk / kFold) * kFold;
     const uint32_t count = min(kFold, sd.n_chunks - first);
     __syncthreads();
-    if (sd.n_jobs == 1 && sd.n_cases <= 1) {
-        // The segment was this one job (small tensors: the call is bound by latency, and
-        // two tickets with their folds would double it): its rows are final.  They were
-        // written by this workgroup and the barrier above orders them before these loads.
-        for (uint32_t p = threadIdx.x; p < sd.P - sd.n_pad; p += kThreads) {
-            uint32_t group, gi;
-            locate(sd.P, p, &group, &gi);      // one group block: the group is the slot
-            const Partial a = partials[(uint64_t)job * kRowsPerJob + group * kG + gi];
-            write_stats(&stats[sd.stats_row0 + p], a, sd.n);
-        }
-        return true;
-    }
+    if (sd.n_jobs == 1 && sd.n_cases <= 1) return true;   // run_job has written the evo_stats rows
     Partial *case_rows = rows1 + (uint64_t)total_jobs * kRowsPerJob;
     // A segment whose jobs' rows one workgroup can add in a few batches per thread (at most
     // kOneLevelRows per thread in finalize_segment's layout, i.e. one batch of loads: up to 128
