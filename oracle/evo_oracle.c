@@ -31,7 +31,9 @@
  * element-at-a-time Python brute force, closed forms on the synthetic configs;
  * binary64 tensors: the same table and class fixtures, numpy.isclose in binary64,
  * agreement with the binary32 path where both are exact; integer tensors: Python
- * integers; mean-based speedup: closed forms on exactly summable samples).
+ * integers; mean-based speedup: closed forms on exactly summable samples; the
+ * rounding order of the tolerance: hand-built examples in which a fused or a
+ * wider product flips the verdict).
  *
  * Build:  gcc -O2 -std=c11 -ffp-contract=off -fPIC -shared
  * Every fp32 operation below is rounded on its own (no fused multiply-add, no
