@@ -193,6 +193,24 @@ __device__ __forceinline__ double last_lane_f64(double v) {
     STEP(kRowBcast15, 0xa);              \
     STEP(kRowBcast31, 0xc)
 
+// Per-lane counts of one tile (mismatches in the low half, exclusions in the high half: at
+// most 16 each, so the halves of the wavefront's total do not meet) and per-lane flags into
+// the wavefront's LDS record of the candidate.
+__device__ __forceinline__ void settle_counts(ExactAcc *out, int lane, uint32_t counts, uint32_t flags) {
+#define EVO_STEP(CTRL_, MASK_) counts += dpp_word<CTRL_, MASK_>(counts)
+    EVO_WAVE_REDUCE(EVO_STEP);
+#undef EVO_STEP
+    const uint32_t total = __builtin_amdgcn_readlane(counts, kLanes - 1);
+    const uint32_t nan_flags = EVO_F_CAND_NAN | EVO_F_NAN_SITE_DIFF, inf_flags = EVO_F_CAND_INF | EVO_F_INF_DIFF;
+    const uint32_t all_flags = (ballot((flags & nan_flags) != 0) ? nan_flags : 0u) |
+                               (ballot((flags & inf_flags) != 0) ? inf_flags : 0u);
+    if (lane == 0) {
+        out->n_mismatch += total & 0xffffu;
+        out->n_excluded += total >> 16;
+        out->flags |= all_flags;
+    }
+}
+
 // Wavefront totals of one exact-path tile into the wavefront's LDS record of the candidate.
 __device__ __forceinline__ void exact_commit(ExactAcc *out, int lane, float max_abs, float max_rel,
                                              double sum_abs, double sum_rel, uint32_t n_mismatch,
@@ -613,9 +631,9 @@ __device__ __forceinline__ void exact_candidate_pass(const char *rptr, const cha
 // Fast path of one wavefront over its full tiles walk.at(0), walk.at(1), ... (those below
 // t_fend) for a full group of NC candidates.  Straight-line code per candidate apart from the
 // commit test; loads run D candidates ahead of the arithmetic, across tile boundaries
-// too.  Candidates of a tile that the fast path must not settle (anything non-finite,
-// overflow) are recorded in redo[tile slot] for the exact path -- except a candidate tile
-// that is NaN or Inf throughout over a moderate reference tile, whose share is added on the spot
+// too.  Candidates of a tile that the fast path must not settle (a non-finite or huge
+// reference element, overflow) are recorded in redo[tile slot] for the exact path; NaN and
+// Inf in a candidate tile over a moderate reference tile are settled on the spot
 // (counts, exclusions and flags in xacc).  Ends with the lanes -> wavefront
 // reduction into wpart[0 .. NC).
 template <uint32_t DT, int NC, bool REF_STREAM, bool PADDED>
@@ -749,7 +767,13 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, const uint64_t 
                     // each tile's first candidates a full memory latency away (5 candidates
                     // ran at 0.68-0.72 of peak where 4 and 8 reach 0.79).
                     const bool same_tile = (uint32_t)(g + D) < n_real;
-                    const uint64_t base = cptr_lds[same_tile ? (uint32_t)(g + D) : (uint32_t)(g % D)] +
+                    // (the table's address through an opaque copy: the NC addresses formed from
+                    // it do not depend on the tile, and kept in registers across the whole
+                    // loop they are what tips the 16-bit kernels into spilling)
+                    uint32_t table_here = table_addr;
+                    asm volatile("" : "+v"(table_here));
+                    lds_u64 *table = (lds_u64 *)(uintptr_t)table_here;
+                    const uint64_t base = table[same_tile ? (uint32_t)(g + D) : (uint32_t)(g % D)] +
                                           (same_tile ? voff : voff_next);
 #pragma unroll
                     for (int j = 0; j < kNV; ++j) buf[u][g % D][j] = load16_at<true>(base + j * 1024);
@@ -800,32 +824,63 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, const uint64_t 
                     acc[g].sum_rel = s_rel;
                     if (mism != 0 && lane == 0) xacc[g].n_mismatch += mism;
                 } else {
-                    // What a broken kernel tends to produce: a tile without a single number in
-                    // it, NaN or +-Inf throughout.  Over reference elements below 2^102 in
+                    // What a broken kernel tends to produce: NaN or +-Inf, throughout a tile
+                    // or scattered among numbers.  Over reference elements below 2^102 in
                     // magnitude a difference is NaN iff the candidate element is NaN and
                     // infinite iff it is infinite (a finite one cannot carry the difference
                     // past the largest binary32 number: 2^102 is a quarter of its last
-                    // place).  Then the tile's share is known without looking further: every
-                    // element mismatches and is excluded from the statistics.
-                    uint64_t number = 0, any_nan = 0, any_inf = 0;
+                    // place), so such a tile is settled here from the differences alone: an
+                    // element whose difference is not a number mismatches and is excluded from
+                    // the statistics (0, the identity of both sums and both maxima, takes its
+                    // place), the flags follow from which of the two kinds occurred.  Counts
+                    // and flags are kept per lane and combined once per tile.
+                    bool settled = false;
+                    // (through an opaque copy: the compiler otherwise duplicates the candidates'
+                    // code along "the tile is moderate" and "it is not", which costs the loop
+                    // its register allocation)
+                    uint32_t moderate_here = __builtin_amdgcn_readfirstlane(moderate_tile ? 1u : 0u);
+                    asm volatile("" : "+s"(moderate_here));
+                    if (moderate_here != 0u) {
+                        float rtol_here = rtol;
+                        asm volatile("" : "+s"(rtol_here));
+                        uint32_t counts = 0;   // mismatches | exclusions << 16
+                        uint32_t flags = 0;
 #pragma unroll
-                    for (int e = 0; e < kE; ++e) {
-                        const uint64_t is_nan = ballot(d[e] != d[e]);
-                        const uint64_t is_inf = ballot(__builtin_fabsf(d[e]) == kInf);
-                        any_nan |= is_nan;
-                        any_inf |= is_inf;
-                        number |= ~(is_nan | is_inf);
-                    }
-                    if (moderate_tile && number == 0) {
-                        if (lane == 0) {
-                            xacc[g].n_mismatch += (uint32_t)tile_elems(DT);
-                            xacc[g].n_excluded += (uint32_t)tile_elems(DT);
-                            xacc[g].flags |= (any_nan ? EVO_F_CAND_NAN | EVO_F_NAN_SITE_DIFF : 0u) |
-                                             (any_inf ? EVO_F_CAND_INF | EVO_F_INF_DIFF : 0u);
+                        for (int e = 0; e < kE; ++e) {
+                            const float scaled = rtol_here * __builtin_fabsf(r[e]);
+                            const float tol = atol + scaled;
+                            const float ad = __builtin_fabsf(d[e]);
+                            counts += (ad <= tol) ? 0u : 1u;          // NaN and Inf included
+                            const bool is_number = ad < kInf;
+                            counts += is_number ? 0u : 0x10000u;
+                            flags |= (ad == kInf) ? (uint32_t)(EVO_F_CAND_INF | EVO_F_INF_DIFF) : 0u;
+                            flags |= (ad != ad) ? (uint32_t)(EVO_F_CAND_NAN | EVO_F_NAN_SITE_DIFF) : 0u;
+                            d[e] = is_number ? ad : 0.0f;
+                            q[e] = is_number ? q[e] : 0.0f;
+                            if (kE > 8 && (e & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // (register pressure)
                         }
-                    } else {
-                        redo_mask |= 1u << g;
+                        const float sa_n = tree_sum<kE, false>(d);
+                        const float sr_n = tree_sum<kE, false>(q);
+                        const float chk_n = sa_n + sr_n;
+                        // (still not finite: a sum or a relative error that overflows binary32
+                        // -- left to the exact path)
+                        if (ballot(!(chk_n < kInf)) == 0) {
+                            float ta_n = max3(0.0f, d[0], d[1]);
+                            float mr_n = max3(acc[g].max_rel, q[0], q[1]);
+#pragma unroll
+                            for (int e = 2; e < kE; e += 2) {
+                                ta_n = max3(ta_n, d[e], d[e + 1]);
+                                mr_n = max3(mr_n, q[e], q[e + 1]);
+                            }
+                            acc[g].max_abs = max3(acc[g].max_abs, ta_n, ta_n);
+                            acc[g].max_rel = mr_n;
+                            acc[g].sum_abs += (double)sa_n;
+                            acc[g].sum_rel += (double)sr_n;
+                            settle_counts(&xacc[g], lane, counts, flags);
+                            settled = true;
+                        }
                     }
+                    if (!settled) redo_mask |= 1u << g;
                 }
             }
             if (lane == 0) redo[slot] = (uint16_t)redo_mask;
@@ -1012,30 +1067,50 @@ __device__ __forceinline__ uint32_t fast_tiles_wide(const char *rptr, uint64_t c
                         acc[g].sum_rel += sr;
                         n_mismatch[g] += mism;
                     } else {
-                        // As in fast_tiles: a candidate tile without a single number in it, NaN
-                        // or +-Inf throughout, over a moderate reference tile (below 2^969 a
-                        // finite candidate element cannot carry the difference past the largest
-                        // binary64 number: that is a quarter of its last place) is settled on
-                        // the spot -- every element mismatches and is excluded.
-                        uint64_t number = 0, any_nan = 0, any_inf = 0;
+                        // As in fast_tiles: over a moderate reference tile (below 2^969 a finite
+                        // candidate element cannot carry the difference past the largest
+                        // binary64 number: that is a quarter of its last place) a tile that
+                        // holds NaN or +-Inf is settled from the differences alone -- an
+                        // element whose difference is not a number mismatches and is excluded.
+                        bool settled = false;
+                        uint32_t moderate_here = __builtin_amdgcn_readfirstlane(moderate_tile ? 1u : 0u);
+                        asm volatile("" : "+s"(moderate_here));   // see fast_tiles
+                        if (moderate_here != 0u) {
+                            uint32_t counts = 0;   // mismatches | exclusions << 16
+                            uint32_t flags = 0;
 #pragma unroll
-                        for (int e = 0; e < kE; ++e) {
-                            const uint64_t is_nan = ballot(d[e] != d[e]);
-                            const uint64_t is_inf = ballot(__builtin_fabs(d[e]) == kInfD);
-                            any_nan |= is_nan;
-                            any_inf |= is_inf;
-                            number |= ~(is_nan | is_inf);
-                        }
-                        if (moderate_tile && number == 0) {
-                            n_mismatch[g] += (uint32_t)tile_elems(DT);
-                            if (lane == 0) {
-                                xacc[g].n_excluded += (uint32_t)tile_elems(DT);
-                                xacc[g].flags |= (any_nan ? EVO_F_CAND_NAN | EVO_F_NAN_SITE_DIFF : 0u) |
-                                                 (any_inf ? EVO_F_CAND_INF | EVO_F_INF_DIFF : 0u);
+                            for (int e = 0; e < kE; ++e) {
+                                const double scaled = rtol_d * __builtin_fabs(r[e]);
+                                const double tol = atol_d + scaled;
+                                const double ad = __builtin_fabs(d[e]);
+                                counts += (ad <= tol) ? 0u : 1u;
+                                const bool is_number = ad < kInfD;
+                                counts += is_number ? 0u : 0x10000u;
+                                flags |= (ad == kInfD) ? (uint32_t)(EVO_F_CAND_INF | EVO_F_INF_DIFF) : 0u;
+                                flags |= (ad != ad) ? (uint32_t)(EVO_F_CAND_NAN | EVO_F_NAN_SITE_DIFF) : 0u;
+                                d[e] = is_number ? ad : 0.0;
+                                q[e] = is_number ? q[e] : 0.0;
                             }
-                        } else {
-                            redo_mask |= 1u << g;
+                            const double sa_n = tree_sum_f64<kE, false>(d);
+                            const double sr_n = tree_sum_f64<kE, false>(q);
+                            const double chk_n = sa_n + sr_n;
+                            if (ballot(!(chk_n < kInfD)) == 0) {   // else: overflow, exact path
+                                double ta_n = d[0], tr_n = q[0];
+#pragma unroll
+                                for (int e = 1; e < kE; ++e) {
+                                    ta_n = __builtin_fmax(ta_n, d[e]);
+                                    tr_n = __builtin_fmax(tr_n, q[e]);
+                                }
+                                const float ta = (float)ta_n, tr = (float)tr_n;
+                                acc[g].max_abs = max3(acc[g].max_abs, ta, ta);
+                                acc[g].max_rel = max3(acc[g].max_rel, tr, tr);
+                                acc[g].sum_abs += sa_n;
+                                acc[g].sum_rel += sr_n;
+                                settle_counts(&xacc[g], lane, counts, flags);
+                                settled = true;
+                            }
                         }
+                        if (!settled) redo_mask |= 1u << g;
                     }
                 } else if constexpr (DT == EVO_I32) {
                     const uint32_t rr[kE] = {rw[0].x, rw[0].y, rw[0].z, rw[0].w, rw[1].x, rw[1].y, rw[1].z, rw[1].w};

@@ -160,6 +160,53 @@ def test_no_number_shortcut_stops_where_a_difference_can_overflow(gu, dtype):
     chk.close()
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16, torch.float64],
+                         ids=lambda d: str(d).split(".")[-1])
+def test_numbers_and_non_numbers_in_one_tile(gu, dtype):
+    """NaN and Inf scattered among numbers (what a kernel with a data-dependent bug produces) are
+    settled in the fast path, tile by tile: an element whose difference is not a number
+    mismatches and is left out of the statistics, its neighbours count as usual.  Here: one NaN
+    per tile, +Inf and -Inf, both kinds in one tile, non-numbers over reference elements that
+    are 0 or subnormal (relative error defined as 0 there), next to finite mismatches and
+    matches in the same tile, candidates whose numbers make a relative error overflow (those
+    tiles go to the exact path), and the same over a reference tile that holds a huge value, a
+    NaN or an Inf (never settled in the fast path)."""
+    _say("mixed tiles %s" % dtype)
+    n = 48 * 1024 + 421
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    ref = (torch.randn(n, generator=g, device="cuda", dtype=torch.float64) + 2).to(dtype)
+    tiny = torch.finfo(dtype).tiny
+    ref[5::97] = 0.0
+    ref[6::197] = tiny / 4                       # subnormal
+    ref[7::397] = -tiny / 2
+    huge = {torch.float64: 2.0 ** 1000}.get(dtype, 2.0 ** 110 if dtype != torch.float16 else 60000.0)
+    ref[30 * 1024 + 3] = huge                    # one tile with a huge reference element
+    ref[33 * 1024 + 9] = float("nan")
+    ref[36 * 1024 + 1] = float("-inf")
+    near = (ref.double() * 1.001).to(dtype)      # inside the tolerance
+    off = (ref.double() * 1.5 + 1).to(dtype)     # outside
+    cands = []
+    c = near.clone(); c[11::256] = float("nan"); cands.append(c)
+    c = near.clone(); c[12::256] = float("inf"); c[140::256] = float("-inf"); cands.append(c)
+    c = off.clone(); c[13::64] = float("nan"); c[14::128] = float("inf"); cands.append(c)
+    c = near.clone(); c[5::97] = float("nan"); c[6::197] = float("inf"); c[7::397] = float("nan"); cands.append(c)
+    c = near.clone(); c[::2] = float("nan"); c[1::512] = off[1::512]; cands.append(c)
+    c = near.clone(); c[100::1000] = float("nan"); c[6::197] = 1.0; cands.append(c)   # 1 / subnormal: Inf
+    c = torch.full_like(ref, float("nan")); c[3::64] = near[3::64]; cands.append(c)
+    c = ref.clone(); c[777] = float("nan"); cands.append(c)                            # a single NaN
+    c = ref.clone(); c[n - 1] = float("inf"); cands.append(c)                          # in the ragged tail
+    cands.append(near.clone())
+    P = len(cands)
+    seg = synth.Segment(ref.contiguous(), [x.contiguous() for x in cands], (n,), [True] * P)
+    w = synth.Workload("mixed-tiles", [seg], 1e-2, 1e-2, torch.ones(P, 4, device="cuda"),
+                       torch.ones(4, device="cuda"))
+    chk, stats, want = gu.check_parity(w, label="mixed tiles %s" % dtype)
+    assert all(want[p]["valid"] == 0 for p in range(P))      # the reference's own NaN never matches
+    assert want[7]["n_mismatch"] == 2 and want[0]["n_finite"] < n - n // 256
+    chk.close()
+
+
 def test_guard_rows_around_the_result_buffer(gu):
     """The calls write the rows they are given and not a byte more."""
     _say("guard rows")
