@@ -8,7 +8,7 @@ before the timed region starts.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--spinup-ms MS] [--workload c2|c1|c3|c3h|c4|c5|cases|f64|i32|i64]
                     [--no-cpu-baseline] [--no-read-ceiling] [--copy-calibration] [--no-extra-workloads]
-                    [--sweep populations|small|cases]
+                    [--sweep populations|small|cases|broken]
 
 The JSON line is about --workload (default c2, the configuration the metric is quoted on).  With
 the default workload it also carries "workloads": the same measurement of the other large
@@ -205,17 +205,26 @@ def sweep(mode: str, steps: int) -> int:
       populations  P = 1..33 candidates at 2.4-4.6 GB per launch, fp32 and bf16
       small        fp32 launches of 8 MB to 1.1 GB
       cases        K = 5 test cases of P = 1..8 candidates (the shape of one evaluation in the
-                   paper's loop), fp32, 2^20 / 2^24 / 2^26 elements per tensor"""
+                   paper's loop), fp32, 2^20 / 2^24 / 2^26 elements per tensor
+      broken       16 candidates of which 0, 1, 4 or all hold a NaN in every 64th place or are
+                   NaN throughout (what kernels with a bug produce), and a reference that holds
+                   -Inf in every 65536th, 4096th or 64th place with candidates that copy it;
+                   fp32, bf16 and fp64 at 2.3 GB per launch"""
     import torch
     import paper_2510_03760_amd as evo
 
-    def run(dt, n, P, K=1):
-        tdt = {"f32": torch.float32, "bf16": torch.bfloat16}[dt]
-        code = {"f32": evo.EVO_F32, "bf16": evo.EVO_BF16}[dt]
+    def run(dt, n, P, K=1, spoil=None, note=None):
+        tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f64": torch.float64}[dt]
+        code = {"f32": evo.EVO_F32, "bf16": evo.EVO_BF16, "f64": evo.EVO_F64}[dt]
         g = torch.Generator(device="cuda")
         g.manual_seed(1)
         refs = [torch.rand(n, device="cuda", generator=g).to(tdt) for _ in range(K)]
-        cands = [[(r.float() * 1.0001).to(tdt) for _ in range(P)] for r in refs]
+        if spoil is not None and spoil[0] == "ref":
+            refs[0][::spoil[1]] = float("-inf")
+        cands = [[(r.double() * 1.0001).to(tdt) for _ in range(P)] for r in refs]
+        if spoil is not None and spoil[0] == "cand":
+            for k in range(spoil[2]):
+                cands[0][(5 * k + 3) % P][::spoil[1]] = float("nan")
         chk = evo.Checker(code, n, 1e-2, 1e-2)
         stats = chk.new_stats(P)
         cases = [{"ref": r, "cand_ptrs": c, "n_elems": n, "dtype": code} for r, c in zip(refs, cands)]
@@ -233,10 +242,13 @@ def sweep(mode: str, steps: int) -> int:
         ms = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
         med = ms[len(ms) // 2]
         byt = K * (P + 1) * n * refs[0].element_size()
-        print(json.dumps({"sweep": mode, "dtype": dt, "n_elems": n, "P": P, "K": K, "algorithmic_bytes": byt,
-                          "median_us": round(med * 1e3, 1), "GBps": round(byt / med / 1e6, 0),
-                          "frac_of_peak": round(byt / med / 1e6 / HBM_PEAK_GBS, 3),
-                          "entry": "evo_check_batch" if K == 1 else "evo_check_cases"}), flush=True)
+        line = {"sweep": mode, "dtype": dt, "n_elems": n, "P": P, "K": K, "algorithmic_bytes": byt,
+                "median_us": round(med * 1e3, 1), "GBps": round(byt / med / 1e6, 0),
+                "frac_of_peak": round(byt / med / 1e6 / HBM_PEAK_GBS, 3),
+                "entry": "evo_check_batch" if K == 1 else "evo_check_cases"}
+        if note is not None:
+            line["input"] = note
+        print(json.dumps(line), flush=True)
         chk.close()
 
     if mode == "populations":
@@ -253,8 +265,17 @@ def sweep(mode: str, steps: int) -> int:
         for P in (1, 2, 4, 8):
             for lg in (20, 24, 26):
                 run("f32", 1 << lg, P, K=5)
+    elif mode == "broken":
+        for dt, lg in (("f32", 25), ("bf16", 26), ("f64", 24)):
+            run(dt, 1 << lg, 16, note="clean")
+            for k in (1, 4, 16):
+                run(dt, 1 << lg, 16, spoil=("cand", 64, k), note="%d of 16 candidates with NaN in every 64th place" % k)
+            for k in (4, 16):
+                run(dt, 1 << lg, 16, spoil=("cand", 1, k), note="%d of 16 candidates NaN throughout" % k)
+            for stride in (65536, 4096, 64):
+                run(dt, 1 << lg, 16, spoil=("ref", stride), note="reference -Inf in every %dth place, candidates copy it" % stride)
     else:
-        print("bench.py: unknown sweep %r (populations, small, cases)" % mode, file=sys.stderr)
+        print("bench.py: unknown sweep %r (populations, small, cases, broken)" % mode, file=sys.stderr)
         return 2
     return 0
 
@@ -414,7 +435,7 @@ def main() -> int:
     ap.add_argument("--no-read-ceiling", action="store_true")
     ap.add_argument("--split", action="store_true",
                     help="two calls per step (check, then fitness) also where evo_evaluate applies")
-    ap.add_argument("--sweep", default=None, help="populations | small | cases: other shapes, one JSON line each")
+    ap.add_argument("--sweep", default=None, help="populations | small | cases | broken: other shapes and inputs, one JSON line each")
     ap.add_argument("--no-extra-workloads", action="store_true",
                     help="with the default workload: do not measure the other large workloads afterwards")
     args = ap.parse_args()

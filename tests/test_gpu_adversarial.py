@@ -184,6 +184,9 @@ def test_numbers_and_non_numbers_in_one_tile(gu, dtype):
     ref[30 * 1024 + 3] = huge                    # one tile with a huge reference element
     ref[33 * 1024 + 9] = float("nan")
     ref[36 * 1024 + 1] = float("-inf")
+    ref[40 * 1024 + 5] = float("inf")            # each kind alone in a tile of otherwise plain values
+    ref[42 * 1024 + 7] = float("-inf")
+    ref[44 * 1024 + 9] = float("nan")
     near = (ref.double() * 1.001).to(dtype)      # inside the tolerance
     off = (ref.double() * 1.5 + 1).to(dtype)     # outside
     cands = []
@@ -196,6 +199,8 @@ def test_numbers_and_non_numbers_in_one_tile(gu, dtype):
     c = torch.full_like(ref, float("nan")); c[3::64] = near[3::64]; cands.append(c)
     c = ref.clone(); c[777] = float("nan"); cands.append(c)                            # a single NaN
     c = ref.clone(); c[n - 1] = float("inf"); cands.append(c)                          # in the ragged tail
+    c = near.clone(); c[40 * 1024 + 5] = float("-inf"); c[42 * 1024 + 7] = float("inf"); cands.append(c)   # wrong sign
+    c = near.clone(); c[40 * 1024 + 5] = 1.0; c[42 * 1024 + 7] = float("nan"); c[44 * 1024 + 9] = 0.0; cands.append(c)
     cands.append(near.clone())
     P = len(cands)
     seg = synth.Segment(ref.contiguous(), [x.contiguous() for x in cands], (n,), [True] * P)
@@ -203,7 +208,7 @@ def test_numbers_and_non_numbers_in_one_tile(gu, dtype):
                        torch.ones(4, device="cuda"))
     chk, stats, want = gu.check_parity(w, label="mixed tiles %s" % dtype)
     assert all(want[p]["valid"] == 0 for p in range(P))      # the reference's own NaN never matches
-    assert want[7]["n_mismatch"] == 2 and want[0]["n_finite"] < n - n // 256
+    assert want[7]["n_mismatch"] == 3 and want[0]["n_finite"] < n - n // 256
     chk.close()
 
 
