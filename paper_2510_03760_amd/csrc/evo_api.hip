@@ -362,6 +362,28 @@ void split_remainders(const std::vector<HostSeg> &in, std::vector<HostSeg> &out)
     out.resize(n);
 }
 
+// A case group is folded directly (kFoldCasesDirect) when one workgroup can hold all of it:
+// a thread per (case, candidate, range of jobs) with at most kDirectRowsPerThread rows to add.
+void choose_fold_modes(SegDesc *descs, size_t n_segs) {
+    for (size_t s = 0; s < n_segs;) {
+        const uint32_t K = descs[s].n_cases;
+        if (K <= 1 || descs[s].case0 != s || s + K > n_segs) {
+            ++s;
+            continue;
+        }
+        const uint32_t Kp = pow2_ceil(K), pc = pow2_ceil(descs[s].P);
+        bool ok = K <= evo::kDirectMaxCases && (uint64_t)Kp * pc <= (uint64_t)evo::kThreads;
+        if (ok) {
+            const uint32_t ranges = (uint32_t)evo::kThreads / (Kp * pc);
+            for (uint32_t k = 0; k < K; ++k)
+                ok = ok && descs[s + k].P == descs[s].P &&
+                     (descs[s + k].n_chunks + ranges - 1) / ranges <= evo::kDirectRowsPerThread;
+        }
+        for (uint32_t k = 0; k < K; ++k) descs[s + k].fold_mode = ok ? evo::kFoldCasesDirect : evo::kFoldLevels;
+        s += K;
+    }
+}
+
 // Splits every segment into jobs (workgroups) of similar cost.  Cost unit: one tile load
 // of one wavefront; a step of a workgroup costs its largest candidate group plus the
 // reference.  The launch is sized to the machine (a fixed number of workgroups per
@@ -378,7 +400,8 @@ void partition(const HostSeg *segs, size_t n_segs, uint32_t target_jobs, SegDesc
         d.n = h.n;
         d.P = padded_population(h.P);
         d.n_pad = (uint8_t)(d.P - h.P);
-        d.dtype = (uint16_t)h.dtype;
+        d.dtype = (uint8_t)h.dtype;
+        d.fold_mode = evo::kFoldLevels;
         d.atol = h.atol;
         d.rtol = h.rtol;
         d.stats_row0 = h.row0;
@@ -430,6 +453,7 @@ void partition(const HostSeg *segs, size_t n_segs, uint32_t target_jobs, SegDesc
         per_job = std::max<uint64_t>(per_job + 1, per_job * job0 / target_jobs);
     }
     total_jobs = job0;
+    choose_fold_modes(descs, n_segs);
 }
 
 // Upper bound on what partition() can produce for these segments (checked before any

@@ -1459,13 +1459,22 @@ __device__ __forceinline__ void add_partial(Partial &a, const Partial &o) {
     a.flags |= o.flags;
 }
 
-// Device-scope load of one 48-byte row (it was written by another workgroup, possibly
-// through another XCD's L2).
+// One 48-byte row, written by another workgroup (possibly through another XCD's L2), as three
+// plain 16-byte loads.  What makes them see the writer's data is the acquire of the ticket
+// that thread 0 drew before (it invalidates this compute unit's L1 and the stale lines of
+// this XCD's L2) and the workgroup barrier behind it; no line of these rows can come back
+// stale afterwards, because rows that share a cache line have one writer, and it had released
+// them before that ticket could be the last.  As six device-scope 8-byte loads -- each of
+// which goes to memory on its own -- the rows of a fold took 5 us to arrive.
 __device__ __forceinline__ void load_row(const Partial *row, uint64_t (&w)[6]) {
-    const uint64_t *src = reinterpret_cast<const uint64_t *>(row);
+    typedef __attribute__((address_space(1))) const u32x4 global_u32x4;
+    global_u32x4 *src = (global_u32x4 *)(uintptr_t)row;
 #pragma unroll
-    for (int q = 0; q < 6; ++q)
-        w[q] = __hip_atomic_load(src + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int q = 0; q < 3; ++q) {
+        const u32x4 v = src[q];
+        w[2 * q] = u64_of(v.x, v.y);
+        w[2 * q + 1] = u64_of(v.z, v.w);
+    }
 }
 
 // Level 1: rows of chunks [first, first + count) of group block `gblock` -> one row per
@@ -1599,6 +1608,64 @@ __device__ __forceinline__ void write_case_group(const SegDesc *descs, const Seg
     }
 }
 
+// kFoldCasesDirect: the rows of all jobs of all K cases of a group in one workgroup.  A thread
+// per (candidate, case, range of the case's jobs) adds its rows in job order (at most
+// kDirectRowsPerThread, fetched together), the ranges of a (candidate, case) are added by a
+// fixed tree in LDS, and the cases of a candidate are merged in case order.
+__device__ __forceinline__ void finalize_cases_direct(const SegDesc *descs, const SegDesc &sd,
+                                                      const Partial *rows, evo_stats *stats, Partial *fold) {
+    const uint32_t K = sd.n_cases;
+    uint32_t Kp = 1, pc = 1;
+    while (Kp < K) Kp <<= 1;
+    while (pc < sd.P) pc <<= 1;
+    const uint32_t R = (uint32_t)kThreads / (Kp * pc);   // >= 1: the host chose this mode
+    const uint32_t ci = threadIdx.x % pc;
+    const uint32_t ki = (threadIdx.x / pc) % Kp;
+    const uint32_t ri = threadIdx.x / (pc * Kp);
+    Partial a{};
+    if (ki < K && ci < sd.P) {
+        const SegDesc &dk = descs[sd.case0 + ki];
+        uint32_t group, gi;
+        locate(dk.P, ci, &group, &gi);
+        const uint32_t gblock = group / dk.gpw;
+        const uint32_t slot = group - gblock * dk.gpw;
+        const uint32_t units = dk.n_chunks;
+        const uint32_t per = (units + R - 1) / R;
+        const uint32_t ch_lo = ri * per;
+        const uint32_t ch_hi = min(ch_lo + per, units);
+        if (ch_lo < ch_hi) {
+            uint64_t w[kDirectRowsPerThread][6];
+#pragma unroll
+            for (uint32_t k = 0; k < kDirectRowsPerThread; ++k) {
+                const uint32_t c2 = min(ch_lo + k, ch_hi - 1);
+                const uint64_t unit = (uint64_t)dk.job0 + (uint64_t)gblock * units + c2;
+                load_row(rows + unit * kRowsPerJob + slot * kG + gi, w[k]);
+            }
+#pragma unroll
+            for (uint32_t k = 0; k < kDirectRowsPerThread; ++k)
+                if (ch_lo + k < ch_hi) add_row(a, w[k]);
+        }
+    }
+    fold[threadIdx.x] = a;
+    __syncthreads();
+    for (uint32_t stride = R >> 1; stride >= 1; stride >>= 1) {
+        if (ri < stride) {
+            add_partial(a, fold[threadIdx.x + stride * pc * Kp]);
+            fold[threadIdx.x] = a;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x < pc && ci < sd.P - sd.n_pad) {   // range 0 of case 0: the candidate's writer
+        Partial m{};
+        uint64_t n_elems = 0;
+        for (uint32_t k = 0; k < K; ++k) {
+            add_partial(m, fold[ci + k * pc]);
+            n_elems += descs[sd.case0 + k].n;
+        }
+        write_stats(&stats[sd.stats_row0 + ci], m, n_elems);
+    }
+}
+
 // DTS = set of element types (bit 1 << evo_dtype) this instantiation can meet.  A launch
 // whose segments all have one element type gets a kernel that holds only that type's
 // code, so that its register allocation is not the worst case over all types.
@@ -1675,7 +1742,7 @@ __device__ __forceinline__ bool check_body(const SegDesc *descs, const uint64_t 
     // scope, whose release makes everything that happened before it in the workgroup
     // visible to the other XCDs.  The workgroup that draws the last ticket acquires through
     // the same operation, hands that on to its other threads through the next barrier, and
-    // reads the rows with device-scope loads (load_row).  There is no separate fence: each
+    // reads the rows with plain loads (see load_row).  There is no separate fence: each
     // one is a write-back and invalidation of the whole L2 of the XCD and was measured at
     // 2-10 us, on a path that nothing overlaps once the last tile has been streamed.
     __shared__ uint32_t is_last;
@@ -1691,6 +1758,24 @@ __device__ __forceinline__ bool check_body(const SegDesc *descs, const uint64_t 
     __syncthreads();
     if (sd.n_jobs == 1 && sd.n_cases <= 1) return true;   // run_job has written the evo_stats rows
     Partial *case_rows = rows1 + (uint64_t)total_jobs * kRowsPerJob;
+    if (sd.fold_mode == kFoldCasesDirect) {
+        // A small case group: one ticket for all jobs of all its cases (they are numbered
+        // consecutively), and the last one folds everything.
+        uint32_t *group_ticket = seg_tickets + S + sd.case0;
+        if (threadIdx.x == 0) {
+            const SegDesc &d_first = descs[sd.case0], &d_last = descs[sd.case0 + sd.n_cases - 1];
+            const uint32_t group_jobs = d_last.job0 + d_last.n_jobs - d_first.job0;
+            const uint32_t prev = __hip_atomic_fetch_add(group_ticket, 1u, __ATOMIC_ACQ_REL,
+                                                         __HIP_MEMORY_SCOPE_AGENT);
+            is_last = (prev == group_jobs - 1) ? 1u : 0u;
+        }
+        __syncthreads();
+        if (!is_last) return false;
+        finalize_cases_direct(descs, sd, partials, stats, fold);
+        if (threadIdx.x == 0)
+            __hip_atomic_store(group_ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return true;
+    }
     // A segment whose jobs' rows one workgroup can add in a few batches per thread (at most
     // kOneLevelRows per thread in finalize_segment's layout, i.e. one batch of loads: up to 128
     // jobs of 16 candidates, 512 of 4, any number of a single one) skips the first level: every job takes the segment's ticket, and the last one

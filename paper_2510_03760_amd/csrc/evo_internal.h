@@ -117,6 +117,16 @@ __host__ __device__ inline void locate(uint32_t P, uint32_t p, uint32_t *group, 
     *gi = off;
 }
 
+// How the jobs' partial rows become evo_stats rows.
+//   kFoldLevels       per segment, by one or two levels of tickets; the cases of a case group
+//                     are then merged behind a ticket of their own
+//   kFoldCasesDirect  a small case group: every job of every case draws the group's ticket and
+//                     the last one adds all rows, case by case, and merges the cases -- one
+//                     ticket round trip and one fold less behind the last job
+constexpr uint8_t kFoldLevels = 0, kFoldCasesDirect = 1;
+constexpr uint32_t kDirectMaxCases = 8;      // most cases of a group folded directly
+constexpr uint32_t kDirectRowsPerThread = 8; // most job rows one thread adds in that fold
+
 // One ragged group as the kernel sees it (device memory, 64 bytes).
 struct SegDesc {
     const void *ref;
@@ -131,7 +141,8 @@ struct SegDesc {
     uint32_t n_groups;          // candidate groups
     uint32_t n_cases;           // segments in that case group (1: the segment stands alone)
     float atol, rtol;           // the tolerance this segment is checked with
-    uint16_t dtype;
+    uint8_t dtype;
+    uint8_t fold_mode;          // kFoldLevels or kFoldCasesDirect (the same for all cases of a group)
     uint8_t gpw;                // groups per workgroup: 1, 2 or 4
     uint8_t n_pad;              // trailing candidates that are stand-ins (their pointer is the
                                 // reference's); they get no evo_stats row

@@ -140,6 +140,39 @@ static void partition_cases() {
     check_partition(std::vector<HostSeg>(1, h), 512);
     h.n = 1ull << 40; h.P = kMaxP;          // too large: refused before partitioning
     EXPECT(!partition_fits(&h, 1));
+
+    // Fold modes: a case group is folded directly only when one workgroup holds a thread per
+    // (case, candidate, range) with at most kDirectRowsPerThread rows each; all cases of a
+    // group get the same mode; segments outside a case group never get it.
+    for (int it = 0; it < 2000; ++it) {
+        const uint32_t K = 1 + (uint32_t)(rng() % 12);
+        const uint32_t P = 1 + (uint32_t)(rng() % (it % 4 == 0 ? 300 : 40));
+        std::vector<HostSeg> segs(K);
+        for (HostSeg &c : segs) {
+            c = HostSeg{};
+            c.n = 1 + rng() % (1ull << (int)(rng() % 30));
+            c.P = P; c.dtype = (uint32_t)(rng() % 6); c.row0 = 0; c.case0 = 0; c.n_cases = K;
+        }
+        if (!partition_fits(segs.data(), segs.size())) continue;
+        std::vector<SegDesc> d(K);
+        uint32_t total = 0;
+        partition(segs.data(), K, targets[it % 5], d.data(), total);
+        const uint32_t Kp = pow2_ceil(K), pc = pow2_ceil(d[0].P);
+        bool fits = K > 1 && K <= evo::kDirectMaxCases && (uint64_t)Kp * pc <= (uint64_t)evo::kThreads;
+        if (fits) {
+            const uint32_t ranges = (uint32_t)evo::kThreads / (Kp * pc);
+            for (const SegDesc &x : d) fits = fits && (x.n_chunks + ranges - 1) / ranges <= evo::kDirectRowsPerThread;
+        }
+        for (const SegDesc &x : d) EXPECT(x.fold_mode == (fits ? evo::kFoldCasesDirect : evo::kFoldLevels));
+    }
+    {
+        std::vector<HostSeg> one(3);
+        for (size_t i = 0; i < 3; ++i) { one[i] = HostSeg{}; one[i].n = 1000; one[i].P = 4; one[i].dtype = EVO_F32; one[i].row0 = 4 * (uint32_t)i; }
+        std::vector<SegDesc> d(3);
+        uint32_t total = 0;
+        partition(one.data(), 3, 512, d.data(), total);
+        for (const SegDesc &x : d) EXPECT(x.fold_mode == evo::kFoldLevels);
+    }
 }
 
 // split_remainders(): a segment stays whole or is cut in two; the parts cover its

@@ -290,6 +290,47 @@ def test_check_cases_equals_one_accumulator_over_all_cases(gu):
         chk.close()
 
 
+@pytest.mark.parametrize("K,P,n", [(8, 32, 3000), (9, 4, 3000), (8, 4, 1 << 20), (5, 4, 1 << 20), (2, 128, 5000),
+                                   (5, 8, 1 << 22), (3, 200, 40000), (8, 16, 70000)],
+                         ids=lambda v: str(v))
+def test_case_groups_on_both_sides_of_the_direct_fold(gu, K, P, n):
+    """A small case group is folded by one workgroup in one go (at most 8 cases, a thread per
+    case, candidate and range of jobs with at most 8 rows each); larger ones go through the
+    per-segment levels and a merge.  Shapes on both sides of every one of those limits, against
+    one oracle accumulator per candidate fed case after case; then the same cases through
+    evo_evaluate, whose rows must be the same bytes."""
+    _say("case group K=%d P=%d n=%d" % (K, P, n))
+    import oracle
+    import paper_2510_03760_amd as evo
+    from paper_2510_03760_amd.binding import stats_to_numpy
+    small = n <= 100000
+    ws = [_mixed(n + 17 * i, P, 9100 + 7 * i + P + K, torch.float32, special=small and i % 2 == 0) for i in range(K)]
+    chk = evo.Checker(evo.EVO_F32, 1, 1e-2, 1e-2)
+    stats = chk.new_stats(P)
+    stats.fill_(0x5A)
+    cases = [{"ref": w.segments[0].ref, "cand_ptrs": w.segments[0].cands, "n_elems": w.segments[0].n,
+              "dtype": evo.EVO_F32} for w in ws]
+    chk.check_cases(cases, stats)
+    torch.cuda.synchronize()
+    got = stats_to_numpy(stats)
+    picks = range(P) if small else (0, P // 2, P - 1)
+    refs = [synth.to_oracle_array(w.segments[0].ref) for w in ws]
+    for p in picks:
+        acc = oracle.CheckAccumulator(oracle.F32, 1e-2, 1e-2)
+        for w, r in zip(ws, refs):
+            acc.feed(r, synth.to_oracle_array(w.segments[0].cands[p]))
+        gu.assert_rows_equal(got[p], acc.result(), "case group K=%d P=%d n=%d row %d" % (K, P, n, p))
+    if K <= 8 and K * P <= 384:
+        timings, baseline = ws[0].timings, ws[0].baseline
+        stats2, summary = chk.new_stats(P), chk.new_summary()
+        chk.evaluate(cases, timings, baseline, stats2, summary)
+        torch.cuda.synchronize()
+        a, b = stats_to_numpy(stats2), got
+        for f in ("n_mismatch", "n_finite", "sum_abs_err", "sum_rel_err", "max_abs_err", "max_rel_err", "flags", "valid"):
+            assert a[f].tobytes() == b[f].tobytes(), f
+    chk.close()
+
+
 def test_large_tables_go_through_the_staged_path(gu):
     """More segments / candidate pointers than fit into the kernel-argument block: the
     descriptors are staged through pinned memory and a device table.  Also more segments
