@@ -193,6 +193,106 @@ __device__ __forceinline__ double last_lane_f64(double v) {
     STEP(kRowBcast15, 0xa);              \
     STEP(kRowBcast31, 0xc)
 
+// Lanes -> wavefront for the NC candidates of a group at the end of a job: per candidate two
+// maxima (as bit patterns, see reduce_step) and two binary64 sums.  Reducing every candidate
+// over all 64 lanes on its own (EVO_WAVE_REDUCE) costs 6 steps x NC candidates x 10
+// instructions of which all but one lane's result is thrown away -- 4 us per job for 16
+// candidates, on the path behind the last tile.  Here the lanes of a row of 16 split the
+// candidates among themselves instead: in each of four steps a lane and its partner (the
+// row's mirror image, the half row's mirror image, the quad's other pair, the neighbour)
+// exchange halves -- the lower one keeps the first half of the candidates it still holds
+// and adds the partner's values for them, the upper one the second half -- so that the data
+// per lane halves with every step and lane l ends up with the row's total of one candidate,
+// (l % 16) >> (4 - log2 NC).  The four rows are then added through two lane exchanges
+// (bpermute; a commutative tree, so all rows hold the same bits), and one lane per candidate
+// writes the wavefront's row.  Every order is fixed by the lane numbers.
+constexpr int kRowMirror = 0x140, kRowHalfMirror = 0x141, kQuadSwapPairs = 0x4E, kQuadSwapNeighbours = 0xB1;
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_all(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_all_f64(double v) {
+    const uint64_t b = __builtin_bit_cast(uint64_t, v);
+    return __builtin_bit_cast(double, ((uint64_t)dpp_all<CTRL>((uint32_t)(b >> 32)) << 32) | dpp_all<CTRL>((uint32_t)b));
+}
+
+// One step: L candidates live in x[0 .. L) of every lane; afterwards L / 2 (or the one, summed
+// with the partner's, when L == 1).  `low`: this lane is the lower one of its pair.
+template <int L, int CTRL>
+__device__ __forceinline__ void scatter_step(bool low, uint32_t *ma, uint32_t *mr, double *sa, double *sr) {
+    if constexpr (L > 1) {
+        constexpr int H = L / 2;
+#pragma unroll
+        for (int j = 0; j < H; ++j) {
+            const uint32_t ma_send = low ? ma[j + H] : ma[j], ma_keep = low ? ma[j] : ma[j + H];
+            const uint32_t mr_send = low ? mr[j + H] : mr[j], mr_keep = low ? mr[j] : mr[j + H];
+            const double sa_send = low ? sa[j + H] : sa[j], sa_keep = low ? sa[j] : sa[j + H];
+            const double sr_send = low ? sr[j + H] : sr[j], sr_keep = low ? sr[j] : sr[j + H];
+            const uint32_t ma_got = dpp_all<CTRL>(ma_send), mr_got = dpp_all<CTRL>(mr_send);
+            ma[j] = ma_got > ma_keep ? ma_got : ma_keep;
+            mr[j] = mr_got > mr_keep ? mr_got : mr_keep;
+            sa[j] = sa_keep + dpp_all_f64<CTRL>(sa_send);
+            sr[j] = sr_keep + dpp_all_f64<CTRL>(sr_send);
+        }
+    } else {
+        const uint32_t ma_got = dpp_all<CTRL>(ma[0]), mr_got = dpp_all<CTRL>(mr[0]);
+        ma[0] = ma_got > ma[0] ? ma_got : ma[0];
+        mr[0] = mr_got > mr[0] ? mr_got : mr[0];
+        sa[0] += dpp_all_f64<CTRL>(sa[0]);
+        sr[0] += dpp_all_f64<CTRL>(sr[0]);
+    }
+}
+
+__device__ __forceinline__ uint32_t from_lane(uint32_t v, int src_lane) {
+    return (uint32_t)__builtin_amdgcn_ds_bpermute(src_lane * 4, (int)v);
+}
+__device__ __forceinline__ double from_lane_f64(double v, int src_lane) {
+    const uint64_t b = __builtin_bit_cast(uint64_t, v);
+    return __builtin_bit_cast(double, ((uint64_t)from_lane((uint32_t)(b >> 32), src_lane) << 32) | from_lane((uint32_t)b, src_lane));
+}
+
+// ma, mr, sa, sr: NC values per lane (destroyed).  n_mismatch_of_lane: what the row of the
+// candidate this lane ends up with gets as its mismatch count (see group_candidate_of_lane).
+template <int NC>
+__device__ __forceinline__ int group_candidate_of_lane(int lane) {
+    constexpr int kShift = NC == 16 ? 0 : NC == 8 ? 1 : NC == 4 ? 2 : NC == 2 ? 3 : 4;
+    return (lane & 15) >> kShift;
+}
+template <int NC>
+__device__ __forceinline__ void reduce_group_to_rows(uint32_t *ma, uint32_t *mr, double *sa, double *sr, int lane,
+                                                     uint32_t n_mismatch_of_lane, Partial *wpart) {
+    static_assert(NC == 1 || NC == 2 || NC == 4 || NC == 8 || NC == 16, "group sizes");
+    scatter_step<NC, kRowMirror>((lane & 8) == 0, ma, mr, sa, sr);
+    scatter_step<(NC > 1 ? NC / 2 : 1), kRowHalfMirror>((lane & 4) == 0, ma, mr, sa, sr);
+    scatter_step<(NC > 2 ? NC / 4 : 1), kQuadSwapPairs>((lane & 2) == 0, ma, mr, sa, sr);
+    scatter_step<(NC > 4 ? NC / 8 : 1), kQuadSwapNeighbours>((lane & 1) == 0, ma, mr, sa, sr);
+    // rows: with the neighbouring row, then with the other pair of rows
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1) {
+        const uint32_t ma_got = from_lane(ma[0], lane ^ off), mr_got = from_lane(mr[0], lane ^ off);
+        const double sa_got = from_lane_f64(sa[0], lane ^ off), sr_got = from_lane_f64(sr[0], lane ^ off);
+        ma[0] = ma_got > ma[0] ? ma_got : ma[0];
+        mr[0] = mr_got > mr[0] ? mr_got : mr[0];
+        sa[0] += sa_got;
+        sr[0] += sr_got;
+    }
+    constexpr int kPerCandidate = 16 / NC;   // lanes of a row that hold the same candidate
+    if (lane < 16 && (lane & (kPerCandidate - 1)) == 0) {
+        Partial p;
+        p.n_mismatch = n_mismatch_of_lane;
+        p.n_excluded = 0;
+        p.sum_abs = sa[0];
+        p.sum_rel = sr[0];
+        p.max_abs = as_f32(ma[0]);
+        p.max_rel = as_f32(mr[0]);
+        p.flags = 0;
+        p.pad = 0;
+        wpart[group_candidate_of_lane<NC>(lane)] = p;
+    }
+}
+
 // Per-lane counts of one tile (mismatches in the low half, exclusions in the high half: at
 // most 16 each, so the halves of the wavefront's total do not meet) and per-lane flags into
 // the wavefront's LDS record of the candidate.
@@ -890,36 +990,17 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, const uint64_t 
     }
 
     __builtin_amdgcn_s_setprio(0);
-    // Lanes -> wavefront (the counts are already wave-uniform).  The step is the outer
-    // loop so that the independent chains of all candidates interleave.
+    // Lanes -> wavefront (the mismatch counts are in xacc), see reduce_group_to_rows.
     uint32_t ma_bits[NC], mr_bits[NC];
+    double sum_a[NC], sum_r[NC];
 #pragma unroll
     for (int g = 0; g < NC; ++g) {
         ma_bits[g] = __builtin_bit_cast(uint32_t, acc[g].max_abs);
         mr_bits[g] = __builtin_bit_cast(uint32_t, acc[g].max_rel);
+        sum_a[g] = acc[g].sum_abs;
+        sum_r[g] = acc[g].sum_rel;
     }
-#define EVO_STEP(CTRL_, MASK_)                                          \
-    _Pragma("unroll") for (int g = 0; g < NC; ++g) {                    \
-        reduce_step<CTRL_, MASK_>(ma_bits[g], acc[g].sum_abs);          \
-        reduce_step<CTRL_, MASK_>(mr_bits[g], acc[g].sum_rel);          \
-    }
-    EVO_WAVE_REDUCE(EVO_STEP);
-#undef EVO_STEP
-    {
-#pragma unroll
-        for (int g = 0; g < NC; ++g) {
-            Partial p;
-            p.n_mismatch = 0;   // counted in xacc
-            p.n_excluded = 0;
-            p.sum_abs = last_lane_f64(acc[g].sum_abs);
-            p.sum_rel = last_lane_f64(acc[g].sum_rel);
-            p.max_abs = last_lane_f32(ma_bits[g]);
-            p.max_rel = last_lane_f32(mr_bits[g]);
-            p.flags = 0;
-            p.pad = 0;
-            if (lane == 0) wpart[g] = p;
-        }
-    }
+    reduce_group_to_rows<NC>(ma_bits, mr_bits, sum_a, sum_r, lane, 0u, wpart);
     return any_redo;
 }
 
@@ -1181,6 +1262,8 @@ __device__ __forceinline__ uint32_t fast_tiles_wide(const char *rptr, uint64_t c
     // Lanes -> wavefront, as in fast_tiles.  Integer maxima become binary32 values first
     // (rounded to nearest even: monotone, so the order of rounding and maximum is free).
     uint32_t ma_bits[NC], mr_bits[NC];
+    double sum_a[NC], sum_r[NC];
+    uint32_t my_mismatches = 0;   // the count of the candidate this lane will write the row of
 #pragma unroll
     for (int g = 0; g < NC; ++g) {
         ma_bits[g] = __builtin_bit_cast(uint32_t, acc[g].max_abs);
@@ -1191,27 +1274,11 @@ __device__ __forceinline__ uint32_t fast_tiles_wide(const char *rptr, uint64_t c
             ma_bits[g] = __builtin_bit_cast(uint32_t, (float)u64_of(ma_bits[g], mr_bits[g]));
             mr_bits[g] = 0;
         }
+        sum_a[g] = acc[g].sum_abs;
+        sum_r[g] = acc[g].sum_rel;
+        my_mismatches = group_candidate_of_lane<NC>(lane) == g ? n_mismatch[g] : my_mismatches;
     }
-#define EVO_STEP(CTRL_, MASK_)                                          \
-    _Pragma("unroll") for (int g = 0; g < NC; ++g) {                    \
-        reduce_step<CTRL_, MASK_>(ma_bits[g], acc[g].sum_abs);          \
-        reduce_step<CTRL_, MASK_>(mr_bits[g], acc[g].sum_rel);          \
-    }
-    EVO_WAVE_REDUCE(EVO_STEP);
-#undef EVO_STEP
-#pragma unroll
-    for (int g = 0; g < NC; ++g) {
-        Partial p;
-        p.n_mismatch = n_mismatch[g];
-        p.n_excluded = 0;
-        p.sum_abs = last_lane_f64(acc[g].sum_abs);
-        p.sum_rel = last_lane_f64(acc[g].sum_rel);
-        p.max_abs = last_lane_f32(ma_bits[g]);
-        p.max_rel = last_lane_f32(mr_bits[g]);
-        p.flags = 0;
-        p.pad = 0;
-        if (lane == 0) wpart[g] = p;
-    }
+    reduce_group_to_rows<NC>(ma_bits, mr_bits, sum_a, sum_r, lane, my_mismatches, wpart);
     return any_redo;
 }
 
