@@ -107,3 +107,46 @@ def test_config7_full(gu, name):
     want, pop = _full(gu, w, "C7-" + name)
     assert [r["valid"] for r in want] == [0 if (p % 4) == 3 else 1 for p in range(16)]
     assert int(pop["n_valid"]) == 12
+
+
+@pytest.mark.timeout(600)
+def test_more_than_two_to_the_32_elements(gu):
+    """Element indices beyond 32 bits: 2^32 + 12345 bf16 elements per tensor (8.6 GB each), two
+    candidates, with the differences that matter placed behind element 2^32 -- a far value, a
+    NaN in the very last element, an Inf in the ragged last tile -- and one just before it.
+    Every row against the CPU oracle, fed chunk by chunk; n_elems needs its high word."""
+    free, _ = torch.cuda.mem_get_info()
+    n = (1 << 32) + 12345
+    if free < 4 * 2 * n:
+        pytest.skip("needs 35 GB of free device memory")
+    t0 = time.time()
+    g = torch.Generator(device="cuda")
+    g.manual_seed(0x5EED2032)
+    ref = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    step = 1 << 28
+    for lo in range(0, n, step):                       # piecewise: no fp32 temporary of the whole tensor
+        hi = min(n, lo + step)
+        ref[lo:hi] = (torch.randn(hi - lo, generator=g, device="cuda") + 2).to(torch.bfloat16)
+    near = ref.clone()
+    for lo in range(0, n, step):
+        hi = min(n, lo + step)
+        near[lo:hi] = (near[lo:hi].float() * 1.003).to(torch.bfloat16)
+    edge = ref.clone()
+    edge[(1 << 32) - 1] = 50.0
+    edge[(1 << 32) + 5] = -50.0
+    edge[n - 1] = float("nan")
+    edge[n - 300] = float("inf")
+    _say("2^32+: tensors generated (%.1f s)" % (time.time() - t0))
+    seg = synth.Segment(ref, [near, edge], (n,), [True, False])
+    w = synth.Workload("beyond-2^32-bf16-P2", [seg], 1e-2, 1e-2, 1 + torch.rand(2, 8, device="cuda"),
+                       1 + torch.rand(8, device="cuda"))
+    chk, stats, want = gu.check_parity(w, oracle_threads=2, label="2^32+")
+    _say("2^32+: rows agree (%.1f s)" % (time.time() - t0))
+    assert want[0]["valid"] == 1 and want[0]["n_finite"] == n
+    assert want[1]["n_mismatch"] == 4 and want[1]["n_finite"] == n - 2
+    from paper_2510_03760_amd.binding import stats_to_numpy
+    got = stats_to_numpy(stats)
+    assert int(got[0]["n_elems_hi"]) == 1 and int(got[0]["n_elems_lo"]) == 12345
+    chk.close()
+    del ref, near, edge, seg, w
+    torch.cuda.empty_cache()
