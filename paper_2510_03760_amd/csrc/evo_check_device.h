@@ -838,6 +838,20 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, const uint64_t 
                 }
             }
 
+            // PADDED: the pointer that candidate g's refill starts from -- candidate g + D of this
+            // tile or, behind the last real ones, candidate g % D of the next.  (The table's
+            // address through an opaque copy: the NC addresses formed from it do not depend
+            // on the tile, and kept in registers across the whole loop they are what tips the
+            // 16-bit kernels into spilling.)
+            auto padded_refill_ptr = [&](int g) -> uint64_t {
+                uint32_t table_here = table_addr;
+                asm volatile("" : "+v"(table_here));
+                lds_u64 *table = (lds_u64 *)(uintptr_t)table_here;
+                return table[(uint32_t)(g + D) < n_real ? (uint32_t)(g + D) : (uint32_t)(g % D)];
+            };
+            uint64_t ptr_ahead = 0;
+            if constexpr (PADDED) ptr_ahead = padded_refill_ptr(0);
+
             uint32_t redo_mask = 0;
 #pragma unroll
             for (int g = 0; g < NC; ++g) {
@@ -867,16 +881,14 @@ __device__ __forceinline__ uint32_t fast_tiles(const char *rptr, const uint64_t 
                     // each tile's first candidates a full memory latency away (5 candidates
                     // ran at 0.68-0.72 of peak where 4 and 8 reach 0.79).
                     const bool same_tile = (uint32_t)(g + D) < n_real;
-                    // (the table's address through an opaque copy: the NC addresses formed from
-                    // it do not depend on the tile, and kept in registers across the whole
-                    // loop they are what tips the 16-bit kernels into spilling)
-                    uint32_t table_here = table_addr;
-                    asm volatile("" : "+v"(table_here));
-                    lds_u64 *table = (lds_u64 *)(uintptr_t)table_here;
-                    const uint64_t base = table[same_tile ? (uint32_t)(g + D) : (uint32_t)(g % D)] +
-                                          (same_tile ? voff : voff_next);
+                    const uint64_t base = ptr_ahead + (same_tile ? voff : voff_next);
 #pragma unroll
                     for (int j = 0; j < kNV; ++j) buf[u][g % D][j] = load16_at<true>(base + j * 1024);
+                    // the pointer the NEXT candidate's refill starts from, fetched a candidate
+                    // ahead: which one it is depends on n_real, so its LDS read cannot be
+                    // placed early by the compiler as in the plain loop, and issued where it
+                    // is needed it held every refill back by an LDS round trip
+                    if (g + 1 < NC) ptr_ahead = padded_refill_ptr(g + 1);
                 }
                 if (!real) continue;
 #pragma unroll
