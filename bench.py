@@ -282,8 +282,9 @@ def sweep(mode: str, steps: int) -> int:
 
 def measure(name: str, steps: int, warmup: int, spinup_ms: float, split: bool):
     """Builds workload `name`, spins the device up, runs `warmup` untimed and `steps` timed steps
-    and returns (result fields, workload, checker, stats, summary).  One event per launch
-    boundary on the launch stream times every launch of the dominant kernel."""
+    and returns (result fields, workload, checker, stats, summary).  Two events on the launch
+    stream, one before and one behind the K launches, give the dominant kernel's average launch
+    duration (see the timed region below)."""
     import torch
     import paper_2510_03760_amd as evo
     from paper_2510_03760_amd.binding import stats_to_numpy, summary_to_numpy
@@ -375,25 +376,45 @@ def measure(name: str, steps: int, warmup: int, spinup_ms: float, split: bool):
     torch.cuda.Event(enable_timing=True).record(stream)
     torch.cuda.synchronize()
 
-    # One event between consecutive steps (plus one inside a step when it is two launches):
-    # enough to time every launch of the dominant kernel on its stream, and no more than
-    # that inside the timed region.
-    bounds = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    # The timed region.  One launch per step (the fused entry points): one event before the K
+    # steps and one after them, on the launch stream -- the kernel's average launch duration is
+    # the time between the two over K, launch gaps included.  An event between every two
+    # launches would cost 2.8-3.0 us per launch by itself (measured: 2^26 x 16 fp32 677.4 against
+    # 674.4 us per launch, 2^24 x 64 bf16 345.8 / 343.0), which is the measurement's, not the
+    # path's.  Two launches per step (--split): one event per launch boundary, since the two
+    # kernels have to be told apart.
+    bounds = [torch.cuda.Event(enable_timing=True) for _ in range(2 if fused else steps + 1)]
     mids = [None if fused else torch.cuda.Event(enable_timing=True) for _ in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     bounds[0].record(stream)
     for k in range(steps):
         step(mids[k])
-        bounds[k + 1].record(stream)
+        if not fused:
+            bounds[k + 1].record(stream)
+    if fused:
+        bounds[1].record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    gc.enable()
 
     ms_per_step = wall * 1e3 / steps
-    check_ms = sorted(bounds[k].elapsed_time(bounds[k + 1] if fused else mids[k]) for k in range(steps))
-    fit_ms = [0.0] if fused else sorted(mids[k].elapsed_time(bounds[k + 1]) for k in range(steps))
-    check_avg = sum(check_ms) / len(check_ms)
+    if fused:
+        check_avg = bounds[0].elapsed_time(bounds[1]) / steps
+        # the spread of single launches, from a pass of its own behind the timed region (one
+        # event per launch boundary, so each figure carries that event's 3 us)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        marks[0].record(stream)
+        for k in range(steps):
+            step()
+            marks[k + 1].record(stream)
+        torch.cuda.synchronize()
+        check_ms = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(steps))
+        fit_ms = [0.0]
+    else:
+        check_ms = sorted(bounds[k].elapsed_time(mids[k]) for k in range(steps))
+        fit_ms = sorted(mids[k].elapsed_time(bounds[k + 1]) for k in range(steps))
+        check_avg = sum(check_ms) / len(check_ms)
+    gc.enable()
     alg_bytes = w.algorithmic_bytes
     achieved = alg_bytes / (check_avg * 1e-3) / 1e9
 
@@ -412,7 +433,9 @@ def measure(name: str, steps: int, warmup: int, spinup_ms: float, split: bool):
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
                      "kernel": "evo_evaluate_kernel" if fused else "evo_check_kernel", "avg_ms": check_avg,
-                     "median_ms": check_ms[len(check_ms) // 2], "min_ms": check_ms[0]},
+                     "how": ("events around the K timed launches" if fused else "one event per launch boundary"),
+                     "median_ms": check_ms[len(check_ms) // 2], "min_ms": check_ms[0],
+                     "single_launches": ("separate pass, one event per launch" if fused else "timed region")},
         "fitness_kernel_us": None if fused else {"avg": 1e3 * sum(fit_ms) / len(fit_ms),
                                                  "median": 1e3 * fit_ms[len(fit_ms) // 2]},
         "hbm_gbps_whole_step": alg_bytes / (wall / steps) / 1e9,
